@@ -1,0 +1,266 @@
+"""Pins for the oracle's attention functions (section 3 Eq. 5; section 4.3 Eq. 10; Algorithm 1;
+appendix A.2) — CPU only.  Degenerate cases that reduce to textbook attention, closed forms, a
+literal end-of-prompt transcription of Algorithm 1, a brute-force set-builder re-derivation and
+the equivalence of absorbed and explicitly up-projected MLA.
+"""
+import numpy as np
+import pytest
+from scipy.special import softmax
+
+
+def _problem(o, seed, B=1, L=40, H=4, S=2, d_pool=5, d_sel=3, g=4, w=6, mode=0, scale=0.6, bias=0.0):
+    rng = np.random.default_rng(seed)
+    d = o.Desc(B=B, L=L, H=H, S=S, d_pool=d_pool, d_sel=d_sel, g=g, w=w, mode=mode, scale=scale, rep_logit_bias=bias)
+    POOL = rng.standard_normal((B, L, d_pool) if mode == 0 else (B, L, S, d_pool))
+    SEL = rng.standard_normal((B, L, d_sel) if mode == 0 else (B, L, S, d_sel))
+    Q = rng.standard_normal((B, L, H, d.d_qk))
+    return d, Q, POOL, SEL
+
+
+def _condense(o, d, Q, POOL, SEL):
+    return o.condense(d, o.summary_query(d, Q[:, d.L - d.nq:]), POOL, SEL)
+
+
+def _all_rows(d):
+    return np.arange(d.L, dtype=np.int32)
+
+
+def _kv_of(d, POOL, SEL, b, s):
+    """keys [L, d_qk], values [L, d_v] of set s."""
+    if d.mode == 0:
+        return np.concatenate([POOL[b], SEL[b]], -1), POOL[b]
+    return SEL[b, :, s], POOL[b, :, s]
+
+
+def _numpy_dense(d, Q, POOL, SEL):
+    O = np.zeros((d.B, d.L, d.H, d.d_v))
+    for b in range(d.B):
+        for h in range(d.H):
+            K, V = _kv_of(d, POOL, SEL, b, h // (d.H // d.S))
+            logits = d.scale * Q[b, :, h] @ K.T
+            logits[np.triu_indices(d.L, 1)] = -np.inf
+            O[b, :, h] = softmax(logits, axis=-1) @ V
+    return O
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_dense_equals_textbook_softmax_matmul(oracle, mode):
+    d, Q, POOL, SEL = _problem(oracle, 1, B=2, mode=mode)
+    O, lse = oracle.dense_attn_rows(d, _all_rows(d), Q, POOL, SEL, want_lse=True)
+    np.testing.assert_allclose(O, _numpy_dense(d, Q, POOL, SEL), atol=1e-12)
+    K, _ = _kv_of(d, POOL, SEL, 1, 1)
+    t = 17
+    ref = np.log(np.exp(d.scale * K[: t + 1] @ Q[1, t, d.H // d.S]).sum())
+    np.testing.assert_allclose(lse[1, t, d.H // d.S], ref, atol=1e-12)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("w", [0, 1, 7, 64])
+def test_group_size_one_is_dense_attention(oracle, mode, w):
+    # one-token groups: alpha = 1, c^rep = c_i, anchor = i, so every row sees every token once
+    d, Q, POOL, SEL = _problem(oracle, 2, g=1, w=w, mode=mode)
+    c = _condense(oracle, d, Q, POOL, SEL)
+    O = oracle.lca_attn_rows(d, _all_rows(d), Q, POOL, SEL, c["pool_rep"], c["sel_rep"])
+    np.testing.assert_allclose(O, oracle.dense_attn_rows(d, _all_rows(d), Q, POOL, SEL), atol=1e-12)
+
+
+@pytest.mark.parametrize("L,w,g", [(40, 40, 4), (40, 100, 4), (10, 8, 4)])
+def test_short_sequence_falls_back_to_dense(oracle, L, w, g):
+    # section 4.3: L < w + g -> standard attention
+    d, Q, POOL, SEL = _problem(oracle, 3, L=L, w=w, g=g)
+    assert d.m == 0
+    c = _condense(oracle, d, Q, POOL, SEL)
+    O = oracle.lca_attn_rows(d, _all_rows(d), Q, POOL, SEL, c["pool_rep"], c["sel_rep"])
+    np.testing.assert_allclose(O, oracle.dense_attn_rows(d, _all_rows(d), Q, POOL, SEL), atol=1e-13)
+
+
+def _entries(t, L, w, g):
+    """E_t by set-builder: groups wholly inside the distant history {0..t-w}, raw tokens after them."""
+    history = {i for i in range(t + 1) if i <= t - w}
+    reps = [j for j in range(L // g + 1) if all(i in history for i in range(j * g, (j + 1) * g))]
+    covered = {i for j in reps for i in range(j * g, (j + 1) * g)}
+    raw = [i for i in range(t + 1) if i not in covered]
+    return reps, raw
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("L,g,w", [(32, 4, 5), (29, 2, 0), (32, 4, 2), (31, 8, 3), (24, 4, 4)])
+def test_lca_rows_match_brute_force_set_builder(oracle, mode, L, g, w):
+    d, Q, POOL, SEL = _problem(oracle, 4 + L + g + w, B=2, L=L, g=g, w=w, mode=mode, d_pool=4, d_sel=3)
+    c = _condense(oracle, d, Q, POOL, SEL)
+    O, lse = oracle.lca_attn_rows(d, _all_rows(d), Q, POOL, SEL, c["pool_rep"], c["sel_rep"], want_lse=True)
+    for b in range(d.B):
+        for h in range(d.H):
+            s = h // (d.H // d.S)
+            K, V = _kv_of(d, POOL, SEL, b, s)
+            Krep = np.concatenate([c["pool_rep"][b, s], c["sel_rep"][b, s]], -1) if mode == 0 else c["sel_rep"][b, s]
+            Vrep = c["pool_rep"][b, s]
+            for t in range(L):
+                reps, raw = _entries(t, L, w, g)
+                assert all(j < d.m for j in reps)
+                keys = np.concatenate([Krep[reps], K[raw]])
+                vals = np.concatenate([Vrep[reps], V[raw]])
+                p = softmax(d.scale * keys @ Q[b, t, h])
+                np.testing.assert_allclose(O[b, t, h], p @ vals, atol=1e-12)
+                np.testing.assert_allclose(lse[b, t, h], np.log(np.exp(d.scale * keys @ Q[b, t, h]).sum()), atol=1e-12)
+
+
+def test_last_row_is_algorithm_1(oracle):
+    """Algorithm 1 written out for the end of the prompt: K^fused = [K^rep ; K^loc], one softmax."""
+    d, Q, POOL, SEL = _problem(oracle, 5, L=53, g=4, w=7, H=2, S=1)
+    g, w, L = d.g, d.w, d.L
+    qbar = Q[0, L - g:].mean(axis=(0, 1))
+    m = (L - w) // g
+    keys = np.concatenate([POOL[0], SEL[0]], -1)
+    c_rep, k_rep = [], []
+    for j in range(m):
+        G = np.arange(j * g, (j + 1) * g)
+        a = softmax(d.scale * keys[G] @ qbar)
+        c_rep.append(a @ POOL[0, G])
+        k_rep.append(SEL[0, G[np.argmax(a)]])
+    k = w + (L - w) % g
+    K_fused = np.concatenate([np.concatenate([np.array(c_rep), np.array(k_rep)], -1), keys[L - k:]])
+    V_fused = np.concatenate([np.array(c_rep), POOL[0, L - k:]])
+    c = _condense(oracle, d, Q, POOL, SEL)
+    O = oracle.lca_attn_rows(d, [L - 1], Q[:, L - 1:], POOL, SEL, c["pool_rep"], c["sel_rep"])
+    for h in range(d.H):
+        np.testing.assert_allclose(O[0, 0, h], softmax(d.scale * K_fused @ Q[0, L - 1, h]) @ V_fused, atol=1e-12)
+
+
+def test_zero_queries_give_plain_averages_and_entry_counts(oracle):
+    d, Q, POOL, SEL = _problem(oracle, 6, L=64, g=4, w=8, H=2, S=2)
+    c = _condense(oracle, d, Q, POOL, SEL)
+    O, lse = oracle.lca_attn_rows(d, _all_rows(d), np.zeros_like(Q), POOL, SEL, c["pool_rep"], c["sel_rep"], want_lse=True)
+    for t in range(d.L):
+        mt = max(0, (t + 1 - d.w) // d.g)
+        n = mt + t + 1 - mt * d.g
+        np.testing.assert_allclose(lse[0, t], np.log(n), atol=1e-13)       # softmax over |E_t| equal logits
+        for h in range(d.H):
+            ref = (c["pool_rep"][0, h, :mt].sum(0) + POOL[0, mt * d.g: t + 1].sum(0)) / n
+            np.testing.assert_allclose(O[0, t, h], ref, atol=1e-13)
+
+
+def test_visible_pair_count_of_the_tiny_configuration(oracle):
+    # L = 1024, g = 16, w = 128: sum_t |E_t| = 154 360 (query, key) pairs per head, through exp(lse) at q = 0
+    d = oracle.Desc(B=1, L=1024, H=1, S=1, d_pool=1, d_sel=1, g=16, w=128)
+    z = np.zeros((1, 1024, 1))
+    c = oracle.condense(d, np.zeros((1, 1, 2)), z, z)
+    _, lse = oracle.lca_attn_rows(d, _all_rows(d), np.zeros((1, 1024, 1, 2)), z, z, c["pool_rep"], c["sel_rep"], want_lse=True)
+    assert int(round(float(np.exp(lse).sum()))) == 154360
+    t = np.arange(1024)
+    mt = np.maximum(0, (t + 1 - 128) // 16)
+    assert int((mt + t + 1 - mt * 16).sum()) == 154360
+
+
+def test_rep_logit_bias_ln_g_counts_each_representative_g_times(oracle):
+    d, Q, POOL, SEL = _problem(oracle, 7, L=48, g=4, w=4, bias=np.log(4.0))
+    c = _condense(oracle, d, Q, POOL, SEL)
+    _, lse = oracle.lca_attn_rows(d, _all_rows(d), np.zeros_like(Q), POOL, SEL, c["pool_rep"], c["sel_rep"], want_lse=True)
+    np.testing.assert_allclose(np.exp(lse[0, :, 0]), np.arange(1, d.L + 1), atol=1e-9)   # every token counted once
+
+
+def test_absorbed_form_equals_explicit_up_projection(oracle):
+    """Section 3, Eq. 2-5 and Algorithm 1's representative construction: attention in head space with
+    K^h = [C W^UK_h, K^R], V^h = C W^UV_h equals the latent-space output times W^UV_h when the query
+    is q~ = [W^UK_h q^nope ; q^R].  Holds for dense MLA and for LCA (the representatives are
+    up-projected with the same matrices)."""
+    rng = np.random.default_rng(8)
+    L, H, d_c, d_r, dk, dv, g, w = 36, 3, 16, 4, 8, 8, 4, 5
+    C, KR = rng.standard_normal((1, L, d_c)), rng.standard_normal((1, L, d_r))
+    WUK, WUV = rng.standard_normal((H, d_c, dk)), rng.standard_normal((H, d_c, dv))
+    q_nope, q_rope = rng.standard_normal((L, H, dk)), rng.standard_normal((L, H, d_r))
+    scale = 1.0 / np.sqrt(dk + d_r)
+    Qabs = np.concatenate([np.einsum("hck,lhk->lhc", WUK, q_nope), q_rope], -1)[None]
+    d = oracle.Desc(B=1, L=L, H=H, S=H, d_pool=d_c, d_sel=d_r, g=g, w=w, scale=scale)
+    rows = _all_rows(d)
+    c = _condense(oracle, d, Qabs, C, KR)
+    O_lca = oracle.lca_attn_rows(d, rows, Qabs, C, KR, c["pool_rep"], c["sel_rep"])
+    O_dense = oracle.dense_attn_rows(d, rows, Qabs, C, KR)
+    for h in range(H):
+        Kh = np.concatenate([C[0] @ WUK[h], KR[0]], -1)
+        Vh = C[0] @ WUV[h]
+        qh = np.concatenate([q_nope[:, h], q_rope[:, h]], -1)
+        logits = scale * qh @ Kh.T
+        logits[np.triu_indices(L, 1)] = -np.inf
+        np.testing.assert_allclose(O_dense[0, :, h] @ WUV[h], softmax(logits, -1) @ Vh, atol=1e-10)
+        # LCA in head space: representatives built per Algorithm 1 from the oracle's c^rep and anchors
+        Krep = np.concatenate([c["pool_rep"][0, h] @ WUK[h], KR[0, c["anchor"][0, h]]], -1)
+        Vrep = c["pool_rep"][0, h] @ WUV[h]
+        for t in range(L):
+            mt = max(0, (t + 1 - w) // g)
+            keys = np.concatenate([Krep[:mt], Kh[mt * g: t + 1]])
+            vals = np.concatenate([Vrep[:mt], Vh[mt * g: t + 1]])
+            np.testing.assert_allclose(O_lca[0, t, h] @ WUV[h], softmax(scale * keys @ qh[t]) @ vals, atol=1e-10)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_decode_step_equals_last_prefill_row(oracle, mode):
+    d, Q, POOL, SEL = _problem(oracle, 9, B=2, L=45, g=4, w=6, mode=mode)
+    c = _condense(oracle, d, Q, POOL, SEL)
+    last = oracle.lca_attn_rows(d, [d.L - 1], Q[:, d.L - 1:], POOL, SEL, c["pool_rep"], c["sel_rep"])[:, 0]
+    tail = slice(d.m * d.g, d.L)
+    if mode == 0:
+        pt, st = POOL[:, None, tail], SEL[:, None, tail]
+    else:
+        pt, st = POOL[:, tail].transpose(0, 2, 1, 3), SEL[:, tail].transpose(0, 2, 1, 3)
+    O = oracle.decode_attn(d, Q[:, d.L - 1], c["pool_rep"], c["sel_rep"], pt, st)
+    np.testing.assert_allclose(O, last, atol=1e-13)
+
+
+def _theorem_terms(d, q, K, V, Krep, Vrep, t):
+    """Q, V, delta_k, delta_v of the uniform error bound for row t, measured in the absorbed space."""
+    mt = max(0, (t + 1 - d.w) // d.g)
+    dk = dv = 0.0
+    for j in range(mt):
+        G = slice(j * d.g, (j + 1) * d.g)
+        dk = max(dk, np.linalg.norm(K[G] - Krep[j], axis=-1).max())
+        dv = max(dv, np.linalg.norm(V[G] - Vrep[j], axis=-1).max())
+    return np.linalg.norm(q), np.linalg.norm(V[: t + 1], axis=-1).max(), dk, dv
+
+
+def test_uniform_error_bound_holds_for_the_multiplicity_weighted_variant(oracle):
+    """Theorem 1 / appendix A.2: with every representative standing for its g tokens in the
+    normaliser (rep_logit_bias = ln g, the Z' of the proof), ||Attn_t - Attn_t^LCA||_2 <=
+    V (exp(2 Q delta_k scale) - 1) + delta_v on every row."""
+    rng = np.random.default_rng(10)
+    L, g, w = 96, 4, 8
+    d = oracle.Desc(B=1, L=L, H=2, S=1, d_pool=6, d_sel=2, g=g, w=w, scale=0.35, rep_logit_bias=np.log(g))
+    base = np.cumsum(0.05 * rng.standard_normal((1, L, 6)), axis=1) + rng.standard_normal((1, 1, 6))
+    POOL, SEL = base, 0.3 * rng.standard_normal((1, L, 2))
+    Q = 0.5 * rng.standard_normal((1, L, 2, 8))
+    c = _condense(oracle, d, Q, POOL, SEL)
+    rows = _all_rows(d)
+    err = np.linalg.norm(oracle.dense_attn_rows(d, rows, Q, POOL, SEL)
+                         - oracle.lca_attn_rows(d, rows, Q, POOL, SEL, c["pool_rep"], c["sel_rep"]), axis=-1)
+    K = np.concatenate([POOL[0], SEL[0]], -1)
+    Krep = np.concatenate([c["pool_rep"][0, 0], c["sel_rep"][0, 0]], -1)
+    checked = 0
+    for t in range(L):
+        for h in range(2):
+            Qn, Vn, dk, dv = _theorem_terms(d, Q[0, t, h], K, POOL[0], Krep, c["pool_rep"][0, 0], t)
+            bound = Vn * (np.exp(2 * Qn * dk * d.scale) - 1) + dv
+            assert err[0, t, h] <= bound + 1e-12
+            checked += err[0, t, h] > 0
+    assert checked > 100          # the inequality was exercised on rows that do see representatives
+
+
+def test_error_against_dense_does_not_grow_with_length(oracle):
+    """Empirical companion of Theorem 1 for the method as stated (bias 0): the last-row error vs dense
+    attention, averaged over seeds, stays flat as L grows (same input distribution)."""
+    from paper_2604_12452_amd import inputs
+    errs = {}
+    for L in (512, 2048, 8192):
+        e = []
+        for seed in range(12):
+            wl = inputs.Workload("len", B=1, L=L, H=2, S=1, d_pool=32, d_sel=8, g=16, w=128, dtype="f32", seed=seed)
+            POOL, SEL = inputs.gen_kv(wl, 0)
+            POOL, SEL = POOL[None].astype(np.float64), SEL[None].astype(np.float64)
+            qt = inputs.gen_q_rows(wl, 0, L - wl.g, L)[None].astype(np.float64)
+            d = oracle.Desc(B=1, L=L, H=2, S=1, d_pool=32, d_sel=8, g=16, w=128)
+            c = oracle.condense(d, oracle.summary_query(d, qt), POOL, SEL)
+            a = oracle.lca_attn_rows(d, [L - 1], qt[:, -1:], POOL, SEL, c["pool_rep"], c["sel_rep"])
+            b = oracle.dense_attn_rows(d, [L - 1], qt[:, -1:], POOL, SEL)
+            e.append(np.linalg.norm(a - b, axis=-1).mean())
+        errs[L] = float(np.mean(e))
+    assert errs[8192] <= 1.5 * errs[512], errs
+    assert errs[2048] <= 1.5 * errs[512], errs
