@@ -1,0 +1,130 @@
+/*
+ * liblca — Latent-Condensed Attention (LCA) hot path for AMD MI355X (gfx950), C ABI.
+ *
+ * Notation follows the paper: L tokens, group size g, local window w, m = floor((L - w) / g)
+ * groups (0 when L <= w), k = L - m*g raw tokens (section 4.2; Algorithm 1).  Indices are 0-based:
+ * group j covers tokens [j*g, (j+1)*g).
+ *
+ * Modes
+ *   LCA_MODE_MLA  POOL = C^KV [B, L, d_pool], SEL = K^R [B, L, d_sel], shared by all heads.  Absorbed
+ *                 form (section 3, Eq. 2-5 with W^UK, W^UV folded away): key_i = [c_i ; k^R_i],
+ *                 d_qk = d_pool + d_sel, value_i = c_i, d_v = d_pool.
+ *   LCA_MODE_GQA  POOL = V, SEL = K, both [B, L, S, d] with one condensed set per KV head
+ *                 (section 5.4: max-selection on keys, weighted pooling on values); d_qk = d_sel,
+ *                 d_v = d_pool.
+ * Condensed sets: S per sequence, query head h uses set h / (H / S).  S = 1 (MLA) or S = KV heads
+ * (GQA) reproduces the cache sizes the paper reports; S = H condenses per query head.
+ *
+ * Conventions for every entry point
+ *   - All tensor arguments are DEVICE pointers, row-major, last dimension contiguous, 16-byte
+ *     aligned; `desc` and size outputs are HOST pointers.  Element type is desc->dtype for Q, POOL,
+ *     SEL, the representatives and O; anchor indices are int32; lse and alpha_dbg are float.
+ *   - The caller owns every buffer, including the workspace (size from lca_workspace_size).  The
+ *     library allocates nothing, keeps no state between calls and never synchronises: work is
+ *     enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream) and outputs are
+ *     valid once the caller has synchronised that stream.
+ *   - Every call returns an lca_status.  On any status other than LCA_OK nothing was launched and no
+ *     output was touched, except LCA_ERR_HIP, which reports a launch failure from the HIP runtime.
+ *     lca_last_error() gives a thread-local message for the last non-OK status.
+ *   - Invalid: NULL required pointer; B, L, H, S, g <= 0; w < 0; H % S != 0; n_q > L; a dtype or
+ *     mode outside the enums; d_pool / d_sel not multiples of 8 (bf16) or 4 (f32) or above 1024;
+ *     g > 64; workspace too small (LCA_ERR_WORKSPACE).  m = 0 (L < w + g) is valid: lca_condense
+ *     writes nothing and lca_prefill_attn equals dense attention (section 4.3, fallback remark).
+ */
+#ifndef LCA_H
+#define LCA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LCA_OK = 0,
+    LCA_ERR_INVALID_ARG = 1,
+    LCA_ERR_UNSUPPORTED = 2,
+    LCA_ERR_WORKSPACE = 3,
+    LCA_ERR_HIP = 4
+} lca_status;
+
+typedef enum { LCA_MODE_MLA = 0, LCA_MODE_GQA = 1 } lca_mode;
+typedef enum { LCA_BF16 = 0, LCA_F32 = 1 } lca_dtype;
+
+typedef struct {
+    int32_t B, L, H, S;     /* batch, tokens, query heads, condensed sets (H % S == 0)            */
+    int32_t d_pool, d_sel;  /* widths of the pooled and of the selected component                  */
+    int32_t g, w, n_q;      /* group size, local window, number of summary queries (0 means g)     */
+    int32_t mode, dtype;    /* lca_mode, lca_dtype                                                 */
+    float scale;            /* multiplies q.k in the importance score and in the attention logits  */
+    float rep_logit_bias;   /* added to representatives' logits: 0 = Algorithm 1; ln(g) = each
+                               representative counted g times, the normaliser used in appendix A.2 */
+} lca_desc;
+
+/* Bytes of workspace that any call below needs for this descriptor (host only, launches nothing). */
+lca_status lca_workspace_size(const lca_desc *desc, size_t *bytes);
+
+/*
+ * KV-cache footprint of one layer (section 4.3, decoding paragraph; appendix B): dense = one
+ * (pool, sel) row per token and KV head; condensed = S*m representatives plus k raw tail rows per
+ * KV head.  Host only.
+ */
+lca_status lca_cache_bytes(const lca_desc *desc, size_t *dense_bytes, size_t *condensed_bytes);
+
+/*
+ * Latent-space condensation (section 4.2; Algorithm 1, first step and loop over groups).
+ *   summary query  qbar[b,s,:] = mean of Q[b, L-n_q .. L-1, heads of set s, :]
+ *   score          s_i = scale * <qbar, key_i>,  alpha = softmax of s inside each group   (Eq. 6)
+ *   pool_rep[b,s,j,:] = sum_i alpha_i * POOL_i                                             (Eq. 7)
+ *   anchor_idx[b,s,j] = lowest token index attaining max s_i, sel_rep[b,s,j,:] = SEL row of it (Eq. 8)
+ * In:  Q [B,L,H,d_qk], POOL, SEL (layouts above).
+ * Out: pool_rep [B,S,m,d_pool], sel_rep [B,S,m,d_sel] (dtype of the inputs, pooled values rounded
+ *      to nearest-even once on store), anchor_idx [B,S,m] (absolute token index),
+ *      alpha_dbg [B,S,m*g] float, may be NULL.  With m = 0 nothing is written.
+ */
+lca_status lca_condense(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL,
+                        void *pool_rep, void *sel_rep, int32_t *anchor_idx, float *alpha_dbg,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Prefill attention over the condensed context (section 4.3, Eq. 10; Algorithm 1, last steps;
+ * appendix A.2 notation for a query at position t).  Row t of head h (set s) attends
+ *   representatives j < m_t,  m_t = max(0, floor((t + 1 - w) / g)),  and raw tokens m_t*g <= i <= t,
+ * with one softmax over both; logits scale*<q, key> (+ rep_logit_bias on representatives); the
+ * output is the probability-weighted sum of pool_rep rows and raw POOL rows (latent space for MLA).
+ * In:  Q [B,L,H,d_qk], POOL, SEL, pool_rep, sel_rep (as written by lca_condense).
+ * Out: O [B,L,H,d_pool]; lse [B,L,H] float (natural-log normaliser of the scaled logits), may be NULL.
+ */
+lca_status lca_prefill_attn(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL,
+                            const void *pool_rep, const void *sel_rep, void *O, float *lse,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Dense causal attention, the in-run baseline (section 3, Eq. 5; absorbed form for MLA): row t
+ * attends every token i <= t.  desc->g, w, n_q and rep_logit_bias are ignored.  Same layouts as
+ * lca_prefill_attn without the representatives.
+ */
+lca_status dense_mla_attn(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL,
+                          void *O, float *lse, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One decode step over a condensed cache (section 4.3, decoding paragraph).  desc->L is the number
+ * of tokens so far INCLUDING the new one, whose key/value the caller has appended to the raw tail;
+ * the library derives m = floor((L - w) / g) and the tail length k = L - m*g.  The new token's
+ * query attends the m representatives and the k tail rows.
+ * In:  q [B,H,d_qk]; pool_rep [B,S,m,d_pool], sel_rep [B,S,m,d_sel];
+ *      pool_tail [B,P,k,d_pool], sel_tail [B,P,k,d_sel] with P = 1 (MLA) or S (GQA).
+ * Out: O [B,H,d_pool].
+ */
+lca_status lca_decode_attn(const lca_desc *desc, const void *q, const void *pool_rep, const void *sel_rep,
+                           const void *pool_tail, const void *sel_tail, void *O,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Message for the calling thread's last non-OK status; never NULL. */
+const char *lca_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LCA_H */

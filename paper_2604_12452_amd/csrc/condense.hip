@@ -1,0 +1,368 @@
+// Latent-space condensation kernels (section 4.2 of the paper; Algorithm 1, first step and group loop).
+//
+//   summary_query_kernel   qbar = mean of the last n_q queries (and of the heads of a set)
+//   condense_reg_kernel    one wavefront per group, the group's rows held in registers; scores by
+//                          per-lane partial dots + a reduce-scatter butterfly, online softmax over
+//                          sub-blocks of <= 16 rows, pooling in-lane, anchor by (score, index) max.
+//                          HBM-bound: every C^KV / K^R byte is read once, as 16-byte coalesced loads.
+//   condense_generic_kernel  any sizes, scalar loads; fallback for shapes without an instantiation.
+//
+// gfx950 only (wave64).
+#include "lca_internal.h"
+
+namespace lca {
+namespace {
+
+constexpr int WAVE = 64;
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);   // round to nearest even (inputs are finite)
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Elt;
+template <> struct Elt<uint16_t> {      // bf16 bit patterns
+    static constexpr int EPC = 8;        // elements per 16-byte chunk
+    __device__ static float ld(const uint16_t *p) { return bf16_bits_to_float(*p); }
+    __device__ static void st(uint16_t *p, float v) { *p = float_to_bf16_bits(v); }
+    __device__ static void unpack(const uint4 &c, float *f)
+    {
+        const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+    __device__ static uint4 pack(const float *f)
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)float_to_bf16_bits(f[2 * i]) | ((uint32_t)float_to_bf16_bits(f[2 * i + 1]) << 16);
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+template <> struct Elt<float> {
+    static constexpr int EPC = 4;
+    __device__ static float ld(const float *p) { return *p; }
+    __device__ static void st(float *p, float v) { *p = v; }
+    __device__ static void unpack(const uint4 &c, float *f)
+    {
+        f[0] = __uint_as_float(c.x); f[1] = __uint_as_float(c.y); f[2] = __uint_as_float(c.z); f[3] = __uint_as_float(c.w);
+    }
+    __device__ static uint4 pack(const float *f)
+    {
+        return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Summary query: qbar[b,s,x] = mean over t in [L-n_q, L), h in set s of Q[b,t,h,x]   (fixed order)
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void summary_query_kernel(const T *__restrict__ Q, float *__restrict__ qbar, int L, int H, int S, int d_qk, int n_q)
+{
+    const int b = blockIdx.x / S, s = blockIdx.x % S, hps = H / S;
+    for (int x = threadIdx.x; x < d_qk; x += blockDim.x) {
+        float acc = 0.f;
+        for (int t = L - n_q; t < L; ++t)
+            for (int h = s * hps; h < (s + 1) * hps; ++h) acc += Elt<T>::ld(Q + (((size_t)b * L + t) * H + h) * d_qk + x);
+        qbar[(size_t)blockIdx.x * d_qk + x] = acc / (float)(n_q * hps);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// wave helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float readlane_f(float v, int lane)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// Sum R per-lane partial values across the wave so that lane l ends with the total of value
+// (l >> (6 - log2 R)).  log2(R) halving exchanges, then an all-reduce over the remaining lane bits.
+template <int R>
+__device__ __forceinline__ float wave_reduce_scatter(float (&v)[R], int lane)
+{
+    int mask = 32;
+#pragma unroll
+    for (int n = R; n > 1; n >>= 1, mask >>= 1) {
+        const bool hi = (lane & mask) != 0;
+#pragma unroll
+        for (int i = 0; i < n / 2; ++i) {
+            const float send = hi ? v[i] : v[i + n / 2];
+            const float keep = hi ? v[i + n / 2] : v[i];
+            v[i] = keep + __shfl_xor(send, mask, WAVE);
+        }
+    }
+    float x = v[0];
+    for (; mask >= 1; mask >>= 1) x += __shfl_xor(x, mask, WAVE);
+    return x;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Register-resident condensation: one wave per (sequence, KV source, group).
+// ---------------------------------------------------------------------------------------------
+template <typename T, int DP, int DS, int G, bool MLA>
+__global__ __launch_bounds__(256) void condense_reg_kernel(const T *__restrict__ POOL, const T *__restrict__ SEL,
+                                                           const float *__restrict__ qbar, T *__restrict__ pool_rep,
+                                                           T *__restrict__ sel_rep, int32_t *__restrict__ anchor,
+                                                           float *__restrict__ alpha_dbg, int B, int L, int S, int m, float scale)
+{
+    constexpr int EPC = Elt<T>::EPC;
+    constexpr int NCP = DP / EPC, NCS = DS / EPC, NC = NCP + NCS;
+    constexpr int NSLOT = (NC + WAVE - 1) / WAVE;
+    constexpr int R = G < 16 ? G : 16;          // rows per sub-block
+    constexpr int NSB = G / R;
+    constexpr int LOG2R = R == 16 ? 4 : R == 8 ? 3 : R == 4 ? 2 : R == 2 ? 1 : 0;
+    constexpr int SH = 6 - LOG2R;               // lane l holds the score of sub-block row l >> SH
+    constexpr int DQK = MLA ? DP + DS : DS;
+    static_assert(G % R == 0 && DP % EPC == 0 && DS % EPC == 0, "shape");
+
+    const int lane = threadIdx.x & (WAVE - 1);
+    const long wave_id = (long)blockIdx.x * (blockDim.x / WAVE) + (threadIdx.x / WAVE);
+    const int P = MLA ? 1 : S;                  // KV sources per sequence
+    const long n_units = (long)B * P * m;
+    if (wave_id >= n_units) return;             // whole wave leaves together
+    const int j = (int)(wave_id % m), p = (int)((wave_id / m) % P), b = (int)(wave_id / ((long)m * P));
+
+    const T *pool_base = POOL + ((size_t)b * L * P + p) * DP;   // row i at + i * P * DP
+    const T *sel_base = SEL + ((size_t)b * L * P + p) * DS;
+
+    // which 16-byte chunk of a row this lane owns in each slot
+    bool is_pool[NSLOT], is_sel[NSLOT];
+    int col[NSLOT];
+#pragma unroll
+    for (int sl = 0; sl < NSLOT; ++sl) {
+        const int c = sl * WAVE + lane;
+        is_pool[sl] = c < NCP;
+        is_sel[sl] = c >= NCP && c < NC;
+        col[sl] = is_pool[sl] ? c * EPC : (c - NCP) * EPC;
+    }
+
+    const int s_begin = MLA ? 0 : p, s_end = MLA ? S : p + 1;
+    for (int s = s_begin; s < s_end; ++s) {
+        // this lane's slice of the summary query
+        float qv[NSLOT][EPC];
+        const float *qb = qbar + ((size_t)b * S + s) * DQK;
+#pragma unroll
+        for (int sl = 0; sl < NSLOT; ++sl) {
+            const bool used = MLA ? (is_pool[sl] || is_sel[sl]) : is_sel[sl];
+            const int qoff = is_pool[sl] ? col[sl] : (MLA ? DP + col[sl] : col[sl]);
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) qv[sl][e] = used ? qb[qoff + e] : 0.f;
+        }
+
+        float m_run = -INFINITY, l_run = 0.f;
+        float acc[NSLOT][EPC];
+#pragma unroll
+        for (int sl = 0; sl < NSLOT; ++sl)
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) acc[sl][e] = 0.f;
+        float best_score = -INFINITY;
+        int best_row = 0;
+        float sc_keep[NSB];
+
+#pragma unroll
+        for (int sb = 0; sb < NSB; ++sb) {
+            const int row0 = j * G + sb * R;
+            uint4 data[R][NSLOT];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int sl = 0; sl < NSLOT; ++sl) {
+                    data[r][sl] = make_uint4(0, 0, 0, 0);
+                    if (is_pool[sl]) data[r][sl] = *reinterpret_cast<const uint4 *>(pool_base + (size_t)(row0 + r) * P * DP + col[sl]);
+                    else if (is_sel[sl]) data[r][sl] = *reinterpret_cast<const uint4 *>(sel_base + (size_t)(row0 + r) * P * DS + col[sl]);
+                }
+            // partial dots of every row with this lane's slice of qbar
+            float part[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                float a = 0.f;
+#pragma unroll
+                for (int sl = 0; sl < NSLOT; ++sl) {
+                    float f[EPC];
+                    Elt<T>::unpack(data[r][sl], f);
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e) a = fmaf(f[e], qv[sl][e], a);
+                }
+                part[r] = a;
+            }
+            const float score = scale * wave_reduce_scatter<R>(part, lane);   // row (lane >> SH) of this sub-block
+            sc_keep[sb] = score;
+            // sub-block maximum and its lowest row
+            float bmax = score;
+            int brow = lane >> SH;
+#pragma unroll
+            for (int mask = 32; mask >= (1 << SH); mask >>= 1) {
+                const float os = __shfl_xor(bmax, mask, WAVE);
+                const int orow = __shfl_xor(brow, mask, WAVE);
+                if (os > bmax || (os == bmax && orow < brow)) { bmax = os; brow = orow; }
+            }
+            if (bmax > best_score) { best_score = bmax; best_row = sb * R + brow; }   // earlier sub-block wins ties
+            // online softmax over sub-blocks (Eq. 6) and weighted pooling (Eq. 7)
+            const float m_new = fmaxf(m_run, bmax);
+            const float corr = __expf(m_run - m_new);      // 0 on the first sub-block
+            const float pmine = __expf(score - m_new);
+            l_run *= corr;
+#pragma unroll
+            for (int sl = 0; sl < NSLOT; ++sl)
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) acc[sl][e] *= corr;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float pr = readlane_f(pmine, r << SH);
+                l_run += pr;
+#pragma unroll
+                for (int sl = 0; sl < NSLOT; ++sl) {
+                    if (sl * WAVE < NCP) {               // slots that can hold pool chunks
+                        float f[EPC];
+                        Elt<T>::unpack(data[r][sl], f);
+#pragma unroll
+                        for (int e = 0; e < EPC; ++e) acc[sl][e] = fmaf(pr, f[e], acc[sl][e]);
+                    }
+                }
+            }
+            m_run = m_new;
+        }
+
+        const size_t unit = ((size_t)b * S + s) * m + j;
+        const float inv_l = 1.f / l_run;
+#pragma unroll
+        for (int sl = 0; sl < NSLOT; ++sl) {
+            if (sl * WAVE < NCP && is_pool[sl]) {
+                float o[EPC];
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) o[e] = acc[sl][e] * inv_l;
+                *reinterpret_cast<uint4 *>(pool_rep + unit * DP + col[sl]) = Elt<T>::pack(o);
+            }
+        }
+        const int a_tok = j * G + best_row;
+#pragma unroll
+        for (int sl = 0; sl < NSLOT; ++sl)
+            if (is_sel[sl])
+                *reinterpret_cast<uint4 *>(sel_rep + unit * DS + col[sl]) =
+                    *reinterpret_cast<const uint4 *>(sel_base + (size_t)a_tok * P * DS + col[sl]);
+        if (lane == 0) anchor[unit] = a_tok;
+        if (alpha_dbg != nullptr && (lane & ((1 << SH) - 1)) == 0) {
+#pragma unroll
+            for (int sb = 0; sb < NSB; ++sb) alpha_dbg[unit * G + sb * R + (lane >> SH)] = __expf(sc_keep[sb] - m_run) * inv_l;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic condensation: one wave per (b, s, j), run-time sizes, g <= 64.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void condense_generic_kernel(const T *__restrict__ POOL, const T *__restrict__ SEL,
+                                                               const float *__restrict__ qbar, T *__restrict__ pool_rep,
+                                                               T *__restrict__ sel_rep, int32_t *__restrict__ anchor,
+                                                               float *__restrict__ alpha_dbg, int B, int L, int S, int m, int g,
+                                                               int d_pool, int d_sel, int mla, float scale)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const long unit = (long)blockIdx.x * (blockDim.x / WAVE) + (threadIdx.x / WAVE);
+    if (unit >= (long)B * S * m) return;
+    const int j = (int)(unit % m), s = (int)((unit / m) % S), b = (int)(unit / ((long)m * S));
+    const int P = mla ? 1 : S, p = mla ? 0 : s, d_qk = mla ? d_pool + d_sel : d_sel;
+    const float *qb = qbar + ((size_t)b * S + s) * d_qk;
+    const T *pool_base = POOL + ((size_t)b * L * P + p) * d_pool;
+    const T *sel_base = SEL + ((size_t)b * L * P + p) * d_sel;
+
+    float my_score = -INFINITY;            // lane r holds the score of row r
+    for (int r = 0; r < g; ++r) {
+        const T *pr = pool_base + (size_t)(j * g + r) * P * d_pool;
+        const T *sr = sel_base + (size_t)(j * g + r) * P * d_sel;
+        float a = 0.f;
+        if (mla)
+            for (int x = lane; x < d_pool; x += WAVE) a = fmaf(Elt<T>::ld(pr + x), qb[x], a);
+        const int qoff = mla ? d_pool : 0;
+        for (int x = lane; x < d_sel; x += WAVE) a = fmaf(Elt<T>::ld(sr + x), qb[qoff + x], a);
+        for (int mask = 32; mask >= 1; mask >>= 1) a += __shfl_xor(a, mask, WAVE);
+        if (lane == r) my_score = scale * a;
+    }
+    float bmax = my_score;
+    int brow = lane;
+    for (int mask = 32; mask >= 1; mask >>= 1) {
+        const float os = __shfl_xor(bmax, mask, WAVE);
+        const int orow = __shfl_xor(brow, mask, WAVE);
+        if (os > bmax || (os == bmax && orow < brow)) { bmax = os; brow = orow; }
+    }
+    const float pmine = lane < g ? __expf(my_score - bmax) : 0.f;
+    float z = pmine;
+    for (int mask = 32; mask >= 1; mask >>= 1) z += __shfl_xor(z, mask, WAVE);
+    const float alpha = pmine / z;
+    for (int x = lane; x < d_pool; x += WAVE) {
+        float acc = 0.f;
+        for (int r = 0; r < g; ++r) acc = fmaf(__shfl(alpha, r, WAVE), Elt<T>::ld(pool_base + (size_t)(j * g + r) * P * d_pool + x), acc);
+        Elt<T>::st(pool_rep + (size_t)unit * d_pool + x, acc);
+    }
+    const int a_tok = j * g + brow;
+    for (int x = lane; x < d_sel; x += WAVE) sel_rep[(size_t)unit * d_sel + x] = sel_base[(size_t)a_tok * P * d_sel + x];
+    if (lane == 0) anchor[unit] = a_tok;
+    if (alpha_dbg != nullptr && lane < g) alpha_dbg[(size_t)unit * g + lane] = alpha;
+}
+
+template <typename T, int DP, int DS, int G, bool MLA>
+hipError_t run_reg(const CondenseArgs &a, hipStream_t st)
+{
+    const Dims &d = a.d;
+    const long units = (long)d.B * (MLA ? 1 : d.S) * d.m;
+    const int blocks = (int)((units + 3) / 4);
+    condense_reg_kernel<T, DP, DS, G, MLA><<<blocks, 256, 0, st>>>(
+        (const T *)a.POOL, (const T *)a.SEL, a.qbar, (T *)a.pool_rep, (T *)a.sel_rep, a.anchor, a.alpha_dbg, d.B, d.L, d.S, d.m, d.scale);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t run_generic(const CondenseArgs &a, hipStream_t st)
+{
+    const Dims &d = a.d;
+    const long units = (long)d.B * d.S * d.m;
+    const int blocks = (int)((units + 3) / 4);
+    condense_generic_kernel<T><<<blocks, 256, 0, st>>>((const T *)a.POOL, (const T *)a.SEL, a.qbar, (T *)a.pool_rep, (T *)a.sel_rep,
+                                                       a.anchor, a.alpha_dbg, d.B, d.L, d.S, d.m, d.g, d.d_pool, d.d_sel,
+                                                       d.mode == LCA_MODE_MLA, d.scale);
+    return hipGetLastError();
+}
+
+template <typename T, int DP, int DS, bool MLA>
+bool try_reg(const CondenseArgs &a, hipStream_t st, hipError_t &err)
+{
+    switch (a.d.g) {
+    case 1: err = run_reg<T, DP, DS, 1, MLA>(a, st); return true;
+    case 2: err = run_reg<T, DP, DS, 2, MLA>(a, st); return true;
+    case 4: err = run_reg<T, DP, DS, 4, MLA>(a, st); return true;
+    case 8: err = run_reg<T, DP, DS, 8, MLA>(a, st); return true;
+    case 16: err = run_reg<T, DP, DS, 16, MLA>(a, st); return true;
+    case 32: err = run_reg<T, DP, DS, 32, MLA>(a, st); return true;
+    default: return false;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_condense(const CondenseArgs &a, hipStream_t st)
+{
+    const Dims &d = a.d;
+    // 1. summary query (Algorithm 1, first step)
+    if (d.dtype == LCA_BF16)
+        summary_query_kernel<uint16_t><<<d.B * d.S, 256, 0, st>>>((const uint16_t *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
+    else
+        summary_query_kernel<float><<<d.B * d.S, 256, 0, st>>>((const float *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || d.m == 0) return err;
+    // 2. groups
+    const bool mla = d.mode == LCA_MODE_MLA;
+    if (d.dtype == LCA_BF16 && mla && d.d_pool == 512 && d.d_sel == 64 && try_reg<uint16_t, 512, 64, true>(a, st, err)) return err;
+    if (d.dtype == LCA_BF16 && !mla && d.d_pool == 128 && d.d_sel == 128 && try_reg<uint16_t, 128, 128, false>(a, st, err)) return err;
+    if (d.dtype == LCA_F32 && mla && d.d_pool == 128 && d.d_sel == 32 && try_reg<float, 128, 32, true>(a, st, err)) return err;
+    return d.dtype == LCA_BF16 ? run_generic<uint16_t>(a, st) : run_generic<float>(a, st);
+}
+
+}  // namespace lca

@@ -1,0 +1,197 @@
+// C ABI of liblca: argument validation, workspace carving and kernel dispatch.  No allocation, no
+// synchronisation, no state beyond the thread-local error string.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "lca_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+lca_status fail(lca_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Validate the descriptor and derive sizes. `decode`: L counts the token being decoded.
+lca_status make_dims(const lca_desc *desc, lca::Dims &d)
+{
+    if (desc == nullptr) return fail(LCA_ERR_INVALID_ARG, "desc is NULL");
+    if (desc->B <= 0 || desc->L <= 0 || desc->H <= 0 || desc->S <= 0) return fail(LCA_ERR_INVALID_ARG, "B, L, H, S must be positive");
+    if (desc->H % desc->S != 0) return fail(LCA_ERR_INVALID_ARG, "H (%d) must be a multiple of S (%d)", desc->H, desc->S);
+    if (desc->g <= 0 || desc->g > 64) return fail(LCA_ERR_INVALID_ARG, "g must be in [1, 64], got %d", desc->g);
+    if (desc->w < 0) return fail(LCA_ERR_INVALID_ARG, "w must be >= 0");
+    if (desc->mode != LCA_MODE_MLA && desc->mode != LCA_MODE_GQA) return fail(LCA_ERR_INVALID_ARG, "unknown mode %d", desc->mode);
+    if (desc->dtype != LCA_BF16 && desc->dtype != LCA_F32) return fail(LCA_ERR_INVALID_ARG, "unknown dtype %d", desc->dtype);
+    const int mult = desc->dtype == LCA_BF16 ? 8 : 4;
+    if (desc->d_pool <= 0 || desc->d_sel <= 0 || desc->d_pool % mult || desc->d_sel % mult)
+        return fail(LCA_ERR_INVALID_ARG, "d_pool and d_sel must be positive multiples of %d", mult);
+    const int d_qk = desc->mode == LCA_MODE_MLA ? desc->d_pool + desc->d_sel : desc->d_sel;
+    if (d_qk > 1024 || desc->d_pool > 1024) return fail(LCA_ERR_UNSUPPORTED, "d_qk and d_pool above 1024 are not supported");
+    const int n_q = desc->n_q == 0 ? desc->g : desc->n_q;
+    if (n_q < 0 || n_q > desc->L) return fail(LCA_ERR_INVALID_ARG, "n_q (%d) must be in [1, L]", n_q);
+    if (!(desc->scale == desc->scale) || !(desc->rep_logit_bias == desc->rep_logit_bias)) return fail(LCA_ERR_INVALID_ARG, "scale / bias is NaN");
+    if ((long long)desc->B * desc->L * desc->H >= (1ll << 31)) return fail(LCA_ERR_UNSUPPORTED, "B*L*H must be below 2^31");
+    d.B = desc->B; d.L = desc->L; d.H = desc->H; d.S = desc->S;
+    d.P = desc->mode == LCA_MODE_MLA ? 1 : desc->S;
+    d.d_pool = desc->d_pool; d.d_sel = desc->d_sel; d.d_qk = d_qk; d.d_v = desc->d_pool;
+    d.g = desc->g; d.w = desc->w; d.n_q = n_q;
+    d.m = desc->L > desc->w ? (desc->L - desc->w) / desc->g : 0;
+    d.k = desc->L - d.m * desc->g;
+    d.mode = desc->mode; d.dtype = desc->dtype; d.elt = desc->dtype == LCA_BF16 ? 2 : 4;
+    d.scale = desc->scale; d.rep_logit_bias = desc->rep_logit_bias;
+    return LCA_OK;
+}
+
+size_t qbar_bytes(const lca::Dims &d) { return (((size_t)d.B * d.S * d.d_qk * sizeof(float)) + 255) & ~(size_t)255; }
+
+size_t workspace_bytes(const lca::Dims &d)
+{
+    size_t need = qbar_bytes(d);
+    const size_t dec = lca::decode_workspace_bytes(d);
+    return need > dec ? need : dec;
+}
+
+lca_status check_ptr(const void *p, const char *name, bool required = true)
+{
+    if (p == nullptr) return required ? fail(LCA_ERR_INVALID_ARG, "%s is NULL", name) : LCA_OK;
+    if (!aligned16(p)) return fail(LCA_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
+    return LCA_OK;
+}
+
+#define LCA_TRY(expr)                      \
+    do {                                   \
+        lca_status _s = (expr);            \
+        if (_s != LCA_OK) return _s;       \
+    } while (0)
+
+lca_status check_ws(const lca::Dims &d, const void *ws, size_t ws_bytes)
+{
+    const size_t need = workspace_bytes(d);
+    if (need == 0) return LCA_OK;
+    if (ws == nullptr) return fail(LCA_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", need);
+    if (!aligned16(ws)) return fail(LCA_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+    if (ws_bytes < need) return fail(LCA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, need);
+    return LCA_OK;
+}
+
+lca_status hip_status(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return LCA_OK;
+    return fail(LCA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+lca_status run_attn(const lca::AttnArgs &a, hipStream_t st, const char *what)
+{
+    if (lca::attn_mfma_supported(a.d)) return hip_status(lca::launch_attn_mfma(a, st), what);
+    return hip_status(lca::launch_attn_simple(a, st), what);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *lca_last_error(void) { return g_err; }
+
+lca_status lca_workspace_size(const lca_desc *desc, size_t *bytes)
+{
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    if (bytes == nullptr) return fail(LCA_ERR_INVALID_ARG, "bytes is NULL");
+    *bytes = workspace_bytes(d);
+    return LCA_OK;
+}
+
+lca_status lca_cache_bytes(const lca_desc *desc, size_t *dense_bytes, size_t *condensed_bytes)
+{
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    if (dense_bytes == nullptr || condensed_bytes == nullptr) return fail(LCA_ERR_INVALID_ARG, "output pointer is NULL");
+    const size_t row = (size_t)(d.d_pool + d.d_sel) * d.elt;
+    *dense_bytes = (size_t)d.B * d.L * d.P * row;
+    *condensed_bytes = (size_t)d.B * ((size_t)d.S * d.m + (size_t)d.P * d.k) * row;
+    return LCA_OK;
+}
+
+lca_status lca_condense(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL, void *pool_rep, void *sel_rep,
+                        int32_t *anchor_idx, float *alpha_dbg, void *workspace, size_t workspace_bytes_, void *stream)
+{
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    LCA_TRY(check_ptr(Q, "Q"));
+    LCA_TRY(check_ptr(POOL, "POOL"));
+    LCA_TRY(check_ptr(SEL, "SEL"));
+    LCA_TRY(check_ptr(pool_rep, "pool_rep", d.m > 0));
+    LCA_TRY(check_ptr(sel_rep, "sel_rep", d.m > 0));
+    if (d.m > 0 && anchor_idx == nullptr) return fail(LCA_ERR_INVALID_ARG, "anchor_idx is NULL");
+    LCA_TRY(check_ws(d, workspace, workspace_bytes_));
+    lca::CondenseArgs a;
+    a.d = d; a.Q = Q; a.POOL = POOL; a.SEL = SEL; a.pool_rep = pool_rep; a.sel_rep = sel_rep;
+    a.anchor = anchor_idx; a.alpha_dbg = alpha_dbg; a.qbar = static_cast<float *>(workspace);
+    return hip_status(lca::launch_condense(a, static_cast<hipStream_t>(stream)), "lca_condense");
+}
+
+lca_status lca_prefill_attn(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL, const void *pool_rep,
+                            const void *sel_rep, void *O, float *lse, void *workspace, size_t workspace_bytes_, void *stream)
+{
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    LCA_TRY(check_ptr(Q, "Q"));
+    LCA_TRY(check_ptr(POOL, "POOL"));
+    LCA_TRY(check_ptr(SEL, "SEL"));
+    LCA_TRY(check_ptr(pool_rep, "pool_rep", d.m > 0));
+    LCA_TRY(check_ptr(sel_rep, "sel_rep", d.m > 0));
+    LCA_TRY(check_ptr(O, "O"));
+    LCA_TRY(check_ws(d, workspace, workspace_bytes_));
+    lca::AttnArgs a;
+    a.d = d; a.Q = Q; a.POOL = POOL; a.SEL = SEL; a.pool_rep = pool_rep; a.sel_rep = sel_rep; a.O = O; a.lse = lse; a.dense = 0;
+    return run_attn(a, static_cast<hipStream_t>(stream), "lca_prefill_attn");
+}
+
+lca_status dense_mla_attn(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL, void *O, float *lse,
+                          void *workspace, size_t workspace_bytes_, void *stream)
+{
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    LCA_TRY(check_ptr(Q, "Q"));
+    LCA_TRY(check_ptr(POOL, "POOL"));
+    LCA_TRY(check_ptr(SEL, "SEL"));
+    LCA_TRY(check_ptr(O, "O"));
+    LCA_TRY(check_ws(d, workspace, workspace_bytes_));
+    d.m = 0;            // no representatives: every row attends all tokens i <= t
+    d.k = d.L;
+    lca::AttnArgs a;
+    a.d = d; a.Q = Q; a.POOL = POOL; a.SEL = SEL; a.pool_rep = nullptr; a.sel_rep = nullptr; a.O = O; a.lse = lse; a.dense = 1;
+    return run_attn(a, static_cast<hipStream_t>(stream), "dense_mla_attn");
+}
+
+lca_status lca_decode_attn(const lca_desc *desc, const void *q, const void *pool_rep, const void *sel_rep, const void *pool_tail,
+                           const void *sel_tail, void *O, void *workspace, size_t workspace_bytes_, void *stream)
+{
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    if (!lca::decode_supported(d))
+        return fail(LCA_ERR_UNSUPPORTED, "lca_decode_attn has no kernel for this mode / dtype / widths / heads-per-set combination");
+    LCA_TRY(check_ptr(q, "q"));
+    LCA_TRY(check_ptr(pool_rep, "pool_rep", d.m > 0));
+    LCA_TRY(check_ptr(sel_rep, "sel_rep", d.m > 0));
+    LCA_TRY(check_ptr(pool_tail, "pool_tail"));
+    LCA_TRY(check_ptr(sel_tail, "sel_tail"));
+    LCA_TRY(check_ptr(O, "O"));
+    LCA_TRY(check_ws(d, workspace, workspace_bytes_));
+    lca::DecodeArgs a;
+    a.d = d; a.q = q; a.pool_rep = pool_rep; a.sel_rep = sel_rep; a.pool_tail = pool_tail; a.sel_tail = sel_tail; a.O = O;
+    a.part = static_cast<float *>(workspace);
+    a.splits = lca::decode_splits(d);
+    return hip_status(lca::launch_decode(a, static_cast<hipStream_t>(stream)), "lca_decode_attn");
+}
+
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Internal declarations shared by the liblca translation units (host side of the launchers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "lca.h"
+
+namespace lca {
+
+// Derived sizes of a validated descriptor.
+struct Dims {
+    int B, L, H, S, P;        // P = KV heads physically present in POOL/SEL (1 for MLA, S for GQA)
+    int d_pool, d_sel, d_qk, d_v;
+    int g, w, n_q, m, k;      // m groups, k raw tail tokens
+    int mode, dtype, elt;     // elt = bytes per element
+    float scale, rep_logit_bias;
+};
+
+// Where one attention launch finds its keys/values.
+struct AttnArgs {
+    Dims d;
+    const void *Q, *POOL, *SEL, *pool_rep, *sel_rep;
+    void *O;
+    float *lse;
+    int dense;                // 1: every row sees all tokens i <= t, representatives unused
+};
+
+struct CondenseArgs {
+    Dims d;
+    const void *Q, *POOL, *SEL;
+    void *pool_rep, *sel_rep;
+    int32_t *anchor;
+    float *alpha_dbg;
+    float *qbar;              // workspace, [B, S, d_qk] float
+};
+
+struct DecodeArgs {
+    Dims d;
+    const void *q, *pool_rep, *sel_rep, *pool_tail, *sel_tail;
+    void *O;
+    float *part;              // workspace: split partials
+    int splits;
+};
+
+// Launchers return hipSuccess or the launch error. They assume validated arguments.
+hipError_t launch_condense(const CondenseArgs &a, hipStream_t st);
+hipError_t launch_attn_simple(const AttnArgs &a, hipStream_t st);
+bool attn_mfma_supported(const Dims &d);
+hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t st);
+bool decode_supported(const Dims &d);
+int decode_splits(const Dims &d);
+size_t decode_workspace_bytes(const Dims &d);
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t st);
+
+}  // namespace lca

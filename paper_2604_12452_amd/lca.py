@@ -1,0 +1,184 @@
+"""Thin ctypes binding of liblca (see include/lca.h): argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels.  Tensors are torch tensors on the GPU
+(torch is used for device memory and streams only); bf16 data may be passed as ``torch.bfloat16`` or
+as int16/uint16 bit patterns.  There is no CPU fallback: if ``liblca.so`` has not been built the
+first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "liblca.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
+MODE_MLA, MODE_GQA = 0, 1
+BF16, F32 = 0, 1
+
+EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condense", "lca_prefill_attn", "dense_mla_attn",
+           "lca_decode_attn", "lca_last_error")
+
+
+class LcaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"liblca status {status}: {message}")
+        self.status = status
+
+
+class _CDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "L", "H", "S", "d_pool", "d_sel", "g", "w", "n_q", "mode", "dtype")] + [
+        ("scale", ctypes.c_float), ("rep_logit_bias", ctypes.c_float)]
+
+
+@dataclass
+class Desc:
+    """Mirror of ``lca_desc``; names follow the paper (L tokens, group size g, window w)."""
+    B: int
+    L: int
+    H: int
+    S: int
+    d_pool: int
+    d_sel: int
+    g: int
+    w: int
+    n_q: int = 0
+    mode: int = MODE_MLA
+    dtype: int = BF16
+    scale: float = 1.0
+    rep_logit_bias: float = 0.0
+
+    @property
+    def d_qk(self) -> int:
+        return self.d_pool + self.d_sel if self.mode == MODE_MLA else self.d_sel
+
+    @property
+    def m(self) -> int:
+        return (self.L - self.w) // self.g if self.L > self.w else 0
+
+    @property
+    def k(self) -> int:
+        return self.L - self.m * self.g
+
+    @property
+    def kv_heads(self) -> int:
+        return 1 if self.mode == MODE_MLA else self.S
+
+    def c(self) -> _CDesc:
+        return _CDesc(self.B, self.L, self.H, self.S, self.d_pool, self.d_sel, self.g, self.w, self.n_q, self.mode,
+                      self.dtype, float(self.scale), float(self.rep_logit_bias))
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load liblca.so; raises if it has not been built (``python -m paper_2604_12452_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_12452_amd.build`; "
+                                    "there is no fallback path")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name in EXPORTS:
+            getattr(lib, name).restype = ctypes.c_int
+        lib.lca_last_error.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def _ptr(t):
+    """Device address of a tensor (or None / int passthrough)."""
+    if t is None:
+        return ctypes.c_void_p(0)
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    if not t.is_contiguous():
+        raise ValueError("liblca needs contiguous tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(status: int):
+    if status != OK:
+        raise LcaError(status, load().lca_last_error().decode())
+
+
+def workspace_size(desc: Desc) -> int:
+    n = ctypes.c_size_t(0)
+    cd = desc.c()
+    _check(load().lca_workspace_size(ctypes.byref(cd), ctypes.byref(n)))
+    return int(n.value)
+
+
+def cache_bytes(desc: Desc):
+    a, b = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    cd = desc.c()
+    _check(load().lca_cache_bytes(ctypes.byref(cd), ctypes.byref(a), ctypes.byref(b)))
+    return int(a.value), int(b.value)
+
+
+def condense(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, anchor_idx, alpha_dbg, workspace, stream=None):
+    cd = desc.c()
+    _check(load().lca_condense(ctypes.byref(cd), _ptr(Q), _ptr(POOL), _ptr(SEL), _ptr(pool_rep), _ptr(sel_rep),
+                               _ptr(anchor_idx), _ptr(alpha_dbg), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)),
+                               _stream(stream)))
+
+
+def prefill_attn(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, O, lse, workspace, stream=None):
+    cd = desc.c()
+    _check(load().lca_prefill_attn(ctypes.byref(cd), _ptr(Q), _ptr(POOL), _ptr(SEL), _ptr(pool_rep), _ptr(sel_rep),
+                                   _ptr(O), _ptr(lse), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)),
+                                   _stream(stream)))
+
+
+def dense_attn(desc: Desc, Q, POOL, SEL, O, lse, workspace, stream=None):
+    cd = desc.c()
+    _check(load().dense_mla_attn(ctypes.byref(cd), _ptr(Q), _ptr(POOL), _ptr(SEL), _ptr(O), _ptr(lse), _ptr(workspace),
+                                 ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
+
+
+def decode_attn(desc: Desc, q, pool_rep, sel_rep, pool_tail, sel_tail, O, workspace, stream=None):
+    cd = desc.c()
+    _check(load().lca_decode_attn(ctypes.byref(cd), _ptr(q), _ptr(pool_rep), _ptr(sel_rep), _ptr(pool_tail),
+                                  _ptr(sel_tail), _ptr(O), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)),
+                                  _stream(stream)))
+
+
+# ---------------------------------------------------------------------------------------------
+# device-buffer helpers (torch used for memory only)
+# ---------------------------------------------------------------------------------------------
+def torch_dtype(desc: Desc):
+    import torch
+    return torch.bfloat16 if desc.dtype == BF16 else torch.float32
+
+
+def alloc_workspace(desc: Desc, device="cuda"):
+    import torch
+    return torch.empty(max(workspace_size(desc), 256), dtype=torch.uint8, device=device)
+
+
+def alloc_condensed(desc: Desc, device="cuda", alpha: bool = False):
+    """Buffers lca_condense writes: (pool_rep, sel_rep, anchor_idx, alpha_dbg or None)."""
+    import torch
+    dt = torch_dtype(desc)
+    m = desc.m
+    pool_rep = torch.empty((desc.B, desc.S, m, desc.d_pool), dtype=dt, device=device)
+    sel_rep = torch.empty((desc.B, desc.S, m, desc.d_sel), dtype=dt, device=device)
+    anchor = torch.empty((desc.B, desc.S, m), dtype=torch.int32, device=device)
+    a = torch.empty((desc.B, desc.S, m * desc.g), dtype=torch.float32, device=device) if alpha else None
+    return pool_rep, sel_rep, anchor, a

@@ -1,0 +1,160 @@
+"""GPU parity: liblca (through its C ABI) against the fp64 oracle on the same seeded inputs.
+
+Stage 1: condensation (anchors bit-exact above the score margin, pooled vectors within tolerance,
+selected rows bit-exact copies).  Stage 2: attention fed the GPU's own emitted cache.  Stage 3: end to
+end against the all-fp64 oracle.  Small shapes are compared on every row; they span several query
+blocks, several key tiles and ragged tails of both.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2604_12452_amd import inputs
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+
+def _wl(name, **kw):
+    base = dict(B=1, L=333, H=4, S=2, d_pool=16, d_sel=8, g=4, w=10, dtype="f32", seed=42)
+    base.update(kw)
+    return inputs.Workload(name, **base)
+
+
+def _full_parity(oracle, wl, bias=0.0, dense=True):
+    print(f"[case] {wl}", flush=True)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    Qf, POOLf, SELf = (inputs.to_f64(x, wl.dtype) for x in (Q, POOL, SEL))
+    run = hp.GpuRun(wl, Q, POOL, SEL, rep_logit_bias=bias).condense()
+    ref, differ = hp.check_condense(oracle, wl, run, Qf[:, wl.L - wl.nq:], POOLf, SELf)
+    run.prefill()
+    rows = np.arange(wl.L, dtype=np.int32)
+    e2, e3 = hp.check_prefill(oracle, wl, run, rows, Qf, POOLf, SELf, ref, differ, bias=bias)
+    e_d = None
+    if dense:
+        run.dense()
+        e_d = hp.check_dense(oracle, wl, run, rows, Qf, POOLf, SELf)
+    print(f"  stage2 {e2:.2e} stage3 {e3:.2e} dense {e_d}", flush=True)
+    return run
+
+
+# ---- generic kernels (any widths), both element types, both modes --------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [inputs.MODE_MLA, inputs.MODE_GQA])
+@pytest.mark.parametrize("L,g,w,H,S", [(333, 4, 10, 4, 2), (129, 8, 0, 2, 1), (70, 1, 5, 2, 2), (257, 64, 3, 6, 3), (40, 3, 7, 1, 1)])
+def test_generic_kernels_small_shapes(oracle, dtype, mode, L, g, w, H, S):
+    _full_parity(oracle, _wl("generic", L=L, g=g, w=w, H=H, S=S, dtype=dtype, mode=mode, d_pool=24, d_sel=16, B=2))
+
+
+@pytest.mark.parametrize("L,w,g", [(40, 64, 4), (10, 8, 4), (1, 0, 1), (5, 0, 8)])
+def test_no_groups_falls_back_to_dense(oracle, L, w, g):
+    wl = _wl("short", L=L, w=w, g=min(g, 8), n_q=1)
+    assert wl.m == 0
+    run = _full_parity(oracle, wl)
+    assert np.array_equal(hp.from_dev(run.O, wl.dtype), hp.from_dev(run.O_dense, wl.dtype))
+
+
+# ---- configuration 1: tiny fp32 case, every row -----------------------------------------------------
+@pytest.mark.parametrize("S", [1, 4])
+def test_cfg1_tiny_fp32_all_rows(oracle, S):
+    _full_parity(oracle, inputs.configs()["cfg1"].with_(S=S))
+
+
+# ---- MFMA kernel at the MLA widths (512 + 64), small L, every row -----------------------------------
+@pytest.mark.parametrize("L,g,w,H,S,B", [
+    (700, 16, 100, 2, 1, 1),      # several query blocks and key tiles, ragged tails
+    (700, 16, 100, 2, 2, 2),      # one condensed set per head
+    (513, 32, 0, 1, 1, 1),        # no window: only the remainder stays raw
+    (300, 8, 64, 4, 2, 1),
+    (257, 1, 31, 1, 1, 1),        # one-token groups: equals dense
+    (128, 16, 16, 1, 1, 1),       # exactly one query block
+    (100, 16, 200, 2, 1, 1),      # L < w: no groups
+    (33, 2, 3, 1, 1, 1),
+])
+def test_mla_mfma_small_all_rows(oracle, L, g, w, H, S, B):
+    wl = inputs.Workload("mla_small", B=B, L=L, H=H, S=S, d_pool=512, d_sel=64, g=g, w=w, dtype="bf16", seed=7 + L)
+    _full_parity(oracle, wl)
+
+
+def test_mla_mfma_multiplicity_bias(oracle):
+    wl = inputs.Workload("mla_bias", B=1, L=400, H=2, S=1, d_pool=512, d_sel=64, g=16, w=32, dtype="bf16", seed=5)
+    _full_parity(oracle, wl, bias=math.log(16.0), dense=False)
+
+
+def test_mla_topic_shift_inputs(oracle):
+    wl = inputs.Workload("mla_topics", B=2, L=640, H=2, S=1, d_pool=512, d_sel=64, g=16, w=64, dtype="bf16", seed=9, segments=8)
+    _full_parity(oracle, wl)
+
+
+# ---- MFMA kernel at the GQA widths (128 / 128) --------------------------------------------------------
+@pytest.mark.parametrize("L,g,w,H,S", [(700, 16, 100, 8, 2), (300, 8, 0, 4, 4), (129, 16, 64, 4, 1)])
+def test_gqa_mfma_small_all_rows(oracle, L, g, w, H, S):
+    wl = inputs.Workload("gqa_small", B=1, L=L, H=H, S=S, d_pool=128, d_sel=128, g=g, w=w, dtype="bf16", mode=inputs.MODE_GQA,
+                         theta=500000.0, seed=11 + L)
+    _full_parity(oracle, wl)
+
+
+# ---- configuration 2 at full size: sampled rows -----------------------------------------------------
+@pytest.mark.parametrize("S", [1, 16])
+def test_cfg2_sampled_rows(oracle, S):
+    wl = inputs.configs()["cfg2"].with_(S=S)
+    print(f"[case] {wl}", flush=True)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    POOLf, SELf = inputs.to_f64(POOL, wl.dtype), inputs.to_f64(SEL, wl.dtype)
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense()
+    Qtail = inputs.to_f64(Q[:, wl.L - wl.nq:], wl.dtype)
+    ref, differ = hp.check_condense(oracle, wl, run, Qtail, POOLf, SELf)
+    run.prefill().dense()
+    rows = inputs.sample_rows(wl, 48)
+    Qr = inputs.to_f64(Q[:, rows], wl.dtype)
+    e2, e3 = hp.check_prefill(oracle, wl, run, rows, Qr, POOLf, SELf, ref, differ)
+    e_d = hp.check_dense(oracle, wl, run, rows[::3], Qr[:, ::3], POOLf, SELf)
+    print(f"  stage2 {e2:.2e} stage3 {e3:.2e} dense {e_d:.2e}", flush=True)
+    # every row was written
+    assert bool(run.O.isfinite().all()) and bool(run.O_dense.isfinite().all())
+
+
+def test_results_are_deterministic(oracle):
+    wl = inputs.Workload("det", B=1, L=600, H=2, S=1, d_pool=512, d_sel=64, g=16, w=64, dtype="bf16", seed=3)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    a = hp.GpuRun(wl, Q, POOL, SEL).condense().prefill()
+    b = hp.GpuRun(wl, Q, POOL, SEL).condense().prefill()
+    for x, y in ((a.O, b.O), (a.pool_rep, b.pool_rep), (a.anchor, b.anchor), (a.lse, b.lse)):
+        assert bool((x.view(-1) == y.view(-1)).all())
+
+
+# ---- decode step over the condensed cache -------------------------------------------------------------
+@pytest.mark.parametrize("mode,d_pool,d_sel,H,S,dtype", [
+    (inputs.MODE_GQA, 128, 128, 8, 2, "bf16"),
+    (inputs.MODE_GQA, 128, 128, 4, 4, "bf16"),
+    (inputs.MODE_MLA, 512, 64, 16, 1, "bf16"),
+    (inputs.MODE_MLA, 128, 32, 4, 1, "f32"),
+])
+@pytest.mark.parametrize("L,g,w", [(1000, 16, 100), (77, 4, 9), (50, 16, 64)])
+def test_decode_step(oracle, mode, d_pool, d_sel, H, S, dtype, L, g, w):
+    import torch
+    from paper_2604_12452_amd import lca
+    B = 3
+    wl = inputs.Workload("decode", B=B, L=L, H=H, S=S, d_pool=d_pool, d_sel=d_sel, g=g, w=w, dtype=dtype, mode=mode, seed=21 + L)
+    print(f"[case] {wl}", flush=True)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense(alpha=False)
+    # the cache after L tokens, the newest of which is the one being decoded
+    m, k = wl.m, wl.k
+    if mode == inputs.MODE_MLA:
+        pool_tail = run.POOL[:, None, m * g:].contiguous()
+        sel_tail = run.SEL[:, None, m * g:].contiguous()
+    else:
+        pool_tail = run.POOL[:, m * g:].permute(0, 2, 1, 3).contiguous()
+        sel_tail = run.SEL[:, m * g:].permute(0, 2, 1, 3).contiguous()
+    q = run.Q[:, L - 1].contiguous()
+    O = torch.full((B, H, d_pool), float("nan"), dtype=lca.torch_dtype(run.desc), device="cuda")
+    lca.decode_attn(run.desc, q, run.pool_rep, run.sel_rep, pool_tail, sel_tail, O, run.ws)
+    torch.cuda.synchronize()
+    od = hp.oracle_desc(oracle, wl)
+    ref = oracle.decode_attn(od, hp.from_dev(q, dtype), hp.from_dev(run.pool_rep, dtype), hp.from_dev(run.sel_rep, dtype),
+                             hp.from_dev(pool_tail, dtype), hp.from_dev(sel_tail, dtype))
+    err = hp.vec_rel_err(hp.from_dev(O, dtype), ref)
+    print(f"  decode err {err:.2e}", flush=True)
+    assert err <= hp.TOL[dtype]
