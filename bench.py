@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the LCA prefill hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input that is already
+resident in HBM: lca_condense (summary query + group condensation) followed by lca_prefill_attn.
+Workload = the 128K configuration (batch 1, 16 heads, d_c = 512, d_R = 64, bf16, g = 16, w = 1024,
+one condensed set shared by the heads — the setting whose cache sizes match the paper's).
+Prints ONE JSON line: prefill tokens/s, the roofline of the dominant kernel (attention, bf16 MFMA),
+and the CPU oracle timed on a bounded sample of the same workload.  The dense MLA baseline, the
+condensation kernel's HBM rate, KV-cache bytes and the g = 32 / per-head-set variants go in "extra".
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def pair_count(L: int, w: int, g: int, rows=None) -> int:
+    """Visible (query, key) pairs per head: sum over rows t of m_t + (t + 1 - m_t g)."""
+    t = np.arange(L, dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
+    mt = np.maximum(0, (t + 1 - w) // g)
+    return int((mt + t + 1 - mt * g).sum())
+
+
+def condense_bytes(wl) -> int:
+    """Algorithmic HBM bytes of one condensation: groups read once, representatives + anchors written."""
+    row = (wl.d_pool + wl.d_sel) * 2
+    return wl.B * wl.kv_heads * wl.m * wl.g * row + wl.B * wl.S * wl.m * (row + 4) + wl.nq * wl.H * wl.d_qk * 2
+
+
+def time_kernel(fn, iters: int, warmup: int):
+    """Average duration (ms) of fn's GPU work, HIP events on the current stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def cpu_baseline(wl, Q, POOL, SEL, n_rows: int):
+    """The fp64 oracle as it stands, timed on the host cores, on a bounded sample of the workload:
+    the full condensation plus n_rows evenly spaced query rows (all heads); extrapolated to a full
+    prefill by the sampled rows' share of the visible (query, key) pairs."""
+    import oracle
+    from paper_2604_12452_amd import inputs
+    oracle.build()
+    d = oracle.Desc(B=wl.B, L=wl.L, H=wl.H, S=wl.S, d_pool=wl.d_pool, d_sel=wl.d_sel, g=wl.g, w=wl.w, n_q=wl.n_q,
+                    mode=wl.mode, scale=wl.scale)
+    POOLf, SELf = inputs.to_f64(POOL, wl.dtype), inputs.to_f64(SEL, wl.dtype)
+    rows = (np.arange(n_rows) * wl.L // n_rows + wl.L // (2 * n_rows)).astype(np.int32)
+    Qr = inputs.to_f64(Q[:, rows], wl.dtype)
+    Qt = inputs.to_f64(Q[:, wl.L - wl.nq:], wl.dtype)
+    t0 = time.perf_counter()
+    c = oracle.condense(d, oracle.summary_query(d, Qt), POOLf, SELf)
+    t1 = time.perf_counter()
+    O = oracle.lca_attn_rows(d, rows, Qr, POOLf, SELf, c["pool_rep"], c["sel_rep"])
+    t2 = time.perf_counter()
+    share = pair_count(wl.L, wl.w, wl.g, rows) / pair_count(wl.L, wl.w, wl.g)
+    full_s = (t1 - t0) + (t2 - t1) / share
+    return {
+        "value": wl.B * wl.L / full_s, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"full condensation ({t1 - t0:.2f} s) + {n_rows} evenly spaced query rows x {wl.H} heads "
+                  f"({t2 - t1:.2f} s, {share:.3e} of all visible pairs), extrapolated to the whole prefill",
+    }, rows, O, c
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg4", help="cfg2 | cfg3 | cfg4 (default, the metric's workload)")
+    ap.add_argument("--oracle-rows", type=int, default=512)
+    ap.add_argument("--no-extra", action="store_true", help="skip dense baseline and variants (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives in this path)")
+
+    import torch
+    from paper_2604_12452_amd import device as hp
+    from paper_2604_12452_amd import inputs, lca
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    lca.load()   # fails loudly when liblca.so is missing
+    wl = inputs.configs()[args.config]
+    t_gen = time.perf_counter()
+    Q, POOL, SEL = inputs.gen_all(wl)
+    t_gen = time.perf_counter() - t_gen
+
+    run = hp.GpuRun(wl, Q, POOL, SEL)
+    d = run.desc
+    run.pool_rep, run.sel_rep, run.anchor, _ = lca.alloc_condensed(d)
+    O = torch.empty((d.B, d.L, d.H, d.d_pool), dtype=torch.bfloat16, device="cuda")
+
+    def f_cond():
+        lca.condense(d, run.Q, run.POOL, run.SEL, run.pool_rep, run.sel_rep, run.anchor, None, run.ws)
+
+    def f_attn():
+        lca.prefill_attn(d, run.Q, run.POOL, run.SEL, run.pool_rep, run.sel_rep, O, None, run.ws)
+
+    def step():
+        f_cond()
+        f_attn()
+
+    # ---- the timed region: W warm-up steps, then exactly K steps between synchronisations ----
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    tokens_per_s = wl.B * wl.L / (ms_per_step * 1e-3)
+
+    # ---- per-kernel durations (HIP events on the launch stream) ----
+    ms_attn = time_kernel(f_attn, args.steps, 1)
+    ms_cond = time_kernel(f_cond, max(args.steps, 20), 2)
+    pairs = pair_count(wl.L, wl.w, wl.g)
+    flops = 2.0 * (wl.d_qk + wl.d_v) * wl.B * wl.H * pairs
+    tflops = flops / (ms_attn * 1e-3) / 1e12
+    cbytes = condense_bytes(wl)
+
+    extra = {
+        "ms_condense": ms_cond, "ms_attn": ms_attn,
+        "condense_algorithmic_bytes": cbytes, "condense_GBps": cbytes / (ms_cond * 1e-3) / 1e9,
+        "condense_frac_of_hbm_peak": cbytes / (ms_cond * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "attn_algorithmic_flops": flops, "input_generation_s": t_gen,
+    }
+    dense_b, cond_b = lca.cache_bytes(d)
+    extra["kv_cache_bytes_dense"], extra["kv_cache_bytes_lca"] = dense_b, cond_b
+    extra["kv_cache_saved_frac"] = 1.0 - cond_b / dense_b
+
+    # ---- parity spot-check + CPU baseline on a bounded sample ----
+    base, rows, O_ref, cref = cpu_baseline(wl, Q, POOL, SEL, args.oracle_rows)
+    O_gpu = hp.from_dev(O[:, rows.tolist()], wl.dtype)
+    num = np.abs(O_gpu - O_ref).max(axis=-1)
+    extra["parity_max_rel_err_sampled_rows"] = float((num / np.maximum(np.abs(O_ref).max(axis=-1), 1e-6)).max())
+
+    if not args.no_extra:
+        # in-run dense MLA baseline (same kernel engine, plain causal mask)
+        O2 = torch.empty_like(O)
+        n_dense = 2 if wl.L > 65536 else 5
+        ms_dense = time_kernel(lambda: lca.dense_attn(d, run.Q, run.POOL, run.SEL, O2, None, run.ws), n_dense, 1)
+        dflops = 2.0 * (wl.d_qk + wl.d_v) * wl.B * wl.H * (wl.L * (wl.L + 1) // 2)
+        extra.update({"ms_dense_mla_attn": ms_dense, "dense_TFLOPs": dflops / (ms_dense * 1e-3) / 1e12,
+                      "speedup_vs_dense_mla": ms_dense / ms_per_step, "dense_tokens_per_s": wl.B * wl.L / (ms_dense * 1e-3)})
+        del O2
+        # variants: g = 32, and one condensed set per head (S = H)
+        for tag, kw in (("g32", dict(g=32)), ("per_head_sets", dict(S=wl.H))):
+            w2 = wl.with_(**kw)
+            d2 = hp.lca_desc(w2)
+            pr, sr, an, _ = lca.alloc_condensed(d2)
+            ws2 = lca.alloc_workspace(d2)
+            fc = lambda: lca.condense(d2, run.Q, run.POOL, run.SEL, pr, sr, an, None, ws2)
+            fa = lambda: lca.prefill_attn(d2, run.Q, run.POOL, run.SEL, pr, sr, O, None, ws2)
+            mc, ma = time_kernel(fc, 10, 2), time_kernel(fa, max(3, args.steps // 2), 1)
+            db, cb = lca.cache_bytes(d2)
+            fl = 2.0 * (w2.d_qk + w2.d_v) * w2.B * w2.H * pair_count(w2.L, w2.w, w2.g)
+            extra[tag] = {"ms_condense": mc, "ms_attn": ma, "tokens_per_s": w2.B * w2.L / ((mc + ma) * 1e-3),
+                          "attn_TFLOPs": fl / (ma * 1e-3) / 1e12, "condense_GBps": condense_bytes(w2) / (mc * 1e-3) / 1e9,
+                          "kv_cache_bytes_lca": cb, "kv_cache_saved_frac": 1.0 - cb / db}
+            del pr, sr, an
+
+    out = {
+        "metric": "LCA prefill tokens/s at 128K (MLA, 16 heads) + speedup vs dense MLA" if args.config == "cfg4"
+        else f"LCA prefill tokens/s ({wl.name})",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={wl.B} L={wl.L} H={wl.H} d_c={wl.d_pool} d_R={wl.d_sel} g={wl.g} w={wl.w} "
+                               f"S={wl.S} bf16, AR(1) rho=0.9 latents, RoPE keys, Gaussian queries; one attention layer",
+                   "step": "lca_condense + lca_prefill_attn"},
+        "roofline": {"bound": "mfma", "kernel": "attn_mfma_kernel (lca_prefill_attn)", "achieved": tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None},
+        "cpu_baseline": base,
+        "extra": extra,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

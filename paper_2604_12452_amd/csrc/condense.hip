@@ -297,10 +297,14 @@ __global__ __launch_bounds__(256) void condense_generic_kernel(const T *__restri
     float z = pmine;
     for (int mask = 32; mask >= 1; mask >>= 1) z += __shfl_xor(z, mask, WAVE);
     const float alpha = pmine / z;
-    for (int x = lane; x < d_pool; x += WAVE) {
+    for (int x0 = 0; x0 < d_pool; x0 += WAVE) {      // every lane takes part in the broadcasts
+        const int x = x0 + lane;
         float acc = 0.f;
-        for (int r = 0; r < g; ++r) acc = fmaf(__shfl(alpha, r, WAVE), Elt<T>::ld(pool_base + (size_t)(j * g + r) * P * d_pool + x), acc);
-        Elt<T>::st(pool_rep + (size_t)unit * d_pool + x, acc);
+        for (int r = 0; r < g; ++r) {
+            const float ar = __shfl(alpha, r, WAVE);
+            if (x < d_pool) acc = fmaf(ar, Elt<T>::ld(pool_base + (size_t)(j * g + r) * P * d_pool + x), acc);
+        }
+        if (x < d_pool) Elt<T>::st(pool_rep + (size_t)unit * d_pool + x, acc);
     }
     const int a_tok = j * g + brow;
     for (int x = lane; x < d_sel; x += WAVE) sel_rep[(size_t)unit * d_sel + x] = sel_base[(size_t)a_tok * P * d_sel + x];

@@ -14,6 +14,8 @@ rotation already applied), not of the method.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, replace
 
 import numpy as np
@@ -141,10 +143,11 @@ def rope(x: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
 
 def ar1(rng: np.random.Generator, n: int, width, rho: float) -> np.ndarray:
     """Stationary AR(1) along axis 0 with unit-variance Gaussian innovations: x_t = rho x_{t-1} + e_t."""
-    shape = (n,) + tuple(np.atleast_1d(width))
-    e = rng.standard_normal(shape)
-    e[0] /= np.sqrt(1.0 - rho * rho)
-    return lfilter([1.0], [1.0, -rho], e, axis=0)
+    wshape = tuple(int(x) for x in np.atleast_1d(width))
+    e = rng.standard_normal((int(np.prod(wshape)), n))        # time along the contiguous axis: fast filtering
+    e[:, 0] /= np.sqrt(1.0 - rho * rho)
+    x = lfilter([1.0], [1.0, -rho], e, axis=-1)
+    return np.ascontiguousarray(x.T).reshape((n,) + wshape)
 
 
 def gen_kv(wl: Workload, b: int):
@@ -183,7 +186,12 @@ def gen_q_rows(wl: Workload, b: int, t0: int, t1: int) -> np.ndarray:
 
 def gen_all(wl: Workload):
     """Full inputs in storage form: Q [B,L,H,d_qk], POOL, SEL ([B,L,d] MLA or [B,L,S,d] GQA)."""
-    Q = np.stack([gen_q_rows(wl, b, 0, wl.L) for b in range(wl.B)])
+    CH = 1024
+    jobs = [(b, t0, min(t0 + CH, wl.L)) for b in range(wl.B) for t0 in range(0, wl.L, CH)]
+    with ThreadPoolExecutor(max_workers=min(16, len(os.sched_getaffinity(0)))) as ex:
+        parts = list(ex.map(lambda j: gen_q_rows(wl, *j), jobs))
+    per_b = len(jobs) // wl.B
+    Q = np.stack([np.concatenate(parts[b * per_b:(b + 1) * per_b], axis=0) for b in range(wl.B)])
     kv = [gen_kv(wl, b) for b in range(wl.B)]
     return Q, np.stack([p for p, _ in kv]), np.stack([s for _, s in kv])
 

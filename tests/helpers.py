@@ -23,27 +23,7 @@ def vec_rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
     return float((num / den).max())
 
 
-def to_dev(a: np.ndarray, dtype: str):
-    import torch
-    if dtype == "bf16":
-        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
-    return torch.from_numpy(a).cuda()
-
-
-def from_dev(t, dtype: str) -> np.ndarray:
-    """Device tensor -> float64 numpy, exactly."""
-    import torch
-    if dtype == "bf16":
-        return inputs.to_f64(t.view(torch.int16).cpu().numpy().view(np.uint16), "bf16")
-    return t.cpu().numpy().astype(np.float64)
-
-
-def lca_desc(wl: inputs.Workload, **over):
-    from paper_2604_12452_amd import lca
-    kw = dict(B=wl.B, L=wl.L, H=wl.H, S=wl.S, d_pool=wl.d_pool, d_sel=wl.d_sel, g=wl.g, w=wl.w, n_q=wl.n_q, mode=wl.mode,
-              dtype=lca.BF16 if wl.dtype == "bf16" else lca.F32, scale=wl.scale)
-    kw.update(over)
-    return lca.Desc(**kw)
+from paper_2604_12452_amd.device import GpuRun, from_dev, lca_desc, to_dev  # noqa: E402,F401
 
 
 def oracle_desc(o, wl: inputs.Workload, **over):
@@ -51,42 +31,6 @@ def oracle_desc(o, wl: inputs.Workload, **over):
               scale=wl.scale)
     kw.update(over)
     return o.Desc(**kw)
-
-
-class GpuRun:
-    """Inputs of a workload on the device plus the outputs of the liblca calls made on them."""
-
-    def __init__(self, wl: inputs.Workload, Q: np.ndarray, POOL: np.ndarray, SEL: np.ndarray, rep_logit_bias: float = 0.0):
-        from paper_2604_12452_amd import lca
-        self.lca, self.wl = lca, wl
-        self.desc = lca_desc(wl, rep_logit_bias=rep_logit_bias)
-        self.Q, self.POOL, self.SEL = to_dev(Q, wl.dtype), to_dev(POOL, wl.dtype), to_dev(SEL, wl.dtype)
-        self.ws = lca.alloc_workspace(self.desc)
-
-    def condense(self, alpha: bool = True):
-        import torch
-        self.pool_rep, self.sel_rep, self.anchor, self.alpha = self.lca.alloc_condensed(self.desc, alpha=alpha)
-        self.lca.condense(self.desc, self.Q, self.POOL, self.SEL, self.pool_rep, self.sel_rep, self.anchor, self.alpha, self.ws)
-        torch.cuda.synchronize()
-        return self
-
-    def prefill(self, lse: bool = True):
-        import torch
-        d = self.desc
-        self.O = torch.full((d.B, d.L, d.H, d.d_pool), float("nan"), dtype=self.lca.torch_dtype(d), device="cuda")
-        self.lse = torch.full((d.B, d.L, d.H), float("nan"), dtype=torch.float32, device="cuda") if lse else None
-        self.lca.prefill_attn(d, self.Q, self.POOL, self.SEL, self.pool_rep, self.sel_rep, self.O, self.lse, self.ws)
-        torch.cuda.synchronize()
-        return self
-
-    def dense(self, lse: bool = True):
-        import torch
-        d = self.desc
-        self.O_dense = torch.full((d.B, d.L, d.H, d.d_pool), float("nan"), dtype=self.lca.torch_dtype(d), device="cuda")
-        self.lse_dense = torch.full((d.B, d.L, d.H), float("nan"), dtype=torch.float32, device="cuda") if lse else None
-        self.lca.dense_attn(d, self.Q, self.POOL, self.SEL, self.O_dense, self.lse_dense, self.ws)
-        torch.cuda.synchronize()
-        return self
 
 
 def check_condense(o, wl, run: GpuRun, Qf_tail, POOLf, SELf, tol=None):
@@ -136,9 +80,18 @@ def check_prefill(o, wl, run: GpuRun, rows, Qf_rows, POOLf, SELf, ref_cond, diff
     sel3 = ref_cond["sel_rep"].copy()
     if differ.any():
         sel3[differ] = sr[differ]
-    O3 = o.lca_attn_rows(od, rows, Qf_rows, POOLf, SELf, ref_cond["pool_rep"], sel3)
+    # The cache is stored in the model's 16-bit type (the paper's implementation note on bf16/fp16), so
+    # the end-to-end oracle rounds its fp64 representatives once to the storage type before attention.
+    pool3 = inputs.to_f64(inputs.to_storage(ref_cond["pool_rep"], wl.dtype), wl.dtype)
+    O3 = o.lca_attn_rows(od, rows, Qf_rows, POOLf, SELf, pool3, sel3)
     e3 = vec_rel_err(O_gpu, O3)
     assert e3 <= tol, f"stage 3 (end to end) rel err {e3:.3e} > {tol}"
+    if wl.d_pool >= 128:
+        # Against an oracle that never rounds its cache the two 16-bit stores (cache, output; unit roundoff
+        # 2^-8 each) alone can reach 0.78 % of a component, so this looser comparison is gated at 2x the bar.
+        O4 = o.lca_attn_rows(od, rows, Qf_rows, POOLf, SELf, ref_cond["pool_rep"], sel3)
+        e4 = vec_rel_err(O_gpu, O4)
+        assert e4 <= 2 * tol, f"stage 3 against the unrounded fp64 cache: rel err {e4:.3e} > {2 * tol}"
     return e2, e3
 
 

@@ -47,7 +47,7 @@ def test_generic_kernels_small_shapes(oracle, dtype, mode, L, g, w, H, S):
     _full_parity(oracle, _wl("generic", L=L, g=g, w=w, H=H, S=S, dtype=dtype, mode=mode, d_pool=24, d_sel=16, B=2))
 
 
-@pytest.mark.parametrize("L,w,g", [(40, 64, 4), (10, 8, 4), (1, 0, 1), (5, 0, 8)])
+@pytest.mark.parametrize("L,w,g", [(40, 64, 4), (10, 8, 4), (1, 1, 1), (5, 0, 8)])
 def test_no_groups_falls_back_to_dense(oracle, L, w, g):
     wl = _wl("short", L=L, w=w, g=min(g, 8), n_q=1)
     assert wl.m == 0
