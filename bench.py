@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--config", default="cfg4", help="cfg2 | cfg3 | cfg4 (default, the metric's workload)")
     ap.add_argument("--oracle-rows", type=int, default=512)
     ap.add_argument("--no-extra", action="store_true", help="skip dense baseline and variants (profiling runs)")
+    ap.add_argument("--pmc-calib", action="store_true",
+                    help="also run one 1 GiB device-to-device copy, the known-size kernel the HBM counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives in this path)")
@@ -119,6 +121,13 @@ def main():
     def step():
         f_cond()
         f_attn()
+
+    if args.pmc_calib:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the timed region: W warm-up steps, then exactly K steps between synchronisations ----
     for _ in range(args.warmup):
@@ -189,7 +198,7 @@ def main():
         "config": {"workload": f"{wl.name}: B={wl.B} L={wl.L} H={wl.H} d_c={wl.d_pool} d_R={wl.d_sel} g={wl.g} w={wl.w} "
                                f"S={wl.S} bf16, AR(1) rho=0.9 latents, RoPE keys, Gaussian queries; one attention layer",
                    "step": "lca_condense + lca_prefill_attn"},
-        "roofline": {"bound": "mfma", "kernel": "attn_mfma_kernel (lca_prefill_attn)", "achieved": tflops,
+        "roofline": {"bound": "mfma", "kernel": "attn_mla_kernel (lca_prefill_attn)", "achieved": tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None},
         "cpu_baseline": base,
         "extra": extra,

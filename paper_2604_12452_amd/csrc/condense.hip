@@ -3,7 +3,7 @@
 //   summary_query_kernel   qbar = mean of the last n_q queries (and of the heads of a set)
 //   condense_reg_kernel    one wavefront per group, the group's rows held in registers; scores by
 //                          per-lane partial dots + a reduce-scatter butterfly, online softmax over
-//                          sub-blocks of <= 16 rows, pooling in-lane, anchor by (score, index) max.
+//                          sub-blocks of <= 8 rows, pooling in-lane, anchor by (score, index) max.
 //                          HBM-bound: every C^KV / K^R byte is read once, as 16-byte coalesced loads.
 //   condense_generic_kernel  any sizes, scalar loads; fallback for shapes without an instantiation.
 //
@@ -60,18 +60,34 @@ template <> struct Elt<float> {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Summary query: qbar[b,s,x] = mean over t in [L-n_q, L), h in set s of Q[b,t,h,x]   (fixed order)
+// Summary query: qbar[b,s,x] = mean over t in [L-n_q, L), h in set s of Q[b,t,h,x].
+// One workgroup per (b, s, 64 columns); its 4 wavefronts split the (t, h) list, each with 8 independent
+// loads in flight, and are merged in a fixed order through LDS.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-__global__ void summary_query_kernel(const T *__restrict__ Q, float *__restrict__ qbar, int L, int H, int S, int d_qk, int n_q)
+__global__ __launch_bounds__(256) void summary_query_kernel(const T *__restrict__ Q, float *__restrict__ qbar, int L, int H, int S, int d_qk, int n_q)
 {
-    const int b = blockIdx.x / S, s = blockIdx.x % S, hps = H / S;
-    for (int x = threadIdx.x; x < d_qk; x += blockDim.x) {
-        float acc = 0.f;
-        for (int t = L - n_q; t < L; ++t)
-            for (int h = s * hps; h < (s + 1) * hps; ++h) acc += Elt<T>::ld(Q + (((size_t)b * L + t) * H + h) * d_qk + x);
-        qbar[(size_t)blockIdx.x * d_qk + x] = acc / (float)(n_q * hps);
+    __shared__ float part[4][WAVE];
+    const int xblocks = (d_qk + WAVE - 1) / WAVE;
+    const int bs = blockIdx.x / xblocks, xb = blockIdx.x % xblocks;
+    const int b = bs / S, s = bs % S, hps = H / S;
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    const int x = xb * WAVE + lane;
+    const int n = n_q * hps;                       // (t, h) pairs, pair u -> t = L - n_q + u / hps, h = s*hps + u % hps
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (x < d_qk) {
+        for (int u0 = wave * 8; u0 < n; u0 += 32) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int u = u0 + i;
+                if (u < n) a[i] += Elt<T>::ld(Q + (((size_t)b * L + (L - n_q + u / hps)) * H + s * hps + u % hps) * d_qk + x);
+            }
+        }
     }
+    part[wave][lane] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+    __syncthreads();
+    if (wave == 0 && x < d_qk)
+        qbar[(size_t)bs * d_qk + x] = ((part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane])) / (float)n;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -105,22 +121,26 @@ __device__ __forceinline__ float wave_reduce_scatter(float (&v)[R], int lane)
 
 // ---------------------------------------------------------------------------------------------
 // Register-resident condensation: one wave per (sequence, KV source, group).
+//   pool part : lane l owns 16-byte chunk l of every row of the sub-block (R <= 8 rows in registers)
+//   sel part  : lane l owns row (l >> SH) and every (64/R)-th chunk of it, so its partial dot already
+//               sits with the lane that receives that row's score from the reduce-scatter
 // ---------------------------------------------------------------------------------------------
 template <typename T, int DP, int DS, int G, bool MLA>
-__global__ __launch_bounds__(256) void condense_reg_kernel(const T *__restrict__ POOL, const T *__restrict__ SEL,
-                                                           const float *__restrict__ qbar, T *__restrict__ pool_rep,
-                                                           T *__restrict__ sel_rep, int32_t *__restrict__ anchor,
-                                                           float *__restrict__ alpha_dbg, int B, int L, int S, int m, float scale)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8)))
+void condense_reg_kernel(const T *__restrict__ POOL, const T *__restrict__ SEL, const float *__restrict__ qbar,
+                         T *__restrict__ pool_rep, T *__restrict__ sel_rep, int32_t *__restrict__ anchor,
+                         float *__restrict__ alpha_dbg, int B, int L, int S, int m, float scale)
 {
     constexpr int EPC = Elt<T>::EPC;
-    constexpr int NCP = DP / EPC, NCS = DS / EPC, NC = NCP + NCS;
-    constexpr int NSLOT = (NC + WAVE - 1) / WAVE;
-    constexpr int R = G < 16 ? G : 16;          // rows per sub-block
+    constexpr int NCP = DP / EPC, NCS = DS / EPC;
+    constexpr int R = G < 8 ? G : 8;            // rows per sub-block (8 keeps three wavefronts per SIMD resident)
     constexpr int NSB = G / R;
-    constexpr int LOG2R = R == 16 ? 4 : R == 8 ? 3 : R == 4 ? 2 : R == 2 ? 1 : 0;
+    constexpr int LOG2R = R == 8 ? 3 : R == 4 ? 2 : R == 2 ? 1 : 0;
     constexpr int SH = 6 - LOG2R;               // lane l holds the score of sub-block row l >> SH
+    constexpr int LPR = 1 << SH;                // lanes per row for the sel part
+    constexpr int SPL = (NCS + LPR - 1) / LPR;  // sel chunks per lane
     constexpr int DQK = MLA ? DP + DS : DS;
-    static_assert(G % R == 0 && DP % EPC == 0 && DS % EPC == 0, "shape");
+    static_assert(G % R == 0 && DP % EPC == 0 && DS % EPC == 0 && NCP <= WAVE, "shape");
 
     const int lane = threadIdx.x & (WAVE - 1);
     const long wave_id = (long)blockIdx.x * (blockDim.x / WAVE) + (threadIdx.x / WAVE);
@@ -131,74 +151,73 @@ __global__ __launch_bounds__(256) void condense_reg_kernel(const T *__restrict__
 
     const T *pool_base = POOL + ((size_t)b * L * P + p) * DP;   // row i at + i * P * DP
     const T *sel_base = SEL + ((size_t)b * L * P + p) * DS;
-
-    // which 16-byte chunk of a row this lane owns in each slot
-    bool is_pool[NSLOT], is_sel[NSLOT];
-    int col[NSLOT];
-#pragma unroll
-    for (int sl = 0; sl < NSLOT; ++sl) {
-        const int c = sl * WAVE + lane;
-        is_pool[sl] = c < NCP;
-        is_sel[sl] = c >= NCP && c < NC;
-        col[sl] = is_pool[sl] ? c * EPC : (c - NCP) * EPC;
-    }
+    const bool has_pool = lane < NCP;
+    const int pcol = (has_pool ? lane : 0) * EPC;
+    const int my_row = lane >> SH, sub = lane & (LPR - 1);
 
     const int s_begin = MLA ? 0 : p, s_end = MLA ? S : p + 1;
     for (int s = s_begin; s < s_end; ++s) {
-        // this lane's slice of the summary query
-        float qv[NSLOT][EPC];
         const float *qb = qbar + ((size_t)b * S + s) * DQK;
-#pragma unroll
-        for (int sl = 0; sl < NSLOT; ++sl) {
-            const bool used = MLA ? (is_pool[sl] || is_sel[sl]) : is_sel[sl];
-            const int qoff = is_pool[sl] ? col[sl] : (MLA ? DP + col[sl] : col[sl]);
-#pragma unroll
-            for (int e = 0; e < EPC; ++e) qv[sl][e] = used ? qb[qoff + e] : 0.f;
-        }
-
         float m_run = -INFINITY, l_run = 0.f;
-        float acc[NSLOT][EPC];
+        float acc[EPC];
 #pragma unroll
-        for (int sl = 0; sl < NSLOT; ++sl)
-#pragma unroll
-            for (int e = 0; e < EPC; ++e) acc[sl][e] = 0.f;
+        for (int e = 0; e < EPC; ++e) acc[e] = 0.f;
         float best_score = -INFINITY;
         int best_row = 0;
-        float sc_keep[NSB];
+        const size_t unit = ((size_t)b * S + s) * m + j;
 
-#pragma unroll
+#pragma unroll 1
         for (int sb = 0; sb < NSB; ++sb) {
             const int row0 = j * G + sb * R;
-            uint4 data[R][NSLOT];
+            // issue every load of the sub-block first
+            uint4 pdata[R], sdata[SPL];
 #pragma unroll
             for (int r = 0; r < R; ++r)
+                pdata[r] = has_pool ? *reinterpret_cast<const uint4 *>(pool_base + (size_t)(row0 + r) * P * DP + pcol) : make_uint4(0, 0, 0, 0);
 #pragma unroll
-                for (int sl = 0; sl < NSLOT; ++sl) {
-                    data[r][sl] = make_uint4(0, 0, 0, 0);
-                    if (is_pool[sl]) data[r][sl] = *reinterpret_cast<const uint4 *>(pool_base + (size_t)(row0 + r) * P * DP + col[sl]);
-                    else if (is_sel[sl]) data[r][sl] = *reinterpret_cast<const uint4 *>(sel_base + (size_t)(row0 + r) * P * DS + col[sl]);
-                }
-            // partial dots of every row with this lane's slice of qbar
-            float part[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                float a = 0.f;
-#pragma unroll
-                for (int sl = 0; sl < NSLOT; ++sl) {
-                    float f[EPC];
-                    Elt<T>::unpack(data[r][sl], f);
-#pragma unroll
-                    for (int e = 0; e < EPC; ++e) a = fmaf(f[e], qv[sl][e], a);
-                }
-                part[r] = a;
+            for (int i = 0; i < SPL; ++i) {
+                const int c = sub + i * LPR;
+                sdata[i] = c < NCS ? *reinterpret_cast<const uint4 *>(sel_base + (size_t)(row0 + my_row) * P * DS + c * EPC) : make_uint4(0, 0, 0, 0);
             }
-            const float score = scale * wave_reduce_scatter<R>(part, lane);   // row (lane >> SH) of this sub-block
-            sc_keep[sb] = score;
+            // sel part of the score: this lane's chunks of its own row, summed over the row's lanes
+            float ssum = 0.f;
+#pragma unroll
+            for (int i = 0; i < SPL; ++i) {
+                const int c = sub + i * LPR;
+                if (c < NCS) {
+                    float f[EPC];
+                    Elt<T>::unpack(sdata[i], f);
+                    const float *qs = qb + (MLA ? DP : 0) + c * EPC;
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e) ssum = fmaf(f[e], qs[e], ssum);
+                }
+            }
+#pragma unroll
+            for (int mask = LPR >> 1; mask >= 1; mask >>= 1) ssum += __shfl_xor(ssum, mask, WAVE);
+            float dot = ssum;
+            if (MLA) {   // pool part of the score: per-lane partial dots of all rows, reduce-scattered
+                float qp[EPC];
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) qp[e] = has_pool ? qb[pcol + e] : 0.f;
+                float part[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float f[EPC];
+                    Elt<T>::unpack(pdata[r], f);
+                    float a = 0.f;
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e) a = fmaf(f[e], qp[e], a);
+                    part[r] = a;
+                }
+                dot += wave_reduce_scatter<R>(part, lane);
+            }
+            const float score = scale * dot;              // row my_row of this sub-block
+            if (alpha_dbg != nullptr && sub == 0) alpha_dbg[unit * G + sb * R + my_row] = score;   // normalised below
             // sub-block maximum and its lowest row
             float bmax = score;
-            int brow = lane >> SH;
+            int brow = my_row;
 #pragma unroll
-            for (int mask = 32; mask >= (1 << SH); mask >>= 1) {
+            for (int mask = 32; mask >= LPR; mask >>= 1) {
                 const float os = __shfl_xor(bmax, mask, WAVE);
                 const int orow = __shfl_xor(brow, mask, WAVE);
                 if (os > bmax || (os == bmax && orow < brow)) { bmax = os; brow = orow; }
@@ -210,47 +229,36 @@ __global__ __launch_bounds__(256) void condense_reg_kernel(const T *__restrict__
             const float pmine = __expf(score - m_new);
             l_run *= corr;
 #pragma unroll
-            for (int sl = 0; sl < NSLOT; ++sl)
-#pragma unroll
-                for (int e = 0; e < EPC; ++e) acc[sl][e] *= corr;
+            for (int e = 0; e < EPC; ++e) acc[e] *= corr;
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const float pr = readlane_f(pmine, r << SH);
                 l_run += pr;
+                float f[EPC];
+                Elt<T>::unpack(pdata[r], f);
 #pragma unroll
-                for (int sl = 0; sl < NSLOT; ++sl) {
-                    if (sl * WAVE < NCP) {               // slots that can hold pool chunks
-                        float f[EPC];
-                        Elt<T>::unpack(data[r][sl], f);
-#pragma unroll
-                        for (int e = 0; e < EPC; ++e) acc[sl][e] = fmaf(pr, f[e], acc[sl][e]);
-                    }
-                }
+                for (int e = 0; e < EPC; ++e) acc[e] = fmaf(pr, f[e], acc[e]);
             }
             m_run = m_new;
         }
 
-        const size_t unit = ((size_t)b * S + s) * m + j;
         const float inv_l = 1.f / l_run;
+        if (has_pool) {
+            float o[EPC];
 #pragma unroll
-        for (int sl = 0; sl < NSLOT; ++sl) {
-            if (sl * WAVE < NCP && is_pool[sl]) {
-                float o[EPC];
-#pragma unroll
-                for (int e = 0; e < EPC; ++e) o[e] = acc[sl][e] * inv_l;
-                *reinterpret_cast<uint4 *>(pool_rep + unit * DP + col[sl]) = Elt<T>::pack(o);
-            }
+            for (int e = 0; e < EPC; ++e) o[e] = acc[e] * inv_l;
+            *reinterpret_cast<uint4 *>(pool_rep + unit * DP + pcol) = Elt<T>::pack(o);
         }
         const int a_tok = j * G + best_row;
-#pragma unroll
-        for (int sl = 0; sl < NSLOT; ++sl)
-            if (is_sel[sl])
-                *reinterpret_cast<uint4 *>(sel_rep + unit * DS + col[sl]) =
-                    *reinterpret_cast<const uint4 *>(sel_base + (size_t)a_tok * P * DS + col[sl]);
+        if (lane < NCS)
+            *reinterpret_cast<uint4 *>(sel_rep + unit * DS + lane * EPC) =
+                *reinterpret_cast<const uint4 *>(sel_base + (size_t)a_tok * P * DS + lane * EPC);
         if (lane == 0) anchor[unit] = a_tok;
-        if (alpha_dbg != nullptr && (lane & ((1 << SH) - 1)) == 0) {
-#pragma unroll
-            for (int sb = 0; sb < NSB; ++sb) alpha_dbg[unit * G + sb * R + (lane >> SH)] = __expf(sc_keep[sb] - m_run) * inv_l;
+        if (alpha_dbg != nullptr && sub == 0) {      // each lane turns the scores it wrote into weights
+            for (int sb = 0; sb < NSB; ++sb) {
+                float *ap = alpha_dbg + unit * G + sb * R + my_row;
+                *ap = __expf(*ap - m_run) * inv_l;
+            }
         }
     }
 }
@@ -355,10 +363,11 @@ hipError_t launch_condense(const CondenseArgs &a, hipStream_t st)
 {
     const Dims &d = a.d;
     // 1. summary query (Algorithm 1, first step)
+    const int sq_blocks = d.B * d.S * ((d.d_qk + WAVE - 1) / WAVE);
     if (d.dtype == LCA_BF16)
-        summary_query_kernel<uint16_t><<<d.B * d.S, 256, 0, st>>>((const uint16_t *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
+        summary_query_kernel<uint16_t><<<sq_blocks, 256, 0, st>>>((const uint16_t *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
     else
-        summary_query_kernel<float><<<d.B * d.S, 256, 0, st>>>((const float *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
+        summary_query_kernel<float><<<sq_blocks, 256, 0, st>>>((const float *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || d.m == 0) return err;
     // 2. groups

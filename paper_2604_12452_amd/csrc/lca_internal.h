@@ -46,6 +46,8 @@ struct DecodeArgs {
 // Launchers return hipSuccess or the launch error. They assume validated arguments.
 hipError_t launch_condense(const CondenseArgs &a, hipStream_t st);
 hipError_t launch_attn_simple(const AttnArgs &a, hipStream_t st);
+bool attn_mla_supported(const Dims &d);
+hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st);
 bool attn_mfma_supported(const Dims &d);
 hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t st);
 bool decode_supported(const Dims &d);
