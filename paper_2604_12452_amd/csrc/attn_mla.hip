@@ -6,17 +6,22 @@
 // and the whole 512-wide output, one wavefront per SIMD with the full 512-register budget:
 //   Q^T fragments   144 VGPRs (held for the whole kernel)
 //   O^T accumulator 256 AGPRs (16 tiles of 32 value columns x 32 queries)
-// Key tiles of 64 entries x 576 columns are copied global -> LDS by direct-to-LDS loads into two
-// 73 KB stages (row stride 73 x 16 B: odd in 16-byte units, so row-strided 16-byte reads spread over
-// all banks); the copy of tile i+1 runs while tile i is consumed.  A tile is used twice from LDS: all
-// 576 columns as keys, the first 512 as values — the absorbed MLA form needs no separate value tile.
+// Key tiles of 32 entries x 576 columns are copied global -> LDS by direct-to-LDS loads into four
+// 36.5 KB stages (row = 1024 B latent + 128 B RoPE key + 16 B pad: an odd number of 16-byte units, so
+// row-strided 16-byte reads spread over all banks); copies run three tiles ahead of their use.  A tile
+// is used twice from LDS: all 576 columns as keys, the first 512 as values — the absorbed MLA form
+// needs no separate value tile.
 //
 // Products are computed transposed so that nothing changes lanes between the two MFMA stages:
 //   S^T[key, query]  = K Q^T       A = key rows from LDS (16-byte reads), B = Q^T in registers
-//   O^T[dv, query]  += V^T P^T     A = V^T through LDS transpose reads,   B = P^T = exp2(S^T - max)
+//   O^T[dv, query]  += V^T P^T     A = V^T through LDS transpose reads,   B = P^T = exp2(S^T - ref)
 // In the 32x32 accumulator layout lane l holds query l%32, so softmax statistics are per-lane scalars
 // and the S^T registers already are the B fragments of the second product when the V^T operand
 // enumerates keys in accumulator order.
+//
+// Software pipeline: while the matrix core runs the S^T chain of tile t+1, the vector ALU turns the
+// S^T of tile t into P^T (its instructions are placed between the MFMAs of the chain); then the O^T
+// update of tile t runs.  One workgroup barrier per tile.
 //
 // Softmax reference: each query row fixes its reference maximum at the first key tile it sees and keeps
 // it; numerator and denominator use the same reference, so the result does not depend on it, and O^T is
@@ -34,17 +39,18 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 #define LCA_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define LCA_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define LCA_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 constexpr int DP = 512, DS = 64, DQK = 576, DV = 512;
 constexpr int BM = 128;                 // query rows per workgroup
-constexpr int BN = 64;                  // entries per key tile (two 32-entry halves)
-constexpr int CPR = 73;                 // 16-byte chunks per LDS row: 64 pool + 8 sel + 1 pad
-constexpr int RSB = CPR * 16;           // LDS row stride in bytes
-constexpr int STAGE_CHUNKS = BN * CPR;  // 4672 = 73 wave-wide copies of 64 chunks
+constexpr int BN = 32;                  // entries per key tile
+constexpr int NSTAGE = 4;
+constexpr int RSB = 1168;               // LDS row stride in bytes: 1024 + 128 + 16
+constexpr int STAGE_BYTES = BN * RSB;   // 37 376
 constexpr int NKS = DQK / 16;           // 36 k-steps of S^T
 constexpr int NDV = DV / 32;            // 16 value tiles
-constexpr float NEG_BIG = -1.0e30f;     // stands for -inf in the running maximum (keeps exp2 arguments finite)
-constexpr float HEADROOM = 60.0f;        // base-2 exponent headroom above the reference before a pass is repeated
+constexpr float NEG_BIG = -1.0e30f;     // stands for -inf in running maxima (keeps exp2 arguments finite)
+constexpr float HEADROOM = 60.0f;       // base-2 exponent headroom above the reference before a pass is repeated
 
 struct MlaParams {
     const uint16_t *Q, *POOL, *SEL, *pool_rep, *sel_rep;
@@ -57,25 +63,121 @@ struct MlaParams {
 // key row held in accumulator register r of lane group G (lanes 32G..32G+31) of a 32x32 tile
 __device__ __forceinline__ int acc_row(int r, int G) { return 8 * (r >> 2) + 4 * G + (r & 3); }
 
-// Copy one 64-entry tile into an LDS stage. Entry rows past the segment end are clamped (masked later).
-__device__ __forceinline__ void issue_tile_copy(uint4 *stage, const uint16_t *pbase, const uint16_t *sbase, int e0, int seg_end,
-                                                int wave, int lane)
+// per-lane softmax state (base-2 logits): reference, running sum over this lane's keys, largest seen
+struct RowState {
+    float m_ref, l_run, m_seen;
+    bool exceeded;
+};
+
+// S^T chain of one tile (36 MFMAs into `snext`, key fragments prefetched four deep) and, when SOFTMAX,
+// the vector work that turns the previous tile's S^T (`scur`) into P^T fragments, spread over the
+// chain's issue slots.  `kb` = LDS address of this lane's first key fragment of the chain's tile.
+// The MFMAs are inline assembly so that their accumulator is an ordinary vector register tuple (all 256
+// accumulation registers belong to O^T); the wait states an MFMA result needs before vector
+// instructions read it are spent explicitly at the end of the chain.
+template <bool CHAIN, bool SOFTMAX>
+__device__ __forceinline__ void chain_and_softmax(const char *kb, const bf16x8 (&qf)[NKS], floatx16 &snext, const floatx16 &scur,
+                                                  bf16x8 (&pb)[2], RowState &st, float c, float bias)
 {
-    for (int i = wave; i < CPR; i += 4) {            // 73 wave-wide copies, 1 KB of LDS each
-        const int pos = i * 64 + lane;
-        const int r = pos / CPR, c = pos - r * CPR;
-        const int e = min(e0 + r, seg_end - 1);
-        const uint16_t *src = c < 64 ? pbase + (size_t)e * DP + c * 8 : sbase + (size_t)e * DS + ((c - 64) & 7) * 8;
-        __builtin_amdgcn_global_load_lds(LCA_GLB_PTR(src), LCA_LDS_PTR(stage + i * 64), 16, 0, 0);
+    bf16x8 fr[4];
+    if (CHAIN) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fr[i] = *reinterpret_cast<const bf16x8 *>(kb + i * 32);
     }
+    float mx[6], nb = 0.f, p[16];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+        LCA_FENCE();
+        if (CHAIN) {
+            if (ks == 0)
+                asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(snext) : "v"(fr[0]), "v"(qf[0]));
+            else
+                asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(snext) : "v"(fr[ks & 3]), "v"(qf[ks]));
+            if (ks + 4 < NKS) fr[ks & 3] = *reinterpret_cast<const bf16x8 *>(kb + (ks + 4) * 32);
+        }
+        if (SOFTMAX) {
+            // slots 0..4: maxima of triples; 5..7: reduce and scale; 8: partner lane; 9: reference; 10..25: exponentials
+            if (ks < 5) mx[ks] = fmaxf(fmaxf(scur[3 * ks], scur[3 * ks + 1]), scur[3 * ks + 2]);
+            if (ks == 5) mx[5] = fmaxf(fmaxf(mx[0], mx[1]), mx[2]);
+            if (ks == 6) mx[0] = fmaxf(fmaxf(mx[3], mx[4]), scur[15]);
+            if (ks == 7) mx[0] = fmaxf(fmaf(fmaxf(mx[5], mx[0]), c, bias), NEG_BIG);
+            if (ks == 8) mx[0] = fmaxf(mx[0], __shfl_xor(mx[0], 32, 64));
+            if (ks == 9) {
+                st.m_ref = (st.m_ref == NEG_BIG) ? mx[0] : st.m_ref;     // first visible keys of this row fix its reference
+                st.m_seen = fmaxf(st.m_seen, mx[0]);
+                st.exceeded |= mx[0] > st.m_ref + HEADROOM;
+                nb = bias - st.m_ref;
+            }
+            if (ks >= 10 && ks < 26) {
+                const int r = ks - 10;
+                p[r] = __builtin_amdgcn_exp2f(fmaf(scur[r], c, nb));
+                st.l_run += p[r];
+                if (r & 1) {
+                    pb[r >> 3][(r & 7) - 1] = (__bf16)p[r - 1];
+                    pb[r >> 3][r & 7] = (__bf16)p[r];
+                }
+            }
+        }
+    }
+    LCA_FENCE();
+    if (CHAIN) asm("s_nop 15\n\ts_nop 7" : "+v"(snext));
+}
+
+// What one wavefront needs to copy its rows of a key tile.
+struct CopyDesc {
+    const uint16_t *pool, *sel;   // first row of the segment (representatives or raw tokens)
+    int e0, last;                 // first entry of the tile, last valid entry of the segment
+};
+
+// Copy a tile into an LDS stage: this wavefront moves rows wave, wave+4, ... with one 1 KB and one 128 B
+// direct-to-LDS load per row (16 loads per tile and wavefront — the count the vmcnt waits rely on).
+// Rows past the end of the segment are clamped here and masked later.
+__device__ __forceinline__ void issue_copy(char *stage, const CopyDesc &cd, int wave, int lane)
+{
+#pragma unroll
+    for (int j = 0; j < BN / 4; ++j) {
+        const int r = wave + 4 * j;
+        const int e = min(cd.e0 + r, cd.last);
+        __builtin_amdgcn_global_load_lds(LCA_GLB_PTR(cd.pool + (size_t)e * DP + lane * 8), LCA_LDS_PTR(stage + r * RSB), 16, 0, 0);
+        if (lane < 8)
+            __builtin_amdgcn_global_load_lds(LCA_GLB_PTR(cd.sel + (size_t)e * DS + lane * 8), LCA_LDS_PTR(stage + r * RSB + 1024), 16, 0, 0);
+    }
+}
+
+// O^T += V^T P^T for one tile; vp = this lane's transpose-read address in the tile's stage.
+__device__ __forceinline__ void pv_update(const char *vp0, const bf16x8 (&pb)[2], floatx16 (&acc)[NDV])
+{
+#pragma unroll
+    for (int dvt = 0; dvt < NDV; ++dvt) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const char *vp = vp0 + kk * 16 * RSB + dvt * 64;
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(vp));
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(vp + 8 * RSB));
+            const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            acc[dvt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kk], acc[dvt], 0, 0, 0);
+        }
+    }
+}
+
+// One pipeline step.  The three stages are distinct (restrict): the copy in flight into `dma_stage` must
+// not make reads of the other two wait for it.
+__device__ __forceinline__ void tile_step(bool do_copy, char *__restrict__ dma_stage, const char *__restrict__ chain_stage,
+                                          const char *__restrict__ pv_stage, const CopyDesc &cd, int wave, int lane, int k_off, int v_off,
+                                          const bf16x8 (&qf)[NKS], floatx16 &snext, const floatx16 &scur, bf16x8 (&pb)[2], RowState &st,
+                                          float c, float bias, floatx16 (&acc)[NDV])
+{
+    if (do_copy) issue_copy(dma_stage, cd, wave, lane);
+    chain_and_softmax<true, true>(chain_stage + k_off, qf, snext, scur, pb, st, c, bias);
+    pv_update(pv_stage + v_off, pb, acc);
 }
 
 __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
 {
-    __shared__ __attribute__((aligned(16))) uint4 stage0[STAGE_CHUNKS];
-    __shared__ __attribute__((aligned(16))) uint4 stage1[STAGE_CHUNKS];
+    __shared__ __attribute__((aligned(16))) char stages[NSTAGE][STAGE_BYTES];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, G = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, G = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // Workgroup -> (sequence, head, query block): ids with equal id%8 (same XCD under round-robin
     // dispatch) walk the heads of one query block back to back, heaviest blocks first.
@@ -107,11 +209,19 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
     const uint16_t *raw_pool = kp.POOL + (size_t)b * L * DP;
     const uint16_t *raw_sel = kp.SEL + (size_t)b * L * DS;
 
-    auto copy_tile = [&](int tl, uint4 *stage) {
+    auto copy_desc = [&](int tl) {
         const bool is_rep = tl < n_rep_tiles;
-        const int e0 = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
-        issue_tile_copy(stage, is_rep ? rep_pool : raw_pool, is_rep ? rep_sel : raw_sel, e0, is_rep ? mt_blk_hi : t_last + 1, wave, lane);
+        CopyDesc cd;
+        cd.pool = is_rep ? rep_pool : raw_pool;
+        cd.sel = is_rep ? rep_sel : raw_sel;
+        cd.e0 = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
+        cd.last = (is_rep ? mt_blk_hi : t_last + 1) - 1;
+        return cd;
     };
+
+    // per-lane LDS byte offsets
+    const int k_off = n * RSB + G * 16;                                              // S^T: key row n, 16-byte chunk G
+    const int v_off = (4 * G + ((lane & 15) >> 2)) * RSB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;   // V^T transpose read
 
     // Q^T fragments: lane (n, G) holds Q[t_row, ks*16 + 8G .. +7]
     bf16x8 qf[NKS];
@@ -121,111 +231,64 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
     }
 
-    // per-lane LDS byte offsets
-    const int k_off = n * RSB + G * 16;                                              // S^T: key row n, 16-byte chunk G
-    const int v_off = (4 * G + ((lane & 15) >> 2)) * RSB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;   // V^T transpose read
-
     floatx16 acc[NDV];
-    float m_ref, l_run, m_seen;              // reference / running sum of this lane's keys / largest logit seen (base 2)
+    RowState st;
     float m_init = NEG_BIG;
-    bool exceeded;
+    const float c = kp.scale_log2;
+
 restart:
 #pragma unroll
     for (int i = 0; i < NDV; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-    m_ref = m_init; l_run = 0.f; m_seen = NEG_BIG; exceeded = false;
-    copy_tile(0, stage0);
+    st.m_ref = m_init; st.l_run = 0.f; st.m_seen = NEG_BIG; st.exceeded = false;
+
+    // prologue: three tiles in flight, then the S^T chain of tile 0
+    for (int tl = 0; tl < min(3, n_tiles); ++tl) issue_copy(stages[tl], copy_desc(tl), wave, lane);
+    floatx16 snext, scur;
+    bf16x8 pb[2];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    chain_and_softmax<true, false>(stages[0] + k_off, qf, snext, snext, pb, st, c, 0.f);
 
     for (int tl = 0; tl < n_tiles; ++tl) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's share of tile tl has landed
-        __syncthreads();                                   // ... and everyone else's; tile tl-1 is fully consumed
-        const char *cur = reinterpret_cast<const char *>((tl & 1) ? stage1 : stage0);
-        if (tl + 1 < n_tiles) copy_tile(tl + 1, (tl & 1) ? stage0 : stage1);
-
+        // tile tl+1 has landed: its copy was issued two iterations ago, only tile tl+2's 16 loads may be pending ...
+        if (tl + 2 < n_tiles) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();      // ... for every wavefront, and every wavefront is done with tile tl-1
         const bool is_rep = tl < n_rep_tiles;
-        const int e_tile = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
+        const int e0 = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
         const float bias = is_rep ? kp.bias_log2 : 0.f;
-
-#pragma unroll 1
-        for (int half = 0; half < 2; ++half) {
-            const int e0 = e_tile + half * 32;
-            // skip halves no row of this wavefront can see (wave-uniform)
-            const bool none = is_rep ? (e0 >= mt_w_hi) : (e0 > t_wlast || e0 + 32 <= mt_w_lo * g);
-            if (none) continue;
-            const bool full = is_rep ? (e0 + 32 <= mt_w_lo) : (e0 + 31 <= t_wfirst && e0 >= mt_w_hi * g);
-            const char *kbase = cur + half * 32 * RSB;
-
-            // ---- S^T = K Q^T ----
-            // Written as inline assembly so that this accumulator is an ordinary vector register tuple: all
-            // 256 accumulation registers belong to O^T.  The chain reuses one destination back to back; the
-            // wait states an MFMA result needs before ordinary vector instructions read it are spent explicitly.
-            floatx16 sacc;
-            {
-                const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(kbase + k_off);
-                asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(sacc) : "v"(a0), "v"(qf[0]));
-            }
-#pragma unroll
-            for (int ks = 1; ks < NKS; ++ks) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kbase + k_off + ks * 32);
-                asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(sacc) : "v"(a), "v"(qf[ks]));
-            }
-            asm("s_nop 15\n\ts_nop 7" : "+v"(sacc));
-
-            // ---- scaled base-2 logits, mask, maximum ----
-            float tmax = NEG_BIG;
+        scur = snext;
+        // boundary tiles: hide the entries this row must not see
+        const bool full = is_rep ? (e0 + BN <= mt_w_lo) : (e0 + BN - 1 <= t_wfirst && e0 >= mt_w_hi * g);
+        if (!full) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                float v = fmaf(sacc[r], kp.scale_log2, bias);
-                if (!full) {
-                    const int e = e0 + acc_row(r, G);
-                    const bool vis = is_rep ? (e < mt_row) : (e >= raw_lo_row && e <= t_row);
-                    v = vis ? v : -INFINITY;
-                }
-                sacc[r] = v;
-                tmax = fmaxf(tmax, v);
-            }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            m_ref = (m_ref == NEG_BIG) ? tmax : m_ref;       // first visible keys of this row fix its reference
-            m_seen = fmaxf(m_seen, tmax);
-            exceeded |= tmax > m_ref + HEADROOM;
-            // ---- P^T = exp2(S^T - m_ref) as bf16 B fragments (registers 0..7 / 8..15 = two k-steps) ----
-            bf16x8 pb[2];
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float pv = __builtin_amdgcn_exp2f(sacc[kk * 8 + i] - m_ref);
-                    l_run += pv;
-                    pb[kk][i] = (__bf16)pv;
-                }
-
-            // ---- O^T += V^T P^T ----
-#pragma unroll
-            for (int dvt = 0; dvt < NDV; ++dvt) {
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
-                    const char *vp = kbase + v_off + kk * 16 * RSB + dvt * 64;
-                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(vp));
-                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(vp + 8 * RSB));
-                    const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    acc[dvt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kk], acc[dvt], 0, 0, 0);
-                }
+                const int e = e0 + acc_row(r, G);
+                const bool vis = is_rep ? (e < mt_row) : (e >= raw_lo_row && e <= t_row);
+                scur[r] = vis ? scur[r] : -INFINITY;
             }
         }
+        // The chain always runs: after the last tile it recomputes that tile's S^T, which nobody reads.
+        char *dma_stage = stages[(tl + 3) & (NSTAGE - 1)];
+        const char *chain_stage = stages[min(tl + 1, n_tiles - 1) & (NSTAGE - 1)], *pv_stage = stages[tl & (NSTAGE - 1)];
+        tile_step(tl + 3 < n_tiles, dma_stage, chain_stage, pv_stage, copy_desc(min(tl + 3, n_tiles - 1)), wave, lane, k_off, v_off, qf, snext,
+                  scur, pb, st, c, bias, acc);
+    }
+
+    // every wavefront is done with the tile stages; repeat the pass if any row ran out of exponent headroom
+    if (__syncthreads_or(st.exceeded)) {
+        m_init = st.m_seen;
+        goto restart;
     }
 
     // ---- epilogue: normalise, transpose through LDS (two passes of 256 value columns), store coalesced ----
-    // every wavefront is done with the tile stages; repeat the pass if any row ran out of exponent headroom
-    if (__syncthreads_or(exceeded)) {
-        m_init = m_seen;
-        goto restart;
-    }
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float l_tot = st.l_run + __shfl_xor(st.l_run, 32, 64);
     const float inv = 1.f / l_tot;
     constexpr int ORS = 256 * 2 + 16;                    // staging row stride (bytes)
-    static_assert(4 * 32 * ORS <= STAGE_CHUNKS * 16, "output staging must fit in one tile stage");
-    char *obuf = reinterpret_cast<char *>(stage0) + wave * 32 * ORS;
+    static_assert(4 * 32 * ORS <= NSTAGE * STAGE_BYTES, "output staging must fit in the tile stages");
+    char *obuf = &stages[0][0] + wave * 32 * ORS;
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
@@ -247,12 +310,15 @@ restart:
         __builtin_amdgcn_wave_barrier();
     }
     if (kp.lse != nullptr && G == 0 && t_row < L)
-        kp.lse[((size_t)b * L + t_row) * H + h] = (m_ref + log2f(l_tot)) * 0.6931471805599453f;
+        kp.lse[((size_t)b * L + t_row) * H + h] = (st.m_ref + log2f(l_tot)) * 0.6931471805599453f;
 }
 
 }  // namespace
 
-bool attn_mla_supported(const Dims &d) { return d.dtype == LCA_BF16 && d.mode == LCA_MODE_MLA && d.d_pool == DP && d.d_sel == DS; }
+bool attn_mla_supported(const Dims &d)
+{
+    return d.dtype == LCA_BF16 && d.mode == LCA_MODE_MLA && d.d_pool == DP && d.d_sel == DS && d.scale > 0.f;
+}
 
 hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st)
 {
