@@ -69,15 +69,38 @@ struct RowState {
     bool exceeded;
 };
 
+// Fragments of the V^T operand: two groups of PV_GROUP steps (double-buffered bursts of transpose reads).
+// Step j of the O^T update = (value tile j/2, k-step j%2).
+constexpr int PV_GROUP = 6;
+struct PvFrags {
+    bf16x4 lo[2][PV_GROUP], hi[2][PV_GROUP];
+};
+__device__ __forceinline__ void pv_load_group(PvFrags &f, const char *vp0, int grp, int buf)
+{
+    typedef __attribute__((address_space(3))) bf16x4 *lds_b64_ptr;
+#pragma unroll
+    for (int i = 0; i < PV_GROUP; ++i) {
+        const int j = grp * PV_GROUP + i;
+        if (j < 2 * NDV) {
+            const char *vp = vp0 + (j & 1) * 16 * RSB + (j >> 1) * 64;
+            f.lo[buf][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp));
+            f.hi[buf][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp + 8 * RSB));
+        }
+    }
+}
+
 // S^T chain of one tile (36 MFMAs into `snext`, key fragments prefetched four deep) and, when SOFTMAX,
 // the vector work that turns the previous tile's S^T (`scur`) into P^T fragments, spread over the
 // chain's issue slots.  `kb` = LDS address of this lane's first key fragment of the chain's tile.
 // The MFMAs are inline assembly so that their accumulator is an ordinary vector register tuple (all 256
 // accumulation registers belong to O^T); the wait states an MFMA result needs before vector
 // instructions read it are spent explicitly at the end of the chain.
-template <bool CHAIN, bool SOFTMAX>
+// When PV_PREFETCH, the first burst of V^T reads of the O^T update that follows is issued near the end of the
+// chain (slot 29), and the explicit wait states are left out: the caller keeps every reader of the chain's
+// result behind the whole O^T update (see tile_step).
+template <bool CHAIN, bool SOFTMAX, bool PV_PREFETCH>
 __device__ __forceinline__ void chain_and_softmax(const char *kb, const bf16x8 (&qf)[NKS], floatx16 &snext, const floatx16 &scur,
-                                                  bf16x8 (&pb)[2], RowState &st, float c, float bias)
+                                                  bf16x8 (&pb)[2], RowState &st, float c, float bias, PvFrags &pvf, const char *vp0)
 {
     bf16x8 fr[4];
     if (CHAIN) {
@@ -118,9 +141,10 @@ __device__ __forceinline__ void chain_and_softmax(const char *kb, const bf16x8 (
                 }
             }
         }
+        if (PV_PREFETCH && ks == 29) pv_load_group(pvf, vp0, 0, 0);
     }
     LCA_FENCE();
-    if (CHAIN) asm("s_nop 15\n\ts_nop 7" : "+v"(snext));
+    if (CHAIN && !PV_PREFETCH) asm("s_nop 15\n\ts_nop 7" : "+v"(snext));
 }
 
 // What one wavefront needs to copy its rows of a key tile.
@@ -144,20 +168,25 @@ __device__ __forceinline__ void issue_copy(char *stage, const CopyDesc &cd, int 
     }
 }
 
-// O^T += V^T P^T for one tile; vp = this lane's transpose-read address in the tile's stage.
-__device__ __forceinline__ void pv_update(const char *vp0, const bf16x8 (&pb)[2], floatx16 (&acc)[NDV])
+// O^T += V^T P^T for one tile; vp0 = this lane's transpose-read address in the tile's stage; group 0 of the
+// V^T fragments is already on its way.  The compiler only ever waits for ALL outstanding transpose reads, so
+// the reads of the next group go out in one burst right after the first MFMA of the current group and have
+// the rest of the group's MFMAs to land.
+__device__ __forceinline__ void pv_update(PvFrags &f, const char *vp0, const bf16x8 (&pb)[2], floatx16 (&acc)[NDV])
 {
+    constexpr int NSTEP = 2 * NDV;
 #pragma unroll
-    for (int dvt = 0; dvt < NDV; ++dvt) {
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const char *vp = vp0 + kk * 16 * RSB + dvt * 64;
-            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(vp));
-            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4 *)(vp + 8 * RSB));
-            const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            acc[dvt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kk], acc[dvt], 0, 0, 0);
+    for (int j = 0; j < NSTEP; ++j) {
+        const int grp = j / PV_GROUP, i = j % PV_GROUP, buf = grp & 1;
+        LCA_FENCE();
+        const bf16x8 a = __builtin_shufflevector(f.lo[buf][i], f.hi[buf][i], 0, 1, 2, 3, 4, 5, 6, 7);
+        acc[j >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[j & 1], acc[j >> 1], 0, 0, 0);
+        if (i == 0 && (grp + 1) * PV_GROUP < NSTEP) {
+            LCA_FENCE();
+            pv_load_group(f, vp0, grp + 1, buf ^ 1);
         }
     }
+    LCA_FENCE();
 }
 
 // One pipeline step.  The three stages are distinct (restrict): the copy in flight into `dma_stage` must
@@ -168,8 +197,13 @@ __device__ __forceinline__ void tile_step(bool do_copy, char *__restrict__ dma_s
                                           float c, float bias, floatx16 (&acc)[NDV])
 {
     if (do_copy) issue_copy(dma_stage, cd, wave, lane);
-    chain_and_softmax<true, true>(chain_stage + k_off, qf, snext, scur, pb, st, c, bias);
-    pv_update(pv_stage + v_off, pb, acc);
+    PvFrags pvf;
+    chain_and_softmax<true, true, true>(chain_stage + k_off, qf, snext, scur, pb, st, c, bias, pvf, pv_stage + v_off);
+    pv_update(pvf, pv_stage + v_off, pb, acc);
+    // Anchor: nothing may read the chain's result before this point (the compiler takes an inline-assembly
+    // result as ready at once; the 32 MFMAs of the O^T update are the wait states it actually needs).
+    asm("" : "+v"(snext));
+    LCA_FENCE();
 }
 
 __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
@@ -249,7 +283,10 @@ restart:
     bf16x8 pb[2];
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    chain_and_softmax<true, false>(stages[0] + k_off, qf, snext, snext, pb, st, c, 0.f);
+    {
+        PvFrags unused;
+        chain_and_softmax<true, false, false>(stages[0] + k_off, qf, snext, snext, pb, st, c, 0.f, unused, nullptr);
+    }
 
     for (int tl = 0; tl < n_tiles; ++tl) {
         // tile tl+1 has landed: its copy was issued two iterations ago, only tile tl+2's 16 loads may be pending ...
