@@ -7,10 +7,12 @@
 //   Q^T fragments   144 VGPRs (held for the whole kernel)
 //   O^T accumulator 256 AGPRs (16 tiles of 32 value columns x 32 queries)
 // Key tiles of 32 entries x 576 columns are copied global -> LDS by direct-to-LDS loads into four
-// 36.5 KB stages (row = 1024 B latent + 128 B RoPE key + 16 B pad: an odd number of 16-byte units, so
-// row-strided 16-byte reads spread over all banks); copies run three tiles ahead of their use.  A tile
-// is used twice from LDS: all 576 columns as keys, the first 512 as values — the absorbed MLA form
-// needs no separate value tile.
+// 37.5 KB stages; copies run three tiles ahead of their use.  A stage holds the latent part as 32 rows
+// of 1024 B at a stride of 1072 B (row-strided 16-byte reads and the 4-row transpose reads both spread
+// over all banks) and the RoPE part as 32 x 128 B, 16-byte chunks XOR-swizzled by row so that one
+// wave-wide load moves eight rows and row-strided reads still spread over all banks.  A tile is used
+// twice from LDS: all 576 columns as keys, the first 512 as values — the absorbed MLA form needs no
+// separate value tile.
 //
 // Products are computed transposed so that nothing changes lanes between the two MFMA stages:
 //   S^T[key, query]  = K Q^T       A = key rows from LDS (16-byte reads), B = Q^T in registers
@@ -37,16 +39,16 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-#define LCA_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
-#define LCA_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define LCA_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 constexpr int DP = 512, DS = 64, DQK = 576, DV = 512;
 constexpr int BM = 128;                 // query rows per workgroup
 constexpr int BN = 32;                  // entries per key tile
 constexpr int NSTAGE = 4;
-constexpr int RSB = 1168;               // LDS row stride in bytes: 1024 + 128 + 16
-constexpr int STAGE_BYTES = BN * RSB;   // 37 376
+constexpr int RSB = 1072;               // LDS row stride of the latent part in bytes: 1024 + 48
+constexpr int SEL_OFF = BN * RSB;       // the RoPE part of a stage starts here: 32 rows x 128 B, swizzled
+constexpr int STAGE_BYTES = SEL_OFF + BN * DS * 2;   // 38 400
+constexpr int COPIES_PER_TILE = 9;      // direct-to-LDS loads one wavefront issues per tile (8 latent rows + 1 RoPE block)
 constexpr int NKS = DQK / 16;           // 36 k-steps of S^T
 constexpr int NDV = DV / 32;            // 16 value tiles
 constexpr float NEG_BIG = -1.0e30f;     // stands for -inf in running maxima (keeps exp2 arguments finite)
@@ -89,23 +91,74 @@ __device__ __forceinline__ void pv_load_group(PvFrags &f, const char *vp0, int g
     }
 }
 
+// What one wavefront needs to copy its share of a key tile.
+struct CopyDesc {
+    int e0, last;                 // first entry of the tile, last valid entry of the segment
+};
+
+// One direct-to-LDS load of 64 x 16 bytes: lane l fetches global bytes [base + voff, +16) into LDS bytes
+// [lds_addr + 16 l, +16).  Written as inline assembly on purpose: the compiler makes every LDS read that
+// follows a direct-to-LDS load it knows about wait for that load, and here the copy must stay in flight
+// for two more tiles.  Ordering is kept by hand instead: s_waitcnt vmcnt + workgroup barrier in the tile
+// loop before a stage is read, 9 loads per tile and wavefront.
+__device__ __forceinline__ void dma_1k(unsigned voff, const void *base, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds_addr));   // writes M0, which no compiler-generated instruction of this kernel uses
+}
+
+__device__ __forceinline__ unsigned lds_address(const char *p)
+{
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char *)p;
+}
+
+// `pool` / `sel` = first row of the segment (representatives or raw tokens).
+// One of the 9 copies a wavefront makes per tile: j < 8 moves latent row 8*wave + j (1 KB), j == 8 moves the
+// RoPE parts of rows 8*wave .. 8*wave+7 (1 KB; lane l fills slot l&7 of local row l>>3 with the chunk
+// sel_chunk that the swizzle assigns to that slot).  Rows past the end of the segment are clamped here and
+// masked later.
+__device__ __forceinline__ void issue_copy_part(int j, const char *stage, const uint16_t *pool, const uint16_t *sel, const CopyDesc &cd,
+                                                int wave, int lane, int sel_chunk)
+{
+    if (j < 8) {
+        const int e = min(cd.e0 + 8 * wave + j, cd.last);
+        dma_1k(lane * 16, pool + (size_t)e * DP, lds_address(stage) + (8 * wave + j) * RSB);
+    } else {
+        const int e = min(cd.e0 + 8 * wave + (lane >> 3), cd.last);
+        dma_1k(e * (DS * 2) + sel_chunk * 16, sel, lds_address(stage) + SEL_OFF + 8 * wave * (DS * 2));
+    }
+}
+
+__device__ __forceinline__ void issue_copy(const char *stage, const uint16_t *pool, const uint16_t *sel, const CopyDesc &cd, int wave, int lane,
+                                           int sel_chunk)
+{
+#pragma unroll
+    for (int j = 0; j < COPIES_PER_TILE; ++j) issue_copy_part(j, stage, pool, sel, cd, wave, lane, sel_chunk);
+}
+
 // S^T chain of one tile (36 MFMAs into `snext`, key fragments prefetched four deep) and, when SOFTMAX,
 // the vector work that turns the previous tile's S^T (`scur`) into P^T fragments, spread over the
 // chain's issue slots.  `kb` = LDS address of this lane's first key fragment of the chain's tile.
 // The MFMAs are inline assembly so that their accumulator is an ordinary vector register tuple (all 256
 // accumulation registers belong to O^T); the wait states an MFMA result needs before vector
 // instructions read it are spent explicitly at the end of the chain.
-// When PV_PREFETCH, the first burst of V^T reads of the O^T update that follows is issued near the end of the
-// chain (slot 29), and the explicit wait states are left out: the caller keeps every reader of the chain's
+// When PV_PREFETCH, the copy of a later tile and the first burst of V^T reads of the O^T update that follows are
+// issued in the last slots of the chain, and the explicit wait states are left out: the caller keeps every reader of the chain's
 // result behind the whole O^T update (see tile_step).
 template <bool CHAIN, bool SOFTMAX, bool PV_PREFETCH>
-__device__ __forceinline__ void chain_and_softmax(const char *kb, const bf16x8 (&qf)[NKS], floatx16 &snext, const floatx16 &scur,
-                                                  bf16x8 (&pb)[2], RowState &st, float c, float bias, PvFrags &pvf, const char *vp0)
+__device__ __forceinline__ void chain_and_softmax(const char *kb, const char *kb_sel, int x6, const bf16x8 (&qf)[NKS], floatx16 &snext,
+                                                  const floatx16 &scur, bf16x8 (&pb)[2], RowState &st, float c, float bias, PvFrags &pvf,
+                                                  const char *vp0, const char *dma_stage, const uint16_t *pool, const uint16_t *sel,
+                                                  const CopyDesc &cd, int wave, int lane, int sel_chunk)
 {
+    // key fragment of k-step ks: latent columns from the row-strided part, RoPE columns (ks >= 32) from the swizzled part
+    auto frag = [&](int ks) {
+        const char *p = ks < DP / 16 ? kb + ks * 32 : kb_sel + ((x6 ^ (2 * (ks - DP / 16))) << 4);
+        return *reinterpret_cast<const bf16x8 *>(p);
+    };
     bf16x8 fr[4];
     if (CHAIN) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fr[i] = *reinterpret_cast<const bf16x8 *>(kb + i * 32);
+        for (int i = 0; i < 4; ++i) fr[i] = frag(i);
     }
     float mx[6], nb = 0.f, p[16];
 #pragma unroll
@@ -116,7 +169,7 @@ __device__ __forceinline__ void chain_and_softmax(const char *kb, const bf16x8 (
                 asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(snext) : "v"(fr[0]), "v"(qf[0]));
             else
                 asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(snext) : "v"(fr[ks & 3]), "v"(qf[ks]));
-            if (ks + 4 < NKS) fr[ks & 3] = *reinterpret_cast<const bf16x8 *>(kb + (ks + 4) * 32);
+            if (ks + 4 < NKS) fr[ks & 3] = frag(ks + 4);
         }
         if (SOFTMAX) {
             // slots 0..4: maxima of triples; 5..7: reduce and scale; 8: partner lane; 9: reference; 10..25: exponentials
@@ -141,31 +194,12 @@ __device__ __forceinline__ void chain_and_softmax(const char *kb, const bf16x8 (
                 }
             }
         }
-        if (PV_PREFETCH && ks == 29) pv_load_group(pvf, vp0, 0, 0);
+        // the copy of the tile three steps ahead rides in the chain's last slots, after the softmax work
+        if (PV_PREFETCH && ks >= 26 && ks - 26 < COPIES_PER_TILE) issue_copy_part(ks - 26, dma_stage, pool, sel, cd, wave, lane, sel_chunk);
+        if (PV_PREFETCH && ks == 35) pv_load_group(pvf, vp0, 0, 0);
     }
     LCA_FENCE();
     if (CHAIN && !PV_PREFETCH) asm("s_nop 15\n\ts_nop 7" : "+v"(snext));
-}
-
-// What one wavefront needs to copy its rows of a key tile.
-struct CopyDesc {
-    const uint16_t *pool, *sel;   // first row of the segment (representatives or raw tokens)
-    int e0, last;                 // first entry of the tile, last valid entry of the segment
-};
-
-// Copy a tile into an LDS stage: this wavefront moves rows wave, wave+4, ... with one 1 KB and one 128 B
-// direct-to-LDS load per row (16 loads per tile and wavefront — the count the vmcnt waits rely on).
-// Rows past the end of the segment are clamped here and masked later.
-__device__ __forceinline__ void issue_copy(char *stage, const CopyDesc &cd, int wave, int lane)
-{
-#pragma unroll
-    for (int j = 0; j < BN / 4; ++j) {
-        const int r = wave + 4 * j;
-        const int e = min(cd.e0 + r, cd.last);
-        __builtin_amdgcn_global_load_lds(LCA_GLB_PTR(cd.pool + (size_t)e * DP + lane * 8), LCA_LDS_PTR(stage + r * RSB), 16, 0, 0);
-        if (lane < 8)
-            __builtin_amdgcn_global_load_lds(LCA_GLB_PTR(cd.sel + (size_t)e * DS + lane * 8), LCA_LDS_PTR(stage + r * RSB + 1024), 16, 0, 0);
-    }
 }
 
 // O^T += V^T P^T for one tile; vp0 = this lane's transpose-read address in the tile's stage; group 0 of the
@@ -189,16 +223,16 @@ __device__ __forceinline__ void pv_update(PvFrags &f, const char *vp0, const bf1
     LCA_FENCE();
 }
 
-// One pipeline step.  The three stages are distinct (restrict): the copy in flight into `dma_stage` must
-// not make reads of the other two wait for it.
-__device__ __forceinline__ void tile_step(bool do_copy, char *__restrict__ dma_stage, const char *__restrict__ chain_stage,
-                                          const char *__restrict__ pv_stage, const CopyDesc &cd, int wave, int lane, int k_off, int v_off,
-                                          const bf16x8 (&qf)[NKS], floatx16 &snext, const floatx16 &scur, bf16x8 (&pb)[2], RowState &st,
-                                          float c, float bias, floatx16 (&acc)[NDV])
+// One pipeline step: copy of tile t+3 (into dma_stage), S^T chain of tile t+1 with the softmax of tile t in
+// its shadow, O^T update of tile t.
+__device__ __forceinline__ void tile_step(const char *dma_stage, const char *chain_stage, const char *pv_stage, const uint16_t *pool,
+                                          const uint16_t *sel, const CopyDesc &cd, int wave, int lane, int sel_chunk, int k_off, int ksel_off,
+                                          int x6, int v_off, const bf16x8 (&qf)[NKS], floatx16 &snext, const floatx16 &scur, bf16x8 (&pb)[2],
+                                          RowState &st, float c, float bias, floatx16 (&acc)[NDV])
 {
-    if (do_copy) issue_copy(dma_stage, cd, wave, lane);
     PvFrags pvf;
-    chain_and_softmax<true, true, true>(chain_stage + k_off, qf, snext, scur, pb, st, c, bias, pvf, pv_stage + v_off);
+    chain_and_softmax<true, true, true>(chain_stage + k_off, chain_stage + ksel_off, x6, qf, snext, scur, pb, st, c, bias, pvf, pv_stage + v_off,
+                                        dma_stage, pool, sel, cd, wave, lane, sel_chunk);
     pv_update(pvf, pv_stage + v_off, pb, acc);
     // Anchor: nothing may read the chain's result before this point (the compiler takes an inline-assembly
     // result as ready at once; the 32 MFMAs of the O^T update are the wait states it actually needs).
@@ -208,7 +242,7 @@ __device__ __forceinline__ void tile_step(bool do_copy, char *__restrict__ dma_s
 
 __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
 {
-    __shared__ __attribute__((aligned(16))) char stages[NSTAGE][STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char stages[NSTAGE][STAGE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, G = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -246,16 +280,19 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
     auto copy_desc = [&](int tl) {
         const bool is_rep = tl < n_rep_tiles;
         CopyDesc cd;
-        cd.pool = is_rep ? rep_pool : raw_pool;
-        cd.sel = is_rep ? rep_sel : raw_sel;
         cd.e0 = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
         cd.last = (is_rep ? mt_blk_hi : t_last + 1) - 1;
         return cd;
     };
 
     // per-lane LDS byte offsets
-    const int k_off = n * RSB + G * 16;                                              // S^T: key row n, 16-byte chunk G
+    const int k_off = n * RSB + G * 16;                                              // S^T, latent part: key row n, 16-byte chunk G
+    const int xs = (n >> 1) & 7;                                                     // swizzle of key row n in the RoPE part
+    const int ksel_off = SEL_OFF + n * (DS * 2) + ((G ^ (xs & 1)) << 4);             // S^T, RoPE part: chunk (2j+G) sits at slot (2j+G)^xs
+    const int x6 = xs & 6;
     const int v_off = (4 * G + ((lane & 15) >> 2)) * RSB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;   // V^T transpose read
+    // copy side of the swizzle: lane l of the RoPE copy fills slot l&7 of local row l>>3 (row 8*wave + (l>>3) of the tile)
+    const int sel_chunk = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
 
     // Q^T fragments: lane (n, G) holds Q[t_row, ks*16 + 8G .. +7]
     bf16x8 qf[NKS];
@@ -278,21 +315,25 @@ restart:
     st.m_ref = m_init; st.l_run = 0.f; st.m_seen = NEG_BIG; st.exceeded = false;
 
     // prologue: three tiles in flight, then the S^T chain of tile 0
-    for (int tl = 0; tl < min(3, n_tiles); ++tl) issue_copy(stages[tl], copy_desc(tl), wave, lane);
+    for (int tl = 0; tl < 3; ++tl) {
+        const int tc = min(tl, n_tiles - 1);
+        issue_copy(stages[tl], tc < n_rep_tiles ? rep_pool : raw_pool, tc < n_rep_tiles ? rep_sel : raw_sel, copy_desc(tc), wave, lane, sel_chunk);
+    }
     floatx16 snext, scur;
     bf16x8 pb[2];
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     {
         PvFrags unused;
-        chain_and_softmax<true, false, false>(stages[0] + k_off, qf, snext, snext, pb, st, c, 0.f, unused, nullptr);
+        chain_and_softmax<true, false, false>(stages[0] + k_off, stages[0] + ksel_off, x6, qf, snext, snext, pb, st, c, 0.f, unused, nullptr,
+                                              nullptr, nullptr, nullptr, CopyDesc(), wave, lane, sel_chunk);
     }
 
     for (int tl = 0; tl < n_tiles; ++tl) {
-        // tile tl+1 has landed: its copy was issued two iterations ago, only tile tl+2's 16 loads may be pending ...
-        if (tl + 2 < n_tiles) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // tile tl+1 has landed: its copy was issued two iterations ago, only tile tl+2's 9 loads may be pending ...
+        asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
         __syncthreads();      // ... for every wavefront, and every wavefront is done with tile tl-1
+
         const bool is_rep = tl < n_rep_tiles;
         const int e0 = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
         const float bias = is_rep ? kp.bias_log2 : 0.f;
@@ -307,13 +348,15 @@ restart:
                 scur[r] = vis ? scur[r] : -INFINITY;
             }
         }
-        // The chain always runs: after the last tile it recomputes that tile's S^T, which nobody reads.
-        char *dma_stage = stages[(tl + 3) & (NSTAGE - 1)];
+        // The chain and the copy always run: past the last tile they redo that tile (S^T that nobody reads, a
+        // copy into a stage that nobody reads again), which keeps the loop body branch-free.
+        const char *dma_stage = stages[(tl + 3) & (NSTAGE - 1)];
         const char *chain_stage = stages[min(tl + 1, n_tiles - 1) & (NSTAGE - 1)], *pv_stage = stages[tl & (NSTAGE - 1)];
-        tile_step(tl + 3 < n_tiles, dma_stage, chain_stage, pv_stage, copy_desc(min(tl + 3, n_tiles - 1)), wave, lane, k_off, v_off, qf, snext,
-                  scur, pb, st, c, bias, acc);
+        const int tc = min(tl + 3, n_tiles - 1);
+        tile_step(dma_stage, chain_stage, pv_stage, tc < n_rep_tiles ? rep_pool : raw_pool, tc < n_rep_tiles ? rep_sel : raw_sel, copy_desc(tc),
+                  wave, lane, sel_chunk, k_off, ksel_off, x6, v_off, qf, snext, scur, pb, st, c, bias, acc);
     }
-
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the trailing copies have landed before the stages are reused
     // every wavefront is done with the tile stages; repeat the pass if any row ran out of exponent headroom
     if (__syncthreads_or(st.exceeded)) {
         m_init = st.m_seen;
