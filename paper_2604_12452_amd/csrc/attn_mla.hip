@@ -7,10 +7,12 @@
 //   Q^T fragments   144 VGPRs (held for the whole kernel)
 //   O^T accumulator 256 AGPRs (16 tiles of 32 value columns x 32 queries)
 // Key tiles of 32 entries x 576 columns are copied global -> LDS by direct-to-LDS loads into four
-// 37.5 KB stages; copies run three tiles ahead of their use.  A stage holds the latent part as 32 rows
-// of 1024 B at a stride of 1072 B (row-strided 16-byte reads and the 4-row transpose reads both spread
-// over all banks) and the RoPE part as 32 x 128 B, 16-byte chunks XOR-swizzled by row so that one
-// wave-wide load moves eight rows and row-strided reads still spread over all banks.  A tile is used
+// 36.5 KB stages; copies run three tiles ahead of their use.  A stage holds the latent part as 32 rows
+// of 1024 B at a stride of 1040 B and the RoPE part as 32 x 128 B, 16-byte chunks XOR-swizzled by row
+// so that one wave-wide load moves eight rows.  S^T row m is computed from LDS row pi(m), a fixed
+// permutation inside each half of 16 rows (pi(8h + 4G + j) = 4j + 2h + G): with it both the
+// row-strided 16-byte key reads (16 lanes = 16 rows that differ mod 16) and the transpose reads of the
+// value operand (each 16-lane block touches 4 rows that are 4 apart) spread over all 64 banks.  A tile is used
 // twice from LDS: all 576 columns as keys, the first 512 as values — the absorbed MLA form needs no
 // separate value tile.
 //
@@ -45,9 +47,9 @@ constexpr int DP = 512, DS = 64, DQK = 576, DV = 512;
 constexpr int BM = 128;                 // query rows per workgroup
 constexpr int BN = 32;                  // entries per key tile
 constexpr int NSTAGE = 4;
-constexpr int RSB = 1072;               // LDS row stride of the latent part in bytes: 1024 + 48
+constexpr int RSB = 1040;               // LDS row stride of the latent part in bytes: 1024 + 16
 constexpr int SEL_OFF = BN * RSB;       // the RoPE part of a stage starts here: 32 rows x 128 B, swizzled
-constexpr int STAGE_BYTES = SEL_OFF + BN * DS * 2;   // 38 400
+constexpr int STAGE_BYTES = SEL_OFF + BN * DS * 2;   // 37 376
 constexpr int COPIES_PER_TILE = 9;      // direct-to-LDS loads one wavefront issues per tile (8 latent rows + 1 RoPE block)
 constexpr int NKS = DQK / 16;           // 36 k-steps of S^T
 constexpr int NDV = DV / 32;            // 16 value tiles
@@ -62,8 +64,11 @@ struct MlaParams {
     float scale_log2, bias_log2;
 };
 
-// key row held in accumulator register r of lane group G (lanes 32G..32G+31) of a 32x32 tile
-__device__ __forceinline__ int acc_row(int r, int G) { return 8 * (r >> 2) + 4 * G + (r & 3); }
+// Accumulator register r of lane group G (lanes 32G..32G+31) of a 32x32 tile holds S^T row
+// m = 8*(r/4) + 4G + r%4.  S^T row m is computed from LDS row (= tile entry) pi(m): inside each half of 16,
+// pi(8h + 4G + j) = 4j + 2h + G.
+__device__ __forceinline__ int lds_row_of_m(int m) { return (m & 16) + 4 * (m & 3) + 2 * ((m >> 3) & 1) + ((m >> 2) & 1); }
+__device__ __forceinline__ int acc_entry(int r, int G) { return lds_row_of_m(8 * (r >> 2) + 4 * G + (r & 3)); }
 
 // per-lane softmax state (base-2 logits): reference, running sum over this lane's keys, largest seen
 struct RowState {
@@ -84,9 +89,11 @@ __device__ __forceinline__ void pv_load_group(PvFrags &f, const char *vp0, int g
     for (int i = 0; i < PV_GROUP; ++i) {
         const int j = grp * PV_GROUP + i;
         if (j < 2 * NDV) {
+            // k-slots i = 4h + j of this step hold keys pi(16kk + 8h + 4G + j) = 16kk + 4j + 2h + G: the lanes of a
+            // 16-lane block address rows 4j + G (j = lane bits 2..3, part of vp0); h = 0 / 1 adds two rows
             const char *vp = vp0 + (j & 1) * 16 * RSB + (j >> 1) * 64;
             f.lo[buf][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp));
-            f.hi[buf][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp + 8 * RSB));
+            f.hi[buf][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp + 2 * RSB));
         }
     }
 }
@@ -286,11 +293,12 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
     };
 
     // per-lane LDS byte offsets
-    const int k_off = n * RSB + G * 16;                                              // S^T, latent part: key row n, 16-byte chunk G
-    const int xs = (n >> 1) & 7;                                                     // swizzle of key row n in the RoPE part
-    const int ksel_off = SEL_OFF + n * (DS * 2) + ((G ^ (xs & 1)) << 4);             // S^T, RoPE part: chunk (2j+G) sits at slot (2j+G)^xs
+    const int krow = lds_row_of_m(n);                                                // LDS row behind S^T row n
+    const int k_off = krow * RSB + G * 16;                                           // S^T, latent part: 16-byte chunk G of that row
+    const int xs = (krow >> 1) & 7;                                                  // swizzle of that row in the RoPE part
+    const int ksel_off = SEL_OFF + krow * (DS * 2) + ((G ^ (xs & 1)) << 4);          // S^T, RoPE part: chunk (2j+G) sits at slot (2j+G)^xs
     const int x6 = xs & 6;
-    const int v_off = (4 * G + ((lane & 15) >> 2)) * RSB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;   // V^T transpose read
+    const int v_off = (4 * ((lane & 15) >> 2) + G) * RSB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;   // V^T transpose read
     // copy side of the swizzle: lane l of the RoPE copy fills slot l&7 of local row l>>3 (row 8*wave + (l>>3) of the tile)
     const int sel_chunk = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
 
@@ -343,7 +351,7 @@ restart:
         if (!full) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int e = e0 + acc_row(r, G);
+                const int e = e0 + acc_entry(r, G);
                 const bool vis = is_rep ? (e < mt_row) : (e >= raw_lo_row && e <= t_row);
                 scur[r] = vis ? scur[r] : -INFINITY;
             }
