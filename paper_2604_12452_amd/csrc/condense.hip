@@ -61,33 +61,56 @@ template <> struct Elt<float> {
 
 // ---------------------------------------------------------------------------------------------
 // Summary query: qbar[b,s,x] = mean over t in [L-n_q, L), h in set s of Q[b,t,h,x].
-// One workgroup per (b, s, 64 columns); its 4 wavefronts split the (t, h) list, each with 8 independent
-// loads in flight, and are merged in a fixed order through LDS.
+// One workgroup of 16 wavefronts per (b, s, 64 chunks of 16 bytes): the wavefronts split the (t, h)
+// list, each lane keeps 8 independent 16-byte loads in flight, and the partial sums are merged in a
+// fixed order through LDS (deterministic).
 // ---------------------------------------------------------------------------------------------
+constexpr int SQ_WAVES = 16;
 template <typename T>
-__global__ __launch_bounds__(256) void summary_query_kernel(const T *__restrict__ Q, float *__restrict__ qbar, int L, int H, int S, int d_qk, int n_q)
+__global__ __launch_bounds__(SQ_WAVES *WAVE) void summary_query_kernel(const T *__restrict__ Q, float *__restrict__ qbar, int L, int H, int S,
+                                                                       int d_qk, int n_q)
 {
-    __shared__ float part[4][WAVE];
-    const int xblocks = (d_qk + WAVE - 1) / WAVE;
+    constexpr int EPC = Elt<T>::EPC;
+    __shared__ float part[SQ_WAVES][WAVE][EPC + 1];
+    const int n_chunks = d_qk / EPC;
+    const int xblocks = (n_chunks + WAVE - 1) / WAVE;
     const int bs = blockIdx.x / xblocks, xb = blockIdx.x % xblocks;
     const int b = bs / S, s = bs % S, hps = H / S;
     const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
-    const int x = xb * WAVE + lane;
+    const int chunk = xb * WAVE + lane;
     const int n = n_q * hps;                       // (t, h) pairs, pair u -> t = L - n_q + u / hps, h = s*hps + u % hps
-    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (x < d_qk) {
-        for (int u0 = wave * 8; u0 < n; u0 += 32) {
+    float acc[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) acc[e] = 0.f;
+    if (chunk < n_chunks) {
+        for (int u0 = wave; u0 < n; u0 += SQ_WAVES * 8) {
+            uint4 v[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int u = u0 + i;
-                if (u < n) a[i] += Elt<T>::ld(Q + (((size_t)b * L + (L - n_q + u / hps)) * H + s * hps + u % hps) * d_qk + x);
+                const int u = u0 + i * SQ_WAVES;
+                v[i] = u < n ? *reinterpret_cast<const uint4 *>(Q + (((size_t)b * L + (L - n_q + u / hps)) * H + s * hps + u % hps) * d_qk + chunk * EPC)
+                             : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float f[EPC];
+                Elt<T>::unpack(v[i], f);
+#pragma unroll
+                for (int e = 0; e < EPC; ++e) acc[e] += f[e];
             }
         }
     }
-    part[wave][lane] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) part[wave][lane][e] = acc[e];
     __syncthreads();
-    if (wave == 0 && x < d_qk)
-        qbar[(size_t)bs * d_qk + x] = ((part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane])) / (float)n;
+    if (wave == 0 && chunk < n_chunks) {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) {
+            float t = 0.f;
+            for (int wv = 0; wv < SQ_WAVES; ++wv) t += part[wv][lane][e];
+            qbar[(size_t)bs * d_qk + chunk * EPC + e] = t / (float)n;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -363,11 +386,13 @@ hipError_t launch_condense(const CondenseArgs &a, hipStream_t st)
 {
     const Dims &d = a.d;
     // 1. summary query (Algorithm 1, first step)
-    const int sq_blocks = d.B * d.S * ((d.d_qk + WAVE - 1) / WAVE);
-    if (d.dtype == LCA_BF16)
-        summary_query_kernel<uint16_t><<<sq_blocks, 256, 0, st>>>((const uint16_t *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
-    else
-        summary_query_kernel<float><<<sq_blocks, 256, 0, st>>>((const float *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
+    if (d.dtype == LCA_BF16) {
+        const int sq_blocks = d.B * d.S * ((d.d_qk / 8 + WAVE - 1) / WAVE);
+        summary_query_kernel<uint16_t><<<sq_blocks, SQ_WAVES * WAVE, 0, st>>>((const uint16_t *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
+    } else {
+        const int sq_blocks = d.B * d.S * ((d.d_qk / 4 + WAVE - 1) / WAVE);
+        summary_query_kernel<float><<<sq_blocks, SQ_WAVES * WAVE, 0, st>>>((const float *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || d.m == 0) return err;
     // 2. groups
