@@ -158,3 +158,38 @@ def test_decode_step(oracle, mode, d_pool, d_sel, H, S, dtype, L, g, w):
     err = hp.vec_rel_err(hp.from_dev(O, dtype), ref)
     print(f"  decode err {err:.2e}", flush=True)
     assert err <= hp.TOL[dtype]
+
+
+# ---- rows whose later logits dwarf the first tile's: the kernel's repeat pass ---------------------------
+@pytest.mark.parametrize("dense_only", [False, True])
+def test_mla_logits_far_above_first_tile(oracle, dense_only):
+    """A key late in the sequence scores ~100 nats above everything in the first key tile of each row.  The
+    MLA kernel fixes its softmax reference at the first tile and must notice that its exponent headroom
+    (2^60) is exceeded and repeat the pass; the result must still match the oracle."""
+    wl = inputs.Workload("mla_spike", B=1, L=420, H=2, S=1, d_pool=512, d_sel=64, g=16, w=64, dtype="bf16", seed=77)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    Qf = inputs.to_f64(Q, wl.dtype)
+    # make tokens 300 (raw window of the last rows) and 40 (inside a condensed group) line up with the queries' mean direction
+    qdir = Qf[0, :, :, :512].mean(axis=(0, 1))
+    qdir /= np.linalg.norm(qdir)
+    POOLf = inputs.to_f64(POOL, wl.dtype)
+    # pick the size so that <q, c> is around 100 for typical q: the queries share a common component along qdir
+    Qf[0, :, :, :512] += 2.0 * qdir
+    for tok in (40, 300):
+        POOLf[0, tok] = 50.0 * qdir
+    Q = inputs.to_storage(Qf, wl.dtype)
+    POOL = inputs.to_storage(POOLf, wl.dtype)
+    Qf, POOLf, SELf = (inputs.to_f64(x, wl.dtype) for x in (Q, POOL, SEL))
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense()
+    ref, differ = hp.check_condense(oracle, wl, run, Qf[:, wl.L - wl.nq:], POOLf, SELf)
+    rows = np.arange(wl.L, dtype=np.int32)
+    keys = np.concatenate([POOLf[0], SELf[0]], -1)
+    logits = keys[:351] @ Qf[0, 350, 0]
+    spread = logits.max() - logits[:32].max()
+    assert spread > 60.0, f"the test input must exceed the kernel's headroom (spread {spread:.1f} nats)"
+    if dense_only:
+        run.dense()
+        hp.check_dense(oracle, wl, run, rows, Qf, POOLf, SELf)
+    else:
+        run.prefill()
+        hp.check_prefill(oracle, wl, run, rows, Qf, POOLf, SELf, ref, differ)
