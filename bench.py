@@ -81,12 +81,31 @@ def cpu_baseline(wl, Q, POOL, SEL, n_rows: int):
     }, rows, O, c
 
 
+def decode_bench(wl, lca, hp, torch):
+    """One decode step of 32 sequences over their condensed caches (HBM-bound). Cache contents are random
+    (torch.randn on the device): only the time matters here, parity is covered by the GPU tests."""
+    B = 32
+    wd = wl.with_(B=B, L=wl.L + 1)
+    desc = hp.lca_desc(wd)
+    m, k = wd.m, wd.k
+    mk = lambda *shape: torch.randn(shape, dtype=torch.bfloat16, device="cuda")
+    pool_rep, sel_rep = mk(B, wd.S, m, wd.d_pool), mk(B, wd.S, m, wd.d_sel)
+    pool_tail, sel_tail = mk(B, wd.kv_heads, k, wd.d_pool), mk(B, wd.kv_heads, k, wd.d_sel)
+    q = mk(B, wd.H, wd.d_qk) * 0.1
+    O = torch.empty((B, wd.H, wd.d_pool), dtype=torch.bfloat16, device="cuda")
+    ws = lca.alloc_workspace(desc)
+    ms = time_kernel(lambda: lca.decode_attn(desc, q, pool_rep, sel_rep, pool_tail, sel_tail, O, ws), 20, 3)
+    nbytes = B * wd.S * (m + k) * (wd.d_pool + wd.d_sel) * 2
+    return {"B": B, "L": wd.L, "m": m, "k": k, "ms_decode_step": ms, "algorithmic_bytes": nbytes,
+            "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="cfg4", help="cfg2 | cfg3 | cfg4 (default, the metric's workload)")
+    ap.add_argument("--config", default="cfg4", help="cfg2 | cfg3 | cfg4 (default, the metric's workload) | cfg5 (GQA + decode step)")
     ap.add_argument("--oracle-rows", type=int, default=512)
     ap.add_argument("--no-extra", action="store_true", help="skip dense baseline and variants (profiling runs)")
     ap.add_argument("--pmc-calib", action="store_true",
@@ -109,6 +128,7 @@ def main():
 
     run = hp.GpuRun(wl, Q, POOL, SEL)
     d = run.desc
+    mla = wl.mode == inputs.MODE_MLA
     run.pool_rep, run.sel_rep, run.anchor, _ = lca.alloc_condensed(d)
     O = torch.empty((d.B, d.L, d.H, d.d_pool), dtype=torch.bfloat16, device="cuda")
 
@@ -174,7 +194,7 @@ def main():
                       "speedup_vs_dense_mla": ms_dense / ms_per_step, "dense_tokens_per_s": wl.B * wl.L / (ms_dense * 1e-3)})
         del O2
         # variants: g = 32, and one condensed set per head (S = H)
-        for tag, kw in (("g32", dict(g=32)), ("per_head_sets", dict(S=wl.H))):
+        for tag, kw in ((("g32", dict(g=32)), ("per_head_sets", dict(S=wl.H))) if mla else ()):
             w2 = wl.with_(**kw)
             d2 = hp.lca_desc(w2)
             pr, sr, an, _ = lca.alloc_condensed(d2)
@@ -189,16 +209,21 @@ def main():
                           "kv_cache_bytes_lca": cb, "kv_cache_saved_frac": 1.0 - cb / db}
             del pr, sr, an
 
+    if not mla and not args.no_extra:
+        extra["decode"] = decode_bench(wl, lca, hp, torch)
+
     out = {
         "metric": "LCA prefill tokens/s at 128K (MLA, 16 heads) + speedup vs dense MLA" if args.config == "cfg4"
         else f"LCA prefill tokens/s ({wl.name})",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: B={wl.B} L={wl.L} H={wl.H} d_c={wl.d_pool} d_R={wl.d_sel} g={wl.g} w={wl.w} "
-                               f"S={wl.S} bf16, AR(1) rho=0.9 latents, RoPE keys, Gaussian queries; one attention layer",
+        "config": {"workload": (f"{wl.name}: B={wl.B} L={wl.L} H={wl.H} d_c={wl.d_pool} d_R={wl.d_sel} g={wl.g} w={wl.w} "
+                                f"S={wl.S} bf16, AR(1) rho=0.9 latents, RoPE keys, Gaussian queries; one attention layer") if mla else
+                               (f"{wl.name}: GQA B={wl.B} L={wl.L} H={wl.H} KV heads={wl.S} d={wl.d_sel} g={wl.g} w={wl.w} bf16, "
+                                f"AR(1) keys/values, RoPE theta {wl.theta:g}; one attention layer"),
                    "step": "lca_condense + lca_prefill_attn"},
-        "roofline": {"bound": "mfma", "kernel": "attn_mla_kernel (lca_prefill_attn)", "achieved": tflops,
+        "roofline": {"bound": "mfma", "kernel": ("attn_mla_kernel" if mla else "attn_mfma_kernel<128,128>") + " (lca_prefill_attn)", "achieved": tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None},
         "cpu_baseline": base,
         "extra": extra,
