@@ -13,7 +13,7 @@ namespace {
 
 constexpr int WAVE = 64;
 constexpr int NWAVE = 4;
-constexpr int TARGET_BLOCKS = 1024;   // ~4 workgroups per CU
+constexpr int TARGET_BLOCKS = 2048;   // ~8 workgroups per CU
 
 template <typename T> struct DElt;
 template <> struct DElt<uint16_t> {
@@ -209,6 +209,151 @@ __global__ __launch_bounds__(WAVE *NWAVE) void decode_split_kernel(const T *__re
     for (int x = tid; x < H * (DP + 2); x += WAVE * NWAVE) dst[x] = comb[x];
 }
 
+// Sum over the 16 lanes of a DPP row (every lane gets the total): four rotate-and-add steps.
+__device__ __forceinline__ float row16_allreduce_sum(float x)
+{
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x128, 0xf, 0xf, false));   // row_ror:8
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x124, 0xf, 0xf, false));   // row_ror:4
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x122, 0xf, 0xf, false));   // row_ror:2
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x121, 0xf, 0xf, false));   // row_ror:1
+    return x;
+}
+
+// Decode split kernel for the GQA widths (d_k = d_v = 128, bf16): 16 lanes per cache row, each lane owns one
+// 16-byte chunk of the key AND of the value of that row; 4 rows per wavefront step, GQ_UNROLL steps in flight
+// (all loads of an iteration are issued before any arithmetic), one softmax rescale per iteration.
+constexpr int GQ_UNROLL = 4;
+template <int HPS>
+__global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ pool_rep,
+                                                                 const uint16_t *__restrict__ sel_rep, const uint16_t *__restrict__ pool_tail,
+                                                                 const uint16_t *__restrict__ sel_tail, float *__restrict__ part, int S, int m,
+                                                                 int k, int splits, float scale, float rep_bias)
+{
+    constexpr int D = 128, H = HPS, RPW = 4;
+    __shared__ float comb[H * (D + 2)];
+    const int tid = threadIdx.x, wave = tid / WAVE, lane = tid % WAVE, sub = lane & 15, grp = lane >> 4;
+    const int split = blockIdx.x % splits, s = (blockIdx.x / splits) % S, b = blockIdx.x / (splits * S);
+    const int n = m + k;
+    const int per = (n + splits - 1) / splits;
+    const int e_lo = split * per, e_hi = min(n, e_lo + per);
+
+    // this lane's 8 columns of every head's query, pre-multiplied by the scale
+    float qv[H][8];
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        float f[8];
+        DElt<uint16_t>::unpack(*reinterpret_cast<const uint4 *>(q + (((size_t)b * S + s) * H + h) * D + sub * 8), f);
+#pragma unroll
+        for (int x = 0; x < 8; ++x) qv[h][x] = f[x] * scale;
+    }
+    const uint16_t *krep = sel_rep + ((size_t)b * S + s) * m * D, *vrep = pool_rep + ((size_t)b * S + s) * m * D;
+    const uint16_t *ktail = sel_tail + ((size_t)b * S + s) * k * D, *vtail = pool_tail + ((size_t)b * S + s) * k * D;
+
+    float mr[H], lr[H], acc[H][8];
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        mr[h] = -INFINITY;
+        lr[h] = 0.f;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) acc[h][x] = 0.f;
+    }
+
+    for (int base = e_lo + wave * RPW; base < e_hi; base += NWAVE * RPW * GQ_UNROLL) {
+        uint4 kd[GQ_UNROLL], vd[GQ_UNROLL];
+        bool valid[GQ_UNROLL], rep[GQ_UNROLL];
+#pragma unroll
+        for (int u = 0; u < GQ_UNROLL; ++u) {
+            const int e = base + u * NWAVE * RPW + grp;
+            valid[u] = e < e_hi;
+            const int ec = valid[u] ? e : e_hi - 1;
+            rep[u] = ec < m;
+            const uint16_t *kp = rep[u] ? krep + (size_t)ec * D : ktail + (size_t)(ec - m) * D;
+            const uint16_t *vp = rep[u] ? vrep + (size_t)ec * D : vtail + (size_t)(ec - m) * D;
+            kd[u] = *reinterpret_cast<const uint4 *>(kp + sub * 8);
+            vd[u] = *reinterpret_cast<const uint4 *>(vp + sub * 8);
+        }
+        float logit[GQ_UNROLL][H];
+#pragma unroll
+        for (int u = 0; u < GQ_UNROLL; ++u) {
+            float f[8];
+            DElt<uint16_t>::unpack(kd[u], f);
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                float a = 0.f;
+#pragma unroll
+                for (int x = 0; x < 8; ++x) a = fmaf(f[x], qv[h][x], a);
+                a = row16_allreduce_sum(a);
+                logit[u][h] = valid[u] ? a + (rep[u] ? rep_bias : 0.f) : -INFINITY;
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            float m_new = mr[h];
+#pragma unroll
+            for (int u = 0; u < GQ_UNROLL; ++u) m_new = fmaxf(m_new, logit[u][h]);
+            const float m_eff = m_new == -INFINITY ? 0.f : m_new;
+            const float corr = __expf(mr[h] - m_eff);
+            mr[h] = m_new;
+            lr[h] *= corr;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) acc[h][x] *= corr;
+#pragma unroll
+            for (int u = 0; u < GQ_UNROLL; ++u) {
+                const float pe = __expf(logit[u][h] - m_eff);
+                lr[h] += pe;
+                float f[8];
+                DElt<uint16_t>::unpack(vd[u], f);
+#pragma unroll
+                for (int x = 0; x < 8; ++x) acc[h][x] = fmaf(pe, f[x], acc[h][x]);
+            }
+        }
+    }
+
+    // merge the four 16-lane groups of this wavefront (same columns, different rows)
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+#pragma unroll
+        for (int mask = 16; mask < WAVE; mask <<= 1) {
+            const float om = __shfl_xor(mr[h], mask, WAVE), ol = __shfl_xor(lr[h], mask, WAVE);
+            const float m_new = fmaxf(mr[h], om);
+            const float m_eff = m_new == -INFINITY ? 0.f : m_new;
+            const float ca = __expf(mr[h] - m_eff), cb = __expf(om - m_eff);
+            lr[h] = lr[h] * ca + ol * cb;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) acc[h][x] = acc[h][x] * ca + __shfl_xor(acc[h][x], mask, WAVE) * cb;
+            mr[h] = m_new;
+        }
+    }
+    // merge the wavefronts one after another through LDS
+    for (int wv = 0; wv < NWAVE; ++wv) {
+        if (wave == wv && grp == 0) {
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                float *cm = comb + h * (D + 2);
+                float ca = 1.f, cb = 0.f, m_new = mr[h], l_new = lr[h];
+                if (wv > 0) {
+                    const float om = cm[0], ol = cm[1];
+                    m_new = fmaxf(mr[h], om);
+                    const float m_eff = m_new == -INFINITY ? 0.f : m_new;
+                    ca = __expf(mr[h] - m_eff);
+                    cb = __expf(om - m_eff);
+                    l_new = lr[h] * ca + ol * cb;
+                }
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    float *dst = cm + 2 + sub * 8 + x;
+                    *dst = acc[h][x] * ca + (wv > 0 ? *dst * cb : 0.f);
+                }
+                __builtin_amdgcn_wave_barrier();
+                if (sub == 0) { cm[0] = m_new; cm[1] = l_new; }
+            }
+        }
+        __syncthreads();
+    }
+    float *dst = part + ((((size_t)b * S + s) * splits + split) * H) * (D + 2);
+    for (int x = tid; x < H * (D + 2); x += WAVE * NWAVE) dst[x] = comb[x];
+}
+
 template <typename T>
 __global__ void decode_merge_kernel(const float *__restrict__ part, T *__restrict__ O, int HPS, int DP, int splits)
 {
@@ -226,6 +371,19 @@ __global__ void decode_merge_kernel(const float *__restrict__ part, T *__restric
         for (int sp = 0; sp < splits; ++sp) a += base[sp * stride + 2 + x] * __expf(base[sp * stride] - mx);
         DElt<T>::st(O + (size_t)blockIdx.x * DP + x, a / l);
     }
+}
+
+template <int HPS>
+hipError_t run_gqa(const DecodeArgs &a, hipStream_t st)
+{
+    const Dims &d = a.d;
+    decode_gqa_kernel<HPS><<<d.B * d.S * a.splits, WAVE * NWAVE, 0, st>>>(
+        (const uint16_t *)a.q, (const uint16_t *)a.pool_rep, (const uint16_t *)a.sel_rep, (const uint16_t *)a.pool_tail,
+        (const uint16_t *)a.sel_tail, a.part, d.S, d.m, d.k, a.splits, d.scale, d.rep_logit_bias);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    decode_merge_kernel<uint16_t><<<d.B * d.H, 128, 0, st>>>(a.part, (uint16_t *)a.O, HPS, 128, a.splits);
+    return hipGetLastError();
 }
 
 template <typename T, int DP, int DS, bool MLA, int HPS>
@@ -275,10 +433,10 @@ size_t decode_workspace_bytes(const Dims &d)
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t st)
 {
     switch (shape_id(a.d)) {
-    case 101: return run<uint16_t, 128, 128, false, 1>(a, st);
-    case 102: return run<uint16_t, 128, 128, false, 2>(a, st);
-    case 104: return run<uint16_t, 128, 128, false, 4>(a, st);
-    case 108: return run<uint16_t, 128, 128, false, 8>(a, st);
+    case 101: return run_gqa<1>(a, st);
+    case 102: return run_gqa<2>(a, st);
+    case 104: return run_gqa<4>(a, st);
+    case 108: return run_gqa<8>(a, st);
     case 201: return run<uint16_t, 512, 64, true, 1>(a, st);
     case 216: return run<uint16_t, 512, 64, true, 16>(a, st);
     case 301: return run<float, 128, 32, true, 1>(a, st);
