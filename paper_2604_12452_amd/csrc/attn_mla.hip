@@ -53,6 +53,10 @@ constexpr int STAGE_BYTES = SEL_OFF + BN * DS * 2;   // 37 376
 constexpr int COPIES_PER_TILE = 9;      // direct-to-LDS loads one wavefront issues per tile (8 latent rows + 1 RoPE block)
 constexpr int NKS = DQK / 16;           // 36 k-steps of S^T
 constexpr int NDV = DV / 32;            // 16 value tiles
+#ifndef LCA_CHAIN_DEPTH
+#define LCA_CHAIN_DEPTH 6
+#endif
+constexpr int CHAIN_DEPTH = LCA_CHAIN_DEPTH;   // key fragments in flight ahead of the S^T chain
 constexpr float NEG_BIG = -1.0e30f;     // stands for -inf in running maxima (keeps exp2 arguments finite)
 constexpr float HEADROOM = 60.0f;       // base-2 exponent headroom above the reference before a pass is repeated
 
@@ -78,7 +82,10 @@ struct RowState {
 
 // Fragments of the V^T operand: two groups of PV_GROUP steps (double-buffered bursts of transpose reads).
 // Step j of the O^T update = (value tile j/2, k-step j%2).
-constexpr int PV_GROUP = 6;
+#ifndef LCA_PV_GROUP
+#define LCA_PV_GROUP 4
+#endif
+constexpr int PV_GROUP = LCA_PV_GROUP;
 struct PvFrags {
     bf16x4 lo[2][PV_GROUP], hi[2][PV_GROUP];
 };
@@ -142,7 +149,7 @@ __device__ __forceinline__ void issue_copy(const char *stage, const uint16_t *po
     for (int j = 0; j < COPIES_PER_TILE; ++j) issue_copy_part(j, stage, pool, sel, cd, wave, lane, sel_chunk);
 }
 
-// S^T chain of one tile (36 MFMAs into `snext`, key fragments prefetched four deep) and, when SOFTMAX,
+// S^T chain of one tile (36 MFMAs into `snext`, key fragments prefetched CHAIN_DEPTH deep) and, when SOFTMAX,
 // the vector work that turns the previous tile's S^T (`scur`) into P^T fragments, spread over the
 // chain's issue slots.  `kb` = LDS address of this lane's first key fragment of the chain's tile.
 // The MFMAs are inline assembly so that their accumulator is an ordinary vector register tuple (all 256
@@ -162,10 +169,10 @@ __device__ __forceinline__ void chain_and_softmax(const char *kb, const char *kb
         const char *p = ks < DP / 16 ? kb + ks * 32 : kb_sel + ((x6 ^ (2 * (ks - DP / 16))) << 4);
         return *reinterpret_cast<const bf16x8 *>(p);
     };
-    bf16x8 fr[4];
+    bf16x8 fr[CHAIN_DEPTH];
     if (CHAIN) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fr[i] = frag(i);
+        for (int i = 0; i < CHAIN_DEPTH; ++i) fr[i] = frag(i);
     }
     float mx[6], nb = 0.f, p[16];
 #pragma unroll
@@ -175,8 +182,8 @@ __device__ __forceinline__ void chain_and_softmax(const char *kb, const char *kb
             if (ks == 0)
                 asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(snext) : "v"(fr[0]), "v"(qf[0]));
             else
-                asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(snext) : "v"(fr[ks & 3]), "v"(qf[ks]));
-            if (ks + 4 < NKS) fr[ks & 3] = frag(ks + 4);
+                asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(snext) : "v"(fr[ks % CHAIN_DEPTH]), "v"(qf[ks]));
+            if (ks + CHAIN_DEPTH < NKS) fr[ks % CHAIN_DEPTH] = frag(ks + CHAIN_DEPTH);
         }
         if (SOFTMAX) {
             // slots 0..4: maxima of triples; 5..7: reduce and scale; 8: partner lane; 9: reference; 10..25: exponentials
@@ -337,18 +344,19 @@ restart:
                                               nullptr, nullptr, nullptr, CopyDesc(), wave, lane, sel_chunk);
     }
 
-    for (int tl = 0; tl < n_tiles; ++tl) {
-        // tile tl+1 has landed: its copy was issued two iterations ago, only tile tl+2's 9 loads may be pending ...
-        asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-        __syncthreads();      // ... for every wavefront, and every wavefront is done with tile tl-1
+    // tiles this wavefront sees completely (no masking): representatives [0, rep_full_end), raw [raw_full_lo, raw_full_hi)
+    const int rep_full_end = mt_w_lo / BN;
+    const int raw_full_lo = n_rep_tiles + (mt_w_hi * g - raw_lo_blk + BN - 1) / BN;
+    const int raw_full_hi = n_rep_tiles + max(0, (t_wfirst + 1 - raw_lo_blk) / BN);
 
+    for (int tl = 0; tl < n_tiles; ++tl) {
+        // everything that does not need the barrier comes before it, so that the chain starts right after it
         const bool is_rep = tl < n_rep_tiles;
-        const int e0 = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
         const float bias = is_rep ? kp.bias_log2 : 0.f;
         scur = snext;
-        // boundary tiles: hide the entries this row must not see
-        const bool full = is_rep ? (e0 + BN <= mt_w_lo) : (e0 + BN - 1 <= t_wfirst && e0 >= mt_w_hi * g);
-        if (!full) {
+        const bool full = tl < rep_full_end || (tl >= raw_full_lo && tl < raw_full_hi);
+        if (!full) {   // boundary tiles: hide the entries this row must not see
+            const int e0 = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int e = e0 + acc_entry(r, G);
@@ -361,8 +369,13 @@ restart:
         const char *dma_stage = stages[(tl + 3) & (NSTAGE - 1)];
         const char *chain_stage = stages[min(tl + 1, n_tiles - 1) & (NSTAGE - 1)], *pv_stage = stages[tl & (NSTAGE - 1)];
         const int tc = min(tl + 3, n_tiles - 1);
-        tile_step(dma_stage, chain_stage, pv_stage, tc < n_rep_tiles ? rep_pool : raw_pool, tc < n_rep_tiles ? rep_sel : raw_sel, copy_desc(tc),
-                  wave, lane, sel_chunk, k_off, ksel_off, x6, v_off, qf, snext, scur, pb, st, c, bias, acc);
+        const CopyDesc cd = copy_desc(tc);
+        const uint16_t *cpool = tc < n_rep_tiles ? rep_pool : raw_pool, *csel = tc < n_rep_tiles ? rep_sel : raw_sel;
+        // tile tl+1 has landed: its copy was issued two iterations ago, only tile tl+2's 9 loads may be pending ...
+        asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+        __syncthreads();      // ... for every wavefront, and every wavefront is done with tile tl-1
+        tile_step(dma_stage, chain_stage, pv_stage, cpool, csel, cd, wave, lane, sel_chunk, k_off, ksel_off, x6, v_off, qf, snext, scur, pb, st,
+                  c, bias, acc);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the trailing copies have landed before the stages are reused
     // every wavefront is done with the tile stages; repeat the pass if any row ran out of exponent headroom

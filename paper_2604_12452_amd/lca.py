@@ -12,7 +12,7 @@ import os
 from dataclasses import dataclass
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "liblca.so")
+LIB_PATH = os.environ.get("LCA_LIB_PATH", os.path.join(_PKG, "liblca.so"))   # override: another build of the same library
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 MODE_MLA, MODE_GQA = 0, 1
