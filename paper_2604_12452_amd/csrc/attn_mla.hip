@@ -57,6 +57,7 @@ constexpr int NDV = DV / 32;            // 16 value tiles
 #define LCA_CHAIN_DEPTH 6
 #endif
 constexpr int CHAIN_DEPTH = LCA_CHAIN_DEPTH;   // key fragments in flight ahead of the S^T chain
+constexpr int MLA_GRID = 256;            // workgroups of the persistent kernel = CUs of the chip
 constexpr float NEG_BIG = -1.0e30f;     // stands for -inf in running maxima (keeps exp2 arguments finite)
 constexpr float HEADROOM = 60.0f;       // base-2 exponent headroom above the reference before a pass is repeated
 
@@ -254,49 +255,93 @@ __device__ __forceinline__ void tile_step(const char *dma_stage, const char *cha
     LCA_FENCE();
 }
 
+// Everything one workgroup needs to know about one work item = 128 query rows of one (sequence, head).
+struct Blk {
+    int b, h, t0, t_last;                    // sequence, head, first / last query row
+    int t_row, mt_row, raw_lo_row;           // per lane: query row, representatives it sees, first raw token it sees
+    int raw_lo_blk, mt_blk_hi;               // first raw token / representatives any row of the block sees
+    int n_rep_tiles, n_tiles;
+    int rep_full_end, raw_full_lo, raw_full_hi;   // tiles this wavefront sees completely (no masking)
+    const uint16_t *rep_pool, *rep_sel, *raw_pool, *raw_sel;
+};
+
+__device__ __forceinline__ Blk make_blk(const MlaParams &kp, int b, int h, int qb, int wave, int n)
+{
+    Blk k;
+    const int L = kp.L, g = kp.g, w = kp.w;
+    auto groups_visible = [&](int t) { return (kp.dense || t + 1 <= w) ? 0 : (t + 1 - w) / g; };
+    k.b = b; k.h = h;
+    k.t0 = qb * BM;
+    k.t_last = min(k.t0 + BM, L) - 1;
+    const int t_wfirst = k.t0 + wave * 32, t_wlast = t_wfirst + 31;
+    k.t_row = t_wfirst + n;
+    k.mt_row = groups_visible(k.t_row);
+    k.raw_lo_row = k.mt_row * g;
+    const int mt_blk_lo = groups_visible(k.t0), mt_w_lo = groups_visible(t_wfirst), mt_w_hi = groups_visible(t_wlast);
+    k.mt_blk_hi = groups_visible(k.t_last);
+    k.raw_lo_blk = mt_blk_lo * g;
+    k.n_rep_tiles = (k.mt_blk_hi + BN - 1) / BN;
+    k.n_tiles = k.n_rep_tiles + (k.t_last + 1 - k.raw_lo_blk + BN - 1) / BN;
+    k.rep_full_end = mt_w_lo / BN;
+    k.raw_full_lo = k.n_rep_tiles + (mt_w_hi * g - k.raw_lo_blk + BN - 1) / BN;
+    k.raw_full_hi = k.n_rep_tiles + max(0, (t_wfirst + 1 - k.raw_lo_blk) / BN);
+    const int s = h / (kp.H / kp.S);
+    k.rep_pool = kp.pool_rep + ((size_t)b * kp.S + s) * kp.m * DP;
+    k.rep_sel = kp.sel_rep + ((size_t)b * kp.S + s) * kp.m * DS;
+    k.raw_pool = kp.POOL + (size_t)b * L * DP;
+    k.raw_sel = kp.SEL + (size_t)b * L * DS;
+    return k;
+}
+
+__device__ __forceinline__ CopyDesc copy_desc(const Blk &k, int tl)
+{
+    const bool is_rep = tl < k.n_rep_tiles;
+    CopyDesc cd;
+    cd.e0 = is_rep ? tl * BN : k.raw_lo_blk + (tl - k.n_rep_tiles) * BN;
+    cd.last = (is_rep ? k.mt_blk_hi : k.t_last + 1) - 1;
+    return cd;
+}
+
+// copies of tiles 0..2 of a work item into stages 0..2 (past the last tile: that tile again, nobody reads it)
+__device__ __forceinline__ void issue_first_copies(const Blk &k, char (*stages)[STAGE_BYTES], int wave, int lane, int sel_chunk)
+{
+    for (int tl = 0; tl < 3; ++tl) {
+        const int tc = min(tl, k.n_tiles - 1);
+        issue_copy(stages[tl], tc < k.n_rep_tiles ? k.rep_pool : k.raw_pool, tc < k.n_rep_tiles ? k.rep_sel : k.raw_sel, copy_desc(k, tc), wave,
+                   lane, sel_chunk);
+    }
+}
+
+// Q^T fragments of a work item: lane (n, G) holds Q[t_row, ks*16 + 8G .. +7]
+__device__ __forceinline__ void load_q(const MlaParams &kp, const Blk &k, int G, bf16x8 (&qf)[NKS])
+{
+    const uint16_t *qp = kp.Q + (((size_t)k.b * kp.L + min(k.t_row, kp.L - 1)) * kp.H + k.h) * DQK + G * 8;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+}
+
+// Persistent kernel: one workgroup per CU walks a list of work items.  Workgroup w lives on XCD w%8 (round-
+// robin placement) and is slot w/8 of that XCD; the XCD's item list is (query-block order x, x+8, ... of
+// the heaviest-first order) x (all heads), so that at any time the slots of an XCD work on the heads of
+// one or two query blocks and share their K/V tiles in that XCD's L2.  The next item's queries and first
+// tiles are requested before the current item's output is written, so the transition costs no round trip.
 __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
 {
     __shared__ __attribute__((aligned(1024))) char stages[NSTAGE][STAGE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, G = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int L = kp.L, H = kp.H;
 
-    // Workgroup -> (sequence, head, query block): ids with equal id%8 (same XCD under round-robin
-    // dispatch) walk the heads of one query block back to back, heaviest blocks first.
-    const int xcd = blockIdx.x & 7, kidx = blockIdx.x >> 3;
-    const int h = kidx % kp.H;
-    const int ord = (kidx / kp.H) * 8 + xcd;
-    if (ord >= kp.n_qb * kp.B) return;
-    const int b = ord % kp.B;
-    const int qb = kp.n_qb - 1 - ord / kp.B;
-    const int L = kp.L, H = kp.H, g = kp.g, w = kp.w;
-    const int s = h / (H / kp.S);
-
-    const int t0 = qb * BM;
-    const int t_last = min(t0 + BM, L) - 1;
-    const int t_row = t0 + wave * 32 + n;
-    const int t_wfirst = t0 + wave * 32, t_wlast = t_wfirst + 31;
-
-    auto groups_visible = [&](int t) { return (kp.dense || t + 1 <= w) ? 0 : (t + 1 - w) / g; };
-    const int mt_row = groups_visible(t_row), raw_lo_row = mt_row * g;
-    const int mt_blk_lo = groups_visible(t0), mt_blk_hi = groups_visible(t_last);
-    const int mt_w_lo = groups_visible(t_wfirst), mt_w_hi = groups_visible(t_wlast);
-    const int raw_lo_blk = mt_blk_lo * g;
-    const int n_rep_tiles = (mt_blk_hi + BN - 1) / BN;
-    const int n_raw_tiles = (t_last + 1 - raw_lo_blk + BN - 1) / BN;
-    const int n_tiles = n_rep_tiles + n_raw_tiles;
-
-    const uint16_t *rep_pool = kp.pool_rep + ((size_t)b * kp.S + s) * kp.m * DP;
-    const uint16_t *rep_sel = kp.sel_rep + ((size_t)b * kp.S + s) * kp.m * DS;
-    const uint16_t *raw_pool = kp.POOL + (size_t)b * L * DP;
-    const uint16_t *raw_sel = kp.SEL + (size_t)b * L * DS;
-
-    auto copy_desc = [&](int tl) {
-        const bool is_rep = tl < n_rep_tiles;
-        CopyDesc cd;
-        cd.e0 = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
-        cd.last = (is_rep ? mt_blk_hi : t_last + 1) - 1;
-        return cd;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, n_slots = gridDim.x >> 3;
+    const int n_units = kp.n_qb * kp.B;                       // (query block, sequence) pairs, heaviest first
+    const int items_per_xcd = ((n_units + 7) / 8) * H;        // some may fall past n_units
+    auto item = [&](int kidx, int &b, int &h, int &qb) {      // false when the item does not exist
+        h = kidx % H;
+        const int ord = (kidx / H) * 8 + xcd;
+        b = ord % kp.B;
+        qb = kp.n_qb - 1 - ord / kp.B;
+        return kidx < items_per_xcd && ord < n_units;
     };
 
     // per-lane LDS byte offsets
@@ -308,110 +353,117 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
     const int v_off = (4 * ((lane & 15) >> 2) + G) * RSB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;   // V^T transpose read
     // copy side of the swizzle: lane l of the RoPE copy fills slot l&7 of local row l>>3 (row 8*wave + (l>>3) of the tile)
     const int sel_chunk = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
-
-    // Q^T fragments: lane (n, G) holds Q[t_row, ks*16 + 8G .. +7]
-    bf16x8 qf[NKS];
-    {
-        const uint16_t *qp = kp.Q + (((size_t)b * L + min(t_row, L - 1)) * H + h) * DQK + G * 8;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
-    }
-
-    floatx16 acc[NDV];
-    RowState st;
-    float m_init = NEG_BIG;
     const float c = kp.scale_log2;
 
-restart:
-#pragma unroll
-    for (int i = 0; i < NDV; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-    st.m_ref = m_init; st.l_run = 0.f; st.m_seen = NEG_BIG; st.exceeded = false;
+    int kidx = slot, ib, ih, iqb;
+    while (kidx < items_per_xcd && !item(kidx, ib, ih, iqb)) kidx += n_slots;   // items past n_units only sit at the list's end
+    if (kidx >= items_per_xcd) return;
+    Blk cur = make_blk(kp, ib, ih, iqb, wave, n);
 
-    // prologue: three tiles in flight, then the S^T chain of tile 0
-    for (int tl = 0; tl < 3; ++tl) {
-        const int tc = min(tl, n_tiles - 1);
-        issue_copy(stages[tl], tc < n_rep_tiles ? rep_pool : raw_pool, tc < n_rep_tiles ? rep_sel : raw_sel, copy_desc(tc), wave, lane, sel_chunk);
-    }
-    floatx16 snext, scur;
-    bf16x8 pb[2];
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    {
-        PvFrags unused;
-        chain_and_softmax<true, false, false>(stages[0] + k_off, stages[0] + ksel_off, x6, qf, snext, snext, pb, st, c, 0.f, unused, nullptr,
-                                              nullptr, nullptr, nullptr, CopyDesc(), wave, lane, sel_chunk);
-    }
+    bf16x8 qf[NKS];
+    floatx16 acc[NDV];
+    RowState st;
+    issue_first_copies(cur, stages, wave, lane, sel_chunk);
+    load_q(kp, cur, G, qf);
 
-    // tiles this wavefront sees completely (no masking): representatives [0, rep_full_end), raw [raw_full_lo, raw_full_hi)
-    const int rep_full_end = mt_w_lo / BN;
-    const int raw_full_lo = n_rep_tiles + (mt_w_hi * g - raw_lo_blk + BN - 1) / BN;
-    const int raw_full_hi = n_rep_tiles + max(0, (t_wfirst + 1 - raw_lo_blk) / BN);
-
-    for (int tl = 0; tl < n_tiles; ++tl) {
-        // everything that does not need the barrier comes before it, so that the chain starts right after it
-        const bool is_rep = tl < n_rep_tiles;
-        const float bias = is_rep ? kp.bias_log2 : 0.f;
-        scur = snext;
-        const bool full = tl < rep_full_end || (tl >= raw_full_lo && tl < raw_full_hi);
-        if (!full) {   // boundary tiles: hide the entries this row must not see
-            const int e0 = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
+    while (true) {
+        float m_init = NEG_BIG;
+    restart:
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int e = e0 + acc_entry(r, G);
-                const bool vis = is_rep ? (e < mt_row) : (e >= raw_lo_row && e <= t_row);
-                scur[r] = vis ? scur[r] : -INFINITY;
-            }
+        for (int i = 0; i < NDV; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+        st.m_ref = m_init; st.l_run = 0.f; st.m_seen = NEG_BIG; st.exceeded = false;
+
+        // the first tiles and the queries of this item are on their way; then the S^T chain of tile 0
+        floatx16 snext, scur;
+        bf16x8 pb[2];
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        {
+            PvFrags unused;
+            chain_and_softmax<true, false, false>(stages[0] + k_off, stages[0] + ksel_off, x6, qf, snext, snext, pb, st, c, 0.f, unused, nullptr,
+                                                  nullptr, nullptr, nullptr, CopyDesc(), wave, lane, sel_chunk);
         }
-        // The chain and the copy always run: past the last tile they redo that tile (S^T that nobody reads, a
-        // copy into a stage that nobody reads again), which keeps the loop body branch-free.
-        const char *dma_stage = stages[(tl + 3) & (NSTAGE - 1)];
-        const char *chain_stage = stages[min(tl + 1, n_tiles - 1) & (NSTAGE - 1)], *pv_stage = stages[tl & (NSTAGE - 1)];
-        const int tc = min(tl + 3, n_tiles - 1);
-        const CopyDesc cd = copy_desc(tc);
-        const uint16_t *cpool = tc < n_rep_tiles ? rep_pool : raw_pool, *csel = tc < n_rep_tiles ? rep_sel : raw_sel;
-        // tile tl+1 has landed: its copy was issued two iterations ago, only tile tl+2's 9 loads may be pending ...
-        asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-        __syncthreads();      // ... for every wavefront, and every wavefront is done with tile tl-1
-        tile_step(dma_stage, chain_stage, pv_stage, cpool, csel, cd, wave, lane, sel_chunk, k_off, ksel_off, x6, v_off, qf, snext, scur, pb, st,
-                  c, bias, acc);
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the trailing copies have landed before the stages are reused
-    // every wavefront is done with the tile stages; repeat the pass if any row ran out of exponent headroom
-    if (__syncthreads_or(st.exceeded)) {
-        m_init = st.m_seen;
-        goto restart;
-    }
 
-    // ---- epilogue: normalise, transpose through LDS (two passes of 256 value columns), store coalesced ----
-    const float l_tot = st.l_run + __shfl_xor(st.l_run, 32, 64);
-    const float inv = 1.f / l_tot;
-    constexpr int ORS = 256 * 2 + 16;                    // staging row stride (bytes)
-    static_assert(4 * 32 * ORS <= NSTAGE * STAGE_BYTES, "output staging must fit in the tile stages");
-    char *obuf = &stages[0][0] + wave * 32 * ORS;
+        for (int tl = 0; tl < cur.n_tiles; ++tl) {
+            // everything that does not need the barrier comes before it, so that the chain starts right after it
+            const bool is_rep = tl < cur.n_rep_tiles;
+            const float bias = is_rep ? kp.bias_log2 : 0.f;
+            scur = snext;
+            const bool full = tl < cur.rep_full_end || (tl >= cur.raw_full_lo && tl < cur.raw_full_hi);
+            if (!full) {   // boundary tiles: hide the entries this row must not see
+                const int e0 = is_rep ? tl * BN : cur.raw_lo_blk + (tl - cur.n_rep_tiles) * BN;
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-#pragma unroll
-        for (int d8 = 0; d8 < 8; ++d8)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                union { bf16x4 h; uint2 u; } o;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) o.h[i] = (__bf16)(acc[pass * 8 + d8][r4 * 4 + i] * inv);
-                *reinterpret_cast<uint2 *>(obuf + n * ORS + (d8 * 32 + 8 * r4 + 4 * G) * 2) = o.u;
+                for (int r = 0; r < 16; ++r) {
+                    const int e = e0 + acc_entry(r, G);
+                    const bool vis = is_rep ? (e < cur.mt_row) : (e >= cur.raw_lo_row && e <= cur.t_row);
+                    scur[r] = vis ? scur[r] : -INFINITY;
+                }
             }
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll 4
-        for (int r2 = 0; r2 < 16; ++r2) {                // one wave-wide store covers two rows of 512 B
-            const int r = r2 * 2 + G, t = t_wfirst + r;
-            const uint4 v = *reinterpret_cast<const uint4 *>(obuf + r * ORS + n * 16);
-            if (t < L) *reinterpret_cast<uint4 *>(kp.O + (((size_t)b * L + t) * H + h) * DV + pass * 256 + n * 8) = v;
+            // The chain and the copy always run: past the last tile they redo that tile (S^T that nobody reads, a
+            // copy into a stage that nobody reads again), which keeps the loop body branch-free.
+            const char *dma_stage = stages[(tl + 3) & (NSTAGE - 1)];
+            const char *chain_stage = stages[min(tl + 1, cur.n_tiles - 1) & (NSTAGE - 1)], *pv_stage = stages[tl & (NSTAGE - 1)];
+            const int tc = min(tl + 3, cur.n_tiles - 1);
+            const CopyDesc cd = copy_desc(cur, tc);
+            const uint16_t *cpool = tc < cur.n_rep_tiles ? cur.rep_pool : cur.raw_pool, *csel = tc < cur.n_rep_tiles ? cur.rep_sel : cur.raw_sel;
+            // tile tl+1 has landed: its copy was issued two iterations ago, only tile tl+2's 9 loads may be pending ...
+            asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+            __syncthreads();      // ... for every wavefront, and every wavefront is done with tile tl-1
+            tile_step(dma_stage, chain_stage, pv_stage, cpool, csel, cd, wave, lane, sel_chunk, k_off, ksel_off, x6, v_off, qf, snext, scur, pb,
+                      st, c, bias, acc);
         }
-        __builtin_amdgcn_wave_barrier();
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the trailing copies have landed before the stages are reused
+        // every wavefront is done with the tile stages; repeat the pass if any row ran out of exponent headroom
+        if (__syncthreads_or(st.exceeded)) {
+            m_init = st.m_seen;
+            issue_first_copies(cur, stages, wave, lane, sel_chunk);
+            goto restart;
+        }
+
+        // request the next item's first tiles (stages 0..2) and queries before writing this item's output
+        int nb, nh, nqb;
+        kidx += n_slots;
+        const bool has_next = item(kidx, nb, nh, nqb);
+        const int out_b = cur.b, out_h = cur.h, out_t0 = cur.t0, out_t_row = cur.t_row;
+        if (has_next) {
+            cur = make_blk(kp, nb, nh, nqb, wave, n);
+            issue_first_copies(cur, stages, wave, lane, sel_chunk);
+            load_q(kp, cur, G, qf);
+        }
+
+        // ---- epilogue: normalise, transpose through LDS stage 3 (four passes of 128 value columns), store coalesced ----
+        const float l_tot = st.l_run + __shfl_xor(st.l_run, 32, 64);
+        const float inv = 1.f / l_tot;
+        constexpr int ORS = 128 * 2 + 16;                    // staging row stride (bytes)
+        static_assert(4 * 32 * ORS <= STAGE_BYTES, "output staging must fit in one tile stage");
+        char *obuf = &stages[3][0] + wave * 32 * ORS;
+        const int t_wfirst = out_t0 + wave * 32;
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+#pragma unroll
+            for (int d4 = 0; d4 < 4; ++d4)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    union { bf16x4 h; uint2 u; } o;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o.h[i] = (__bf16)(acc[pass * 4 + d4][r4 * 4 + i] * inv);
+                    *reinterpret_cast<uint2 *>(obuf + n * ORS + (d4 * 32 + 8 * r4 + 4 * G) * 2) = o.u;
+                }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int r4 = 0; r4 < 8; ++r4) {                 // one wave-wide store covers four rows of 256 B
+                const int r = r4 * 4 + (lane >> 4), t = t_wfirst + r;
+                const uint4 v = *reinterpret_cast<const uint4 *>(obuf + r * ORS + (lane & 15) * 16);
+                if (t < L) *reinterpret_cast<uint4 *>(kp.O + (((size_t)out_b * L + t) * H + out_h) * DV + pass * 128 + (lane & 15) * 8) = v;
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        if (kp.lse != nullptr && G == 0 && out_t_row < L)
+            kp.lse[((size_t)out_b * L + out_t_row) * H + out_h] = (st.m_ref + log2f(l_tot)) * 0.6931471805599453f;
+        if (!has_next) break;
     }
-    if (kp.lse != nullptr && G == 0 && t_row < L)
-        kp.lse[((size_t)b * L + t_row) * H + h] = (st.m_ref + log2f(l_tot)) * 0.6931471805599453f;
 }
 
 }  // namespace
@@ -432,8 +484,10 @@ hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st)
     kp.n_qb = (d.L + BM - 1) / BM;
     kp.scale_log2 = d.scale * 1.4426950408889634f;
     kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
-    const long units = (long)kp.n_qb * d.B;
-    const long grid = ((units + 7) / 8) * 8 * d.H;
+    // persistent grid: one workgroup per CU (a workgroup takes all of a CU's LDS and registers)
+    const long items = (((long)kp.n_qb * d.B + 7) / 8) * 8 * d.H;
+    long grid = items < MLA_GRID ? items : MLA_GRID;
+    grid = (grid + 7) / 8 * 8;
     attn_mla_kernel<<<(unsigned)grid, 256, 0, st>>>(kp);
     return hipGetLastError();
 }
