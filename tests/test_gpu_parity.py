@@ -88,9 +88,10 @@ def test_mla_topic_shift_inputs(oracle):
 
 
 # ---- MFMA kernel at the GQA widths (128 / 128) --------------------------------------------------------
-@pytest.mark.parametrize("L,g,w,H,S", [(700, 16, 100, 8, 2), (300, 8, 0, 4, 4), (129, 16, 64, 4, 1)])
-def test_gqa_mfma_small_all_rows(oracle, L, g, w, H, S):
-    wl = inputs.Workload("gqa_small", B=1, L=L, H=H, S=S, d_pool=128, d_sel=128, g=g, w=w, dtype="bf16", mode=inputs.MODE_GQA,
+@pytest.mark.parametrize("B,L,g,w,H,S", [(1, 700, 16, 100, 8, 2), (1, 300, 8, 0, 4, 4), (1, 129, 16, 64, 4, 1), (2, 515, 16, 32, 4, 2),
+                                           (2, 260, 4, 7, 16, 2), (1, 31, 4, 2, 8, 2), (1, 1100, 32, 256, 8, 1)])
+def test_gqa_mfma_small_all_rows(oracle, B, L, g, w, H, S):
+    wl = inputs.Workload("gqa_small", B=B, L=L, H=H, S=S, d_pool=128, d_sel=128, g=g, w=w, dtype="bf16", mode=inputs.MODE_GQA,
                          theta=500000.0, seed=11 + L)
     _full_parity(oracle, wl)
 
@@ -186,6 +187,35 @@ def test_mla_logits_far_above_first_tile(oracle, dense_only):
     keys = np.concatenate([POOLf[0], SELf[0]], -1)
     logits = keys[:351] @ Qf[0, 350, 0]
     spread = logits.max() - logits[:32].max()
+    assert spread > 60.0, f"the test input must exceed the kernel's headroom (spread {spread:.1f} nats)"
+    if dense_only:
+        run.dense()
+        hp.check_dense(oracle, wl, run, rows, Qf, POOLf, SELf)
+    else:
+        run.prefill()
+        hp.check_prefill(oracle, wl, run, rows, Qf, POOLf, SELf, ref, differ)
+
+
+@pytest.mark.parametrize("dense_only", [False, True])
+def test_gqa_logits_far_above_first_tile(oracle, dense_only):
+    """The same situation at the GQA widths: keys of two tokens score ~100 nats above the first key tile, in
+    every KV head, so the 128-wide kernel's repeat pass has to run."""
+    wl = inputs.Workload("gqa_spike", B=1, L=420, H=8, S=2, d_pool=128, d_sel=128, g=16, w=64, dtype="bf16", mode=inputs.MODE_GQA,
+                         theta=500000.0, seed=78)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    Qf, SELf = inputs.to_f64(Q, wl.dtype), inputs.to_f64(SEL, wl.dtype)
+    qdir = Qf[0].mean(axis=(0, 1))
+    qdir /= np.linalg.norm(qdir)
+    Qf[0] += 2.0 * qdir
+    for tok in (100, 300):                  # both beyond the first 64-key tile of plain causal attention
+        SELf[0, tok] = 50.0 * qdir
+    Q, SEL = inputs.to_storage(Qf, wl.dtype), inputs.to_storage(SELf, wl.dtype)
+    Qf, POOLf, SELf = (inputs.to_f64(x, wl.dtype) for x in (Q, POOL, SEL))
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense()
+    ref, differ = hp.check_condense(oracle, wl, run, Qf[:, wl.L - wl.nq:], POOLf, SELf)
+    rows = np.arange(wl.L, dtype=np.int32)
+    logits = SELf[0, :351, 0] @ Qf[0, 350, 0]
+    spread = logits.max() - logits[:64].max()
     assert spread > 60.0, f"the test input must exceed the kernel's headroom (spread {spread:.1f} nats)"
     if dense_only:
         run.dense()
