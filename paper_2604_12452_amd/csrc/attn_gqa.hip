@@ -15,8 +15,11 @@
 //   S^T[key, query] = K Q^T      16-byte key reads, lane = S^T row m reads LDS row pi(m)
 //   O^T[dv, query] += V^T P^T    transpose reads (ds_read_b64_tr_b16), each 16-lane block touches rows 4 apart
 // with pi(8h + 4G + j) = 4j + 2h + G inside each 16 rows (the S^T accumulator registers then already are
-// the B fragments of the second product).  Softmax uses one fixed reference per row (first tile) and a
-// repeat pass if the exponent headroom of 2^60 is ever exceeded, so O^T is never rescaled.
+// the B fragments of the second product).  Softmax uses one fixed reference per row (the first entries the
+// row sees), so O^T is never rescaled and no maxima are taken in the steady state; row sums that end beyond
+// 2^100 make the workgroup repeat the work from exact maxima.
+#include <type_traits>
+
 #include "lca_internal.h"
 
 namespace lca {
@@ -24,6 +27,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int D = 128;                  // d_k = d_v
@@ -31,18 +35,18 @@ constexpr int BN = 64;                  // entries per tile (two halves of 32)
 constexpr int RB = D * 2;               // row bytes
 constexpr int V_OFF = BN * RB;          // the value rows of a stage start here
 constexpr int STAGE_BYTES = 2 * BN * RB;   // 32 768
+constexpr int NSTAGE = 4;               // two pairs of tiles: one in use, one on its way
+constexpr int NW = 8;                   // wavefronts per workgroup
 constexpr int NKS = D / 16;             // 8 k-steps of S^T
 constexpr int NDV = D / 32;             // 4 value tiles
-constexpr int COPIES_PER_TILE = 8;      // direct-to-LDS loads per wavefront and tile (4 for K, 4 for V)
 constexpr float NEG_BIG = -1.0e30f;
-constexpr float HEADROOM = 60.0f;
 
 struct GqaParams {
     const uint16_t *Q, *K, *V, *k_rep, *v_rep;
     uint16_t *O;
     float *lse;
     int B, L, H, S, g, w, m, dense;
-    int hw, rbs;        // query heads per workgroup (min(H/S, 4)), 32-row blocks per workgroup (4 / hw)
+    int hw, rbs;        // query heads per workgroup (min(H/S, 4)), 32-row blocks per workgroup (8 / hw)
     int n_qb, n_units;  // query blocks per sequence; KV-sharing units = B * S * (H/S / hw)
     float scale_log2, bias_log2;
 };
@@ -59,9 +63,9 @@ __device__ __forceinline__ void dma_1k(unsigned voff, const void *base, unsigned
 }
 __device__ __forceinline__ unsigned lds_address(const char *p) { return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char *)p; }
 
-__global__ __launch_bounds__(256, 2) void attn_gqa_kernel(const GqaParams kp)
+__global__ __launch_bounds__(64 * NW, 1) void attn_gqa_kernel(const GqaParams kp)
 {
-    __shared__ __attribute__((aligned(1024))) char stages[2][STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char stages[NSTAGE][STAGE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, G = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -92,42 +96,45 @@ __global__ __launch_bounds__(256, 2) void attn_gqa_kernel(const GqaParams kp)
     const uint16_t *k_raw = kp.K + ((size_t)b * L * kp.S + s) * D, *v_raw = kp.V + ((size_t)b * L * kp.S + s) * D;
     const int raw_stride = kp.S * RB;
 
-    // copy of tile tl: this wavefront moves rows 16*wave .. 16*wave+15 of K and of V, 4 rows per load; lane l
+    // copy of tile tl: this wavefront moves rows 8*wave .. 8*wave+7 of K and of V, 4 rows per load; lane l
     // fills slot l&15 of local row l>>4 with the chunk the swizzle assigns to that slot
-    const int c0 = (lane & 15) ^ (lane >> 4);
+    constexpr int RPW = BN / NW, NQ = RPW / 4;                 // rows and loads (per operand) per wavefront
+    const int lrow = lane >> 4;
+    const int ksw = ((lane & 15) ^ lrow) << 4, vsw = (lane & 15) << 4;   // K: chunk ^ (row & 15); V: chunk ^ (row & 12)
     auto issue_copy = [&](int tl) {
         const bool is_rep = tl < n_rep_tiles;
-        const int e0 = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
+        const int e0 = (is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN) + RPW * wave;
         const int last = (is_rep ? mt_blk_hi : t_last + 1) - 1;
         const int stride = is_rep ? RB : raw_stride;
-        const uint16_t *kb = is_rep ? k_rep : k_raw, *vb = is_rep ? v_rep : v_raw;
-        const unsigned st = lds_address(stages[tl & 1]);
+        const char *kb = (const char *)(is_rep ? k_rep : k_raw), *vb = (const char *)(is_rep ? v_rep : v_raw);
+        const unsigned st = lds_address(stages[tl & (NSTAGE - 1)]) + RPW * wave * RB;
+        const bool inside = e0 + RPW - 1 <= last;               // else rows past the segment: clamped, masked later
+        const char *kt = kb + (inside ? (size_t)e0 * stride : 0), *vt = vb + (inside ? (size_t)e0 * stride : 0);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int row = 16 * wave + 4 * q;                                   // first of the 4 rows of this load
-            const int e = min(e0 + row + (lane >> 4), last);                     // rows past the segment: clamped, masked later
-            const unsigned voff = (unsigned)e * stride + ((c0 ^ (4 * q)) << 4);
-            dma_1k(voff, kb, st + row * RB);
-            dma_1k(voff, vb, st + V_OFF + row * RB);
+        for (int q = 0; q < NQ; ++q) {
+            const int swz = (((RPW * wave) & 8) ^ (4 * q)) << 4;   // bits 2..3 of the row, uniform
+            const unsigned rowoff = inside ? (unsigned)(4 * q + lrow) * stride : (unsigned)min(e0 + 4 * q + lrow, last) * stride;
+            dma_1k(rowoff + (ksw ^ swz), kt, st + 4 * q * RB);
+            dma_1k(rowoff + (vsw ^ swz), vt, st + V_OFF + 4 * q * RB);
         }
     };
 
-    // per-lane LDS byte offsets
+    // per-lane LDS addresses of the operand fragments in the current stage (they alternate between the stages
+    // as the tiles go by); halves and k-steps are immediate offsets
     const int krow = lds_row_of_m(n), xk = krow & 15;
-    int k_off[NKS];                                            // S^T operand: chunk 2ks+G of row krow sits at slot (2ks+G)^xk
+    const unsigned stage0 = lds_address(stages[0]);
+    unsigned k_addr[NKS];                                      // S^T operand: chunk 2ks+G of row krow sits at slot (2ks+G)^xk
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) k_off[ks] = krow * RB + (((2 * ks + G) ^ xk) << 4);
-    int v_off[NDV][2];                                         // V^T operand, per value tile and run h of four keys
+    for (int ks = 0; ks < NKS; ++ks) k_addr[ks] = stage0 + krow * RB + (((2 * ks + G) ^ xk) << 4);
+    unsigned v_addr[NDV];                                      // V^T operand per value tile: chunk c of row r sits at slot c^(r&12)
     {
         const int p = lane & 15, j = p >> 2, blk = (lane >> 4) & 1, pp = (p & 3) >> 1;
 #pragma unroll
-        for (int dvt = 0; dvt < NDV; ++dvt)
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                const int row = 4 * j + 2 * hh + G;            // + 16*kk + 32*half
-                const int chunk = 4 * dvt + 2 * blk + pp;
-                v_off[dvt][hh] = V_OFF + row * RB + ((chunk ^ (row & 15)) << 4) + 8 * (p & 1);
-            }
+        for (int dvt = 0; dvt < NDV; ++dvt) {
+            const int row = 4 * j + G;                         // + 2*hh + 16*kk + 32*half
+            const int chunk = 4 * dvt + 2 * blk + pp;
+            v_addr[dvt] = stage0 + V_OFF + row * RB + ((chunk ^ (4 * j)) << 4) + 8 * (p & 1);
+        }
     }
 
     // Q^T fragments
@@ -136,101 +143,201 @@ __global__ __launch_bounds__(256, 2) void attn_gqa_kernel(const GqaParams kp)
         const uint16_t *qp = kp.Q + (((size_t)b * L + min(t_row, L - 1)) * H + h) * D + G * 8;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+        // the loads complete here: otherwise the compiler waits for them (and with them for every tile copy
+        // issued in between) inside the tile loop
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[ks]));
     }
 
     floatx16 acc[NDV];
-    float m_ref, l_run, m_seen, m_init = NEG_BIG;
-    bool exceeded;
+    float m_ref = NEG_BIG, l_run = 0.f, m_seen = NEG_BIG;
     const float c = kp.scale_log2;
     typedef __attribute__((address_space(3))) bf16x4 *lds_b64_ptr;
 
-restart:
-#pragma unroll
-    for (int i = 0; i < NDV; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-    m_ref = m_init; l_run = 0.f; m_seen = NEG_BIG; exceeded = false;
-    issue_copy(0);
+    typedef const __attribute__((address_space(3))) bf16x8 *lds_b128_ptr;
+    // LDS fragment reads.  Tiles are worked on in pairs that sit in adjacent stages; `q` = 0..3 counts the halves
+    // of 32 entries of the pair.  K: chunk ks of this lane's row.  V^T: fragment i = (k-step kk = i / 4, value
+    // tile dvt = i % 4), two transpose reads of four keys each.
+    auto load_k = [&](int q, int ks) { return *(lds_b128_ptr)(uintptr_t)(k_addr[ks] + (q / 2) * STAGE_BYTES + (q % 2) * 32 * RB); };
+    auto load_v = [&](int q, int i) {
+        const unsigned o = (q / 2) * STAGE_BYTES + ((q % 2) * 32 + (i / NDV) * 16) * RB;
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(uintptr_t)(v_addr[i % NDV] + o));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(uintptr_t)(v_addr[i % NDV] + o + 2 * RB));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
 
-    for (int tl = 0; tl < n_tiles; ++tl) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's share of tile tl has landed
-        __syncthreads();                                   // ... and everyone's; everyone is done with tile tl-1
-        if (tl + 1 < n_tiles) issue_copy(tl + 1);
-        const char *cur = stages[tl & 1];
-        const bool is_rep = tl < n_rep_tiles;
-        const int e_tile = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
-        const float bias = is_rep ? kp.bias_log2 : 0.f;
-
-#pragma unroll 1
-        for (int half = 0; half < 2; ++half) {
-            const int e0 = e_tile + half * 32;
-            const bool none = is_rep ? (e0 >= mt_w_hi) : (e0 > t_wlast || e0 + 32 <= mt_w_lo * g);
-            if (none) continue;                            // no row of this wavefront sees this half (wave-uniform)
-            const bool full = is_rep ? (e0 + 32 <= mt_w_lo) : (e0 + 31 <= t_wfirst && e0 >= mt_w_hi * g);
-            const char *hb = cur + half * 32 * RB;
-
-            // S^T = K Q^T
-            floatx16 sacc;
+    // Pass 0 is the normal one: every row fixes its reference at the first entries it sees and never looks at
+    // maxima again.  Its probabilities may grow up to 2^100 above that; only if a row sum ends beyond that (or
+    // not finite) the workgroup runs pass 1, which finds every row's true maximum, and pass 2, the normal pass
+    // from those maxima.
+    //
+    // The workgroup synchronises once per PAIR of tiles (the wavefronts of a SIMD stall together at a barrier, so
+    // barriers are kept rare): the pair's copies were requested a pair earlier, into the two stages the pair
+    // before that used.  A tile is scheduled by hand in four phases of eight MFMAs, the softmax of one half
+    // sitting between the MFMAs of the other; LDS fragments are requested four MFMAs before their use (left
+    // alone, the compiler issues each read right before its MFMA and waits out the LDS latency every time).
+    constexpr int RING = 4;
+    for (int pass = 0;; ++pass) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+        for (int i = 0; i < NDV; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+        l_run = 0.f;
+        if (pass == 2) m_ref = m_seen;
+        const bool maxima_only = pass == 1;
+        bool ref_missing = pass != 2;                           // wave-uniform: some row has no reference yet
+        issue_copy(0);
+        if (1 < n_tiles) issue_copy(1);
+
+        bf16x8 kf[RING], vf[RING];
+        // one tile; `sub` = 0, 1: its place in the pair (a compile-time constant)
+        auto do_tile = [&](int tl, auto sub_c) {
+            constexpr int sub = decltype(sub_c)::value;
+            const bool is_rep = tl < n_rep_tiles;
+            const int e_tile = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
+            const float bias = is_rep ? kp.bias_log2 : 0.f;
+            // every row of this wavefront sees all 64 entries: the steady state
+            const bool tile_full = is_rep ? (e_tile + BN <= mt_w_lo) : (e_tile + BN - 1 <= t_wfirst && e_tile >= mt_w_hi * g);
+            // K fragment f = (half f / 8 of the pair, k-step f % 8); V^T fragment f = (half f / 8 of the tile, fragment f % 8)
+            auto req_k = [&](int f) { if (f < 4 * NKS) kf[f % RING] = load_k(f / NKS, f % NKS); };
+            auto req_v = [&](int f) { if (f < 4 * NDV) vf[f % RING] = load_v(2 * sub + f / (2 * NDV), f % (2 * NDV)); };
+
+            floatx16 sacc[2];
+#pragma unroll
+            for (int half = 0; half < 2; ++half)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[half][r] = 0.f;
+            // boundary tiles: hide what a row must not see; rows without a reference take the maximum of what they see
+            auto mask_and_reference = [&](int half) {
+                if (!tile_full) {
+                    const int e0 = e_tile + half * 32;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int e = e0 + acc_entry(r, G);
+                        const bool vis = is_rep ? (e < mt_row) : (e >= raw_lo_row && e <= t_row);
+                        sacc[half][r] = vis ? sacc[half][r] : -INFINITY;
+                    }
+                }
+                if (ref_missing || maxima_only) {
+                    float tmax = sacc[half][0];
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[half][r]);
+                    tmax = fmaxf(fmaf(tmax, c, bias), NEG_BIG);
+                    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+                    m_seen = fmaxf(m_seen, tmax);
+                    if (!maxima_only) {
+                        m_ref = (m_ref == NEG_BIG) ? tmax : m_ref;
+                        ref_missing = __builtin_amdgcn_ballot_w64(m_ref == NEG_BIG) != 0;
+                    }
+                }
+            };
+            // P^T = exp2(S^T * c + bias - reference) in bf16 and its row sums, two S^T registers at a time so that the
+            // work can sit between MFMAs.  Accumulator registers 0..7 / 8..15 are the B operands of the two k-steps of
+            // the second product as they are.  The sums are taken over the rounded values, the ones the second
+            // product sees.  A row that has seen nothing yet has reference -1e30 and only -inf logits: its
+            // probabilities are exact zeros.
+            union Pb { bf16x8 v[2]; bf16x2 p[8]; } pb[2];
+            const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+            float nb = 0.f;
+            auto softmax_pair = [&](int half, int i) {
+                bf16x2 pr;
+                pr[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[half][2 * i], c, nb));
+                pr[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[half][2 * i + 1], c, nb));
+                pb[half].p[i] = pr;
+                l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_run, false);
+            };
+
+            // phase 1: S^T of the first half
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(hb + k_off[ks]);
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc, 0, 0, 0);
+                sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % RING], qf[ks], sacc[0], 0, 0, 0);
+                req_k(2 * sub * NKS + ks + RING);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            // mask, maximum, reference
-            if (!full) {
+            if (!tile_full || ref_missing || maxima_only) mask_and_reference(0);
+            nb = bias - m_ref;
+            __builtin_amdgcn_sched_barrier(0);
+            // phase 2: S^T of the second half, the first half's softmax between its MFMAs
+            if (maxima_only) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int e = e0 + acc_entry(r, G);
-                    const bool vis = is_rep ? (e < mt_row) : (e >= raw_lo_row && e <= t_row);
-                    sacc[r] = vis ? sacc[r] : -INFINITY;
+                for (int ks = 0; ks < NKS; ++ks) {
+                    sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % RING], qf[ks], sacc[1], 0, 0, 0);
+                    req_k((2 * sub + 1) * NKS + ks + RING);    // runs into the pair's second tile
+                }
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) {
+                    sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % RING], qf[ks], sacc[1], 0, 0, 0);
+                    if (ks < NKS - RING) req_k((2 * sub + 1) * NKS + ks + RING);
+                    else req_v(ks - (NKS - RING));
+                    softmax_pair(0, ks);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            float tmax = sacc[0];
+            if (!tile_full || ref_missing || maxima_only) mask_and_reference(1);
+            if (!maxima_only) {
+                nb = bias - m_ref;
+                __builtin_amdgcn_sched_barrier(0);
+                // phase 3: second product of the first half, the second half's softmax between its MFMAs
 #pragma unroll
-            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[r]);
-            tmax = fmaxf(fmaf(tmax, c, bias), NEG_BIG);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            m_ref = (m_ref == NEG_BIG) ? tmax : m_ref;     // first visible keys of this row fix its reference
-            m_seen = fmaxf(m_seen, tmax);
-            exceeded |= tmax > m_ref + HEADROOM;
-            const float nb = bias - m_ref;
-            // P^T = exp2(S^T * c + bias - ref): registers 0..7 / 8..15 are the two k-steps of the second product
-            bf16x8 pb[2];
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[kk * 8 + i], c, nb));
-                    l_run += pv;
-                    pb[kk][i] = (__bf16)pv;
+                for (int i = 0; i < 2 * NDV; ++i) {
+                    acc[i % NDV] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % RING], pb[0].v[i / NDV], acc[i % NDV], 0, 0, 0);
+                    req_v(i + RING);
+                    softmax_pair(1, i);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-            // O^T += V^T P^T
+                // phase 4: second product of the second half; the first K fragments of the pair's second tile requested
+                // (if the pair has none, they are read from the stage all the same and never used)
 #pragma unroll
-            for (int dvt = 0; dvt < NDV; ++dvt)
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
-                    const char *vb = hb + kk * 16 * RB;
-                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vb + v_off[dvt][0]));
-                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vb + v_off[dvt][1]));
-                    const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    acc[dvt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kk], acc[dvt], 0, 0, 0);
+                for (int i = 0; i < 2 * NDV; ++i) {
+                    acc[i % NDV] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % RING], pb[1].v[i / NDV], acc[i % NDV], 0, 0, 0);
+                    req_v(2 * NDV + i + RING);
+                    if (sub == 0 && i >= 2 * NDV - RING) req_k(2 * NKS + i - (2 * NDV - RING));
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-        }
-    }
+            }
+        };
 
-    // every wavefront is done with the stages; repeat the pass if any row ran out of exponent headroom
-    if (__syncthreads_or(exceeded)) {
-        m_init = m_seen;
-        goto restart;
+        for (int tl = 0; tl < n_tiles; tl += 2) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's share of the pair has landed
+            __syncthreads();                                   // ... and everyone's; everyone is done with the pair before
+#pragma unroll
+            for (int f = 0; f < RING; ++f) kf[f] = load_k(0, f);
+            __builtin_amdgcn_sched_barrier(0);
+            if (tl + 2 < n_tiles) issue_copy(tl + 2);          // into the stages of the pair before
+            if (tl + 3 < n_tiles) issue_copy(tl + 3);
+            __builtin_amdgcn_sched_barrier(0);
+            do_tile(tl, std::integral_constant<int, 0>());
+            if (tl + 1 < n_tiles) do_tile(tl + 1, std::integral_constant<int, 1>());
+            // the other two stages next
+            const int flip = (tl & 2) ? -2 * STAGE_BYTES : 2 * STAGE_BYTES;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) k_addr[ks] += flip;
+#pragma unroll
+            for (int i = 0; i < NDV; ++i) v_addr[i] += flip;
+        }
+        if (((n_tiles + 1) / 2) & 1) {                          // back to stage 0 for another pass
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) k_addr[ks] -= 2 * STAGE_BYTES;
+#pragma unroll
+            for (int i = 0; i < NDV; ++i) v_addr[i] -= 2 * STAGE_BYTES;
+        }
+
+        // every wavefront is done with the stages
+        if (pass == 0) {
+            const float l_chk = l_run + __shfl_xor(l_run, 32, 64);
+            if (!__syncthreads_or(!(l_chk <= 0x1p100f))) break;
+        } else {
+            __syncthreads();
+            if (pass == 2) break;
+        }
     }
 
     // epilogue: normalise, transpose through LDS, store rows of 256 B coalesced
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     const float inv = 1.f / l_tot;
     constexpr int ORS = RB + 16;
-    static_assert(4 * 32 * ORS <= 2 * STAGE_BYTES, "output staging must fit in the stages");
+    static_assert(NW * 32 * ORS <= NSTAGE * STAGE_BYTES, "output staging must fit in the stages");
     char *obuf = &stages[0][0] + wave * 32 * ORS;
 #pragma unroll
     for (int dvt = 0; dvt < NDV; ++dvt)
@@ -270,13 +377,13 @@ hipError_t launch_attn_gqa(const AttnArgs &a, hipStream_t st)
     kp.B = d.B; kp.L = d.L; kp.H = d.H; kp.S = d.S; kp.g = d.g; kp.w = d.w; kp.m = d.m; kp.dense = a.dense;
     const int hps = d.H / d.S;
     kp.hw = hps < 4 ? hps : 4;
-    kp.rbs = 4 / kp.hw;
+    kp.rbs = NW / kp.hw;
     kp.n_qb = (d.L + 32 * kp.rbs - 1) / (32 * kp.rbs);
     kp.n_units = d.B * d.S * (hps / kp.hw);
     kp.scale_log2 = d.scale * 1.4426950408889634f;
     kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
     const long grid = (long)kp.n_units * kp.n_qb;
-    attn_gqa_kernel<<<(unsigned)grid, 256, 0, st>>>(kp);
+    attn_gqa_kernel<<<(unsigned)grid, 64 * NW, 0, st>>>(kp);
     return hipGetLastError();
 }
 
