@@ -110,6 +110,11 @@ __device__ __forceinline__ void pv_load_group(PvFrags &f, const char *vp0, int g
 struct CopyDesc {
     int e0, last;                 // first entry of the tile, last valid entry of the segment
 };
+// The same for one wavefront, in the form the copies use: its first row and how far its rows may go.
+struct WaveCopy {
+    const uint16_t *pool0, *sel0;     // the wavefront's first row of the latent / RoPE part: entry min(e0 + 8*wave, last)
+    int dmax;                         // rows 0..dmax after that one exist (>= 0); later ones are clamped to row dmax
+};
 
 // One direct-to-LDS load of 64 x 16 bytes: lane l fetches global bytes [base + voff, +16) into LDS bytes
 // [lds_addr + 16 l, +16).  Written as inline assembly on purpose: the compiler makes every LDS read that
@@ -131,23 +136,36 @@ __device__ __forceinline__ unsigned lds_address(const char *p)
 // RoPE parts of rows 8*wave .. 8*wave+7 (1 KB; lane l fills slot l&7 of local row l>>3 with the chunk
 // sel_chunk that the swizzle assigns to that slot).  Rows past the end of the segment are clamped here and
 // masked later.
-__device__ __forceinline__ void issue_copy_part(int j, const char *stage, const uint16_t *pool, const uint16_t *sel, const CopyDesc &cd,
-                                                int wave, int lane, int sel_chunk)
+__device__ __forceinline__ WaveCopy wave_copy(const uint16_t *pool, const uint16_t *sel, const CopyDesc &cd, int wave)
+{
+    WaveCopy wc;
+    const int first = cd.e0 + 8 * wave, r0 = min(first, cd.last);     // 0 <= r0 <= last: the base row always exists
+    wc.pool0 = pool + (long)r0 * DP;
+    wc.sel0 = sel + (long)r0 * DS;
+    wc.dmax = max(cd.last - first, 0);                                // all eight rows past the segment: every one reads row `last`
+    return wc;
+}
+
+// The row offset (0 .. 7 KB; the hardware takes the per-lane offset as unsigned, so it must never be negative)
+// travels in the per-lane address offset, so that a row costs a scalar min and shift and one vector add
+// instead of 64-bit scalar address arithmetic.
+__device__ __forceinline__ void issue_copy_part(int j, const char *stage, const WaveCopy &wc, int wave, int lane, int sel_chunk)
 {
     if (j < 8) {
-        const int e = min(cd.e0 + 8 * wave + j, cd.last);
-        dma_1k(lane * 16, pool + (size_t)e * DP, lds_address(stage) + (8 * wave + j) * RSB);
+        const int d = min(j, wc.dmax);
+        dma_1k(lane * 16 + d * (DP * 2), wc.pool0, lds_address(stage) + (8 * wave + j) * RSB);
     } else {
-        const int e = min(cd.e0 + 8 * wave + (lane >> 3), cd.last);
-        dma_1k(e * (DS * 2) + sel_chunk * 16, sel, lds_address(stage) + SEL_OFF + 8 * wave * (DS * 2));
+        const int d = min(lane >> 3, wc.dmax);
+        dma_1k(d * (DS * 2) + sel_chunk * 16, wc.sel0, lds_address(stage) + SEL_OFF + 8 * wave * (DS * 2));
     }
 }
 
 __device__ __forceinline__ void issue_copy(const char *stage, const uint16_t *pool, const uint16_t *sel, const CopyDesc &cd, int wave, int lane,
                                            int sel_chunk)
 {
+    const WaveCopy wc = wave_copy(pool, sel, cd, wave);
 #pragma unroll
-    for (int j = 0; j < COPIES_PER_TILE; ++j) issue_copy_part(j, stage, pool, sel, cd, wave, lane, sel_chunk);
+    for (int j = 0; j < COPIES_PER_TILE; ++j) issue_copy_part(j, stage, wc, wave, lane, sel_chunk);
 }
 
 // S^T chain of one tile (36 MFMAs into `snext`, key fragments prefetched CHAIN_DEPTH deep) and, when SOFTMAX,
@@ -162,8 +180,7 @@ __device__ __forceinline__ void issue_copy(const char *stage, const uint16_t *po
 template <bool CHAIN, bool SOFTMAX, bool PV_PREFETCH>
 __device__ __forceinline__ void chain_and_softmax(const char *kb, const char *kb_sel, int x6, const bf16x8 (&qf)[NKS], floatx16 &snext,
                                                   const floatx16 &scur, bf16x8 (&pb)[2], RowState &st, float c, float bias, PvFrags &pvf,
-                                                  const char *vp0, const char *dma_stage, const uint16_t *pool, const uint16_t *sel,
-                                                  const CopyDesc &cd, int wave, int lane, int sel_chunk)
+                                                  const char *vp0, const char *dma_stage, const WaveCopy &wc, int wave, int lane, int sel_chunk)
 {
     // key fragment of k-step ks: latent columns from the row-strided part, RoPE columns (ks >= 32) from the swizzled part
     auto frag = [&](int ks) {
@@ -210,7 +227,7 @@ __device__ __forceinline__ void chain_and_softmax(const char *kb, const char *kb
             }
         }
         // the copy of the tile three steps ahead rides in the chain's last slots, after the softmax work
-        if (PV_PREFETCH && ks >= 26 && ks - 26 < COPIES_PER_TILE) issue_copy_part(ks - 26, dma_stage, pool, sel, cd, wave, lane, sel_chunk);
+        if (PV_PREFETCH && ks >= 26 && ks - 26 < COPIES_PER_TILE) issue_copy_part(ks - 26, dma_stage, wc, wave, lane, sel_chunk);
         if (PV_PREFETCH && ks == 35) pv_load_group(pvf, vp0, 0, 0);
     }
     LCA_FENCE();
@@ -240,14 +257,14 @@ __device__ __forceinline__ void pv_update(PvFrags &f, const char *vp0, const bf1
 
 // One pipeline step: copy of tile t+3 (into dma_stage), S^T chain of tile t+1 with the softmax of tile t in
 // its shadow, O^T update of tile t.
-__device__ __forceinline__ void tile_step(const char *dma_stage, const char *chain_stage, const char *pv_stage, const uint16_t *pool,
-                                          const uint16_t *sel, const CopyDesc &cd, int wave, int lane, int sel_chunk, int k_off, int ksel_off,
+__device__ __forceinline__ void tile_step(const char *dma_stage, const char *chain_stage, const char *pv_stage, const WaveCopy &wc, int wave,
+                                          int lane, int sel_chunk, int k_off, int ksel_off,
                                           int x6, int v_off, const bf16x8 (&qf)[NKS], floatx16 &snext, const floatx16 &scur, bf16x8 (&pb)[2],
                                           RowState &st, float c, float bias, floatx16 (&acc)[NDV])
 {
     PvFrags pvf;
     chain_and_softmax<true, true, true>(chain_stage + k_off, chain_stage + ksel_off, x6, qf, snext, scur, pb, st, c, bias, pvf, pv_stage + v_off,
-                                        dma_stage, pool, sel, cd, wave, lane, sel_chunk);
+                                        dma_stage, wc, wave, lane, sel_chunk);
     pv_update(pvf, pv_stage + v_off, pb, acc);
     // Anchor: nothing may read the chain's result before this point (the compiler takes an inline-assembly
     // result as ready at once; the 32 MFMAs of the O^T update are the wait states it actually needs).
@@ -383,7 +400,7 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         {
             PvFrags unused;
             chain_and_softmax<true, false, false>(stages[0] + k_off, stages[0] + ksel_off, x6, qf, snext, snext, pb, st, c, 0.f, unused, nullptr,
-                                                  nullptr, nullptr, nullptr, CopyDesc(), wave, lane, sel_chunk);
+                                                  nullptr, WaveCopy(), wave, lane, sel_chunk);
         }
 
         for (int tl = 0; tl < cur.n_tiles; ++tl) {
@@ -406,13 +423,13 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
             const char *dma_stage = stages[(tl + 3) & (NSTAGE - 1)];
             const char *chain_stage = stages[min(tl + 1, cur.n_tiles - 1) & (NSTAGE - 1)], *pv_stage = stages[tl & (NSTAGE - 1)];
             const int tc = min(tl + 3, cur.n_tiles - 1);
-            const CopyDesc cd = copy_desc(cur, tc);
-            const uint16_t *cpool = tc < cur.n_rep_tiles ? cur.rep_pool : cur.raw_pool, *csel = tc < cur.n_rep_tiles ? cur.rep_sel : cur.raw_sel;
+            const WaveCopy wc = wave_copy(tc < cur.n_rep_tiles ? cur.rep_pool : cur.raw_pool, tc < cur.n_rep_tiles ? cur.rep_sel : cur.raw_sel,
+                                          copy_desc(cur, tc), wave);
             // tile tl+1 has landed: its copy was issued two iterations ago, only tile tl+2's 9 loads may be pending ...
             asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
             __syncthreads();      // ... for every wavefront, and every wavefront is done with tile tl-1
-            tile_step(dma_stage, chain_stage, pv_stage, cpool, csel, cd, wave, lane, sel_chunk, k_off, ksel_off, x6, v_off, qf, snext, scur, pb,
-                      st, c, bias, acc);
+            tile_step(dma_stage, chain_stage, pv_stage, wc, wave, lane, sel_chunk, k_off, ksel_off, x6, v_off, qf, snext, scur, pb, st, c, bias,
+                      acc);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the trailing copies have landed before the stages are reused
         // every wavefront is done with the tile stages; repeat the pass if any row ran out of exponent headroom
