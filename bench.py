@@ -81,6 +81,24 @@ def cpu_baseline(wl, Q, POOL, SEL, n_rows: int):
     }, rows, O, c
 
 
+PROFILES = {"cfg4": "lca_prefill_cfg4_128k.md", "cfg5": "lca_prefill_cfg5_gqa_64k.md"}
+
+
+def profiled_traffic(config, kernel):
+    """HBM bytes per launch of `kernel` (fetched + written, counters scaled by the copy-kernel calibration) as
+    recorded in the committed rocprofv3 summary of this configuration (its line `traffic_bytes <kernel> <bytes>`);
+    None when there is none.  The counters need the profiler, so they cannot be read inside this run."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", PROFILES.get(config, ""))
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes" and f[1] == kernel:
+                return float(f[2])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def decode_bench(wl, lca, hp, torch):
     """One decode step of 32 sequences over their condensed caches (HBM-bound). Cache contents are random
     (torch.randn on the device): only the time matters here, parity is covered by the GPU tests."""
@@ -106,8 +124,9 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg4", help="cfg2 | cfg3 | cfg4 (default, the metric's workload) | cfg5 (GQA + decode step)")
-    ap.add_argument("--oracle-rows", type=int, default=512)
+    ap.add_argument("--oracle-rows", type=int, default=4096)
     ap.add_argument("--no-extra", action="store_true", help="skip dense baseline and variants (profiling runs)")
+    ap.add_argument("--decode-only", action="store_true", help="cfg5: time only the decode step over the condensed cache (profiling runs)")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size kernel the HBM counters are scaled by")
     args = ap.parse_args()
@@ -122,6 +141,21 @@ def main():
         sys.exit("bench.py: no GPU visible")
     lca.load()   # fails loudly when liblca.so is missing
     wl = inputs.configs()[args.config]
+    if args.pmc_calib:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+    if args.decode_only:
+        if wl.mode == inputs.MODE_MLA:
+            sys.exit("bench.py: --decode-only is for the GQA configuration (cfg5)")
+        dec = decode_bench(wl, lca, hp, torch)
+        print(json.dumps({"metric": f"LCA decode step over the condensed cache ({wl.name})", "value": dec["ms_decode_step"], "unit": "ms",
+                          "n_gpus": 1, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+                          "roofline": {"bound": "hbm", "kernel": "decode_gqa_kernel (lca_decode_attn)", "achieved": dec["GBps"], "peak": PEAK_HBM_GBS,
+                                       "unit": "GB/s", "frac": dec["frac_of_hbm_peak"], "traffic": None}, "extra": dec}))
+        return
     t_gen = time.perf_counter()
     Q, POOL, SEL = inputs.gen_all(wl)
     t_gen = time.perf_counter() - t_gen
@@ -141,13 +175,6 @@ def main():
     def step():
         f_cond()
         f_attn()
-
-    if args.pmc_calib:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        dst.copy_(src)            # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
 
     # ---- the timed region: W warm-up steps, then exactly K steps between synchronisations ----
     for _ in range(args.warmup):
@@ -224,7 +251,8 @@ def main():
                                 f"AR(1) keys/values, RoPE theta {wl.theta:g}; one attention layer"),
                    "step": "lca_condense + lca_prefill_attn"},
         "roofline": {"bound": "mfma", "kernel": ("attn_mla_kernel" if mla else "attn_gqa_kernel") + " (lca_prefill_attn)", "achieved": tflops,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None},
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
+                     "traffic": profiled_traffic(args.config, "attn_mla_kernel" if mla else "attn_gqa_kernel")},
         "cpu_baseline": base,
         "extra": extra,
     }
