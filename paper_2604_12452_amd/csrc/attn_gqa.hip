@@ -155,28 +155,73 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa_kernel(const GqaParams kp
     typedef __attribute__((address_space(3))) bf16x4 *lds_b64_ptr;
 
     typedef const __attribute__((address_space(3))) bf16x8 *lds_b128_ptr;
-    // LDS fragment reads.  Tiles are worked on in pairs that sit in adjacent stages; `q` = 0..3 counts the halves
-    // of 32 entries of the pair.  K: chunk ks of this lane's row.  V^T: fragment i = (k-step kk = i / 4, value
-    // tile dvt = i % 4), two transpose reads of four keys each.
-    auto load_k = [&](int q, int ks) { return *(lds_b128_ptr)(uintptr_t)(k_addr[ks] + (q / 2) * STAGE_BYTES + (q % 2) * 32 * RB); };
-    auto load_v = [&](int q, int i) {
-        const unsigned o = (q / 2) * STAGE_BYTES + ((q % 2) * 32 + (i / NDV) * 16) * RB;
+    // LDS fragment reads; `half` = 0, 1: the half of 32 entries of the tile the addresses point to.
+    // K: chunk ks of this lane's row.  V^T: fragment i = (k-step kk = i / 4, value tile dvt = i % 4), two
+    // transpose reads of four keys each.
+    auto load_k = [&](int half, int ks) { return *(lds_b128_ptr)(uintptr_t)(k_addr[ks] + half * 32 * RB); };
+    auto load_v = [&](int half, int i) {
+        const unsigned o = (half * 32 + (i / NDV) * 16) * RB;
         const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(uintptr_t)(v_addr[i % NDV] + o));
         const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(uintptr_t)(v_addr[i % NDV] + o + 2 * RB));
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
+    // the addresses move on to the next stage (K: tile T -> T+1 at the end of iteration T; V one tile behind)
+    auto advance_k = [&](int t) {
+        const int d = (t & (NSTAGE - 1)) == NSTAGE - 1 ? -(NSTAGE - 1) * STAGE_BYTES : STAGE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) k_addr[ks] += d;
+    };
+    auto advance_v = [&](int t) {
+        const int d = (t & (NSTAGE - 1)) == NSTAGE - 1 ? -(NSTAGE - 1) * STAGE_BYTES : STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < NDV; ++i) v_addr[i] += d;
+    };
+
+    struct TileInfo { bool is_rep, full; int e_tile; float bias; };
+    auto tile_info = [&](int tl) {
+        TileInfo ti;
+        ti.is_rep = tl < n_rep_tiles;
+        ti.e_tile = ti.is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
+        ti.bias = ti.is_rep ? kp.bias_log2 : 0.f;
+        // every row of this wavefront sees all 64 entries: the steady state
+        ti.full = ti.is_rep ? (ti.e_tile + BN <= mt_w_lo) : (ti.e_tile + BN - 1 <= t_wfirst && ti.e_tile >= mt_w_hi * g);
+        return ti;
+    };
+    // boundary tiles: hide what a row must not see
+    auto mask_half = [&](floatx16 &sv, const TileInfo &ti, int half) {
+        const int e0 = ti.e_tile + half * 32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int e = e0 + acc_entry(r, G);
+            const bool vis = ti.is_rep ? (e < mt_row) : (e >= raw_lo_row && e <= t_row);
+            sv[r] = vis ? sv[r] : -INFINITY;
+        }
+    };
+    auto row_max = [&](const floatx16 &sv, float bias) {
+        float mx = sv[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sv[r]);
+        mx = fmaxf(fmaf(mx, c, bias), NEG_BIG);
+        return fmaxf(mx, __shfl_xor(mx, 32, 64));
+    };
 
     // Pass 0 is the normal one: every row fixes its reference at the first entries it sees and never looks at
     // maxima again.  Its probabilities may grow up to 2^100 above that; only if a row sum ends beyond that (or
-    // not finite) the workgroup runs pass 1, which finds every row's true maximum, and pass 2, the normal pass
-    // from those maxima.
+    // not finite) the workgroup runs pass 1, which finds every row's true maximum (S^T chains alone), and pass
+    // 2, the normal pass from those maxima.
     //
-    // The workgroup synchronises once per PAIR of tiles (the wavefronts of a SIMD stall together at a barrier, so
-    // barriers are kept rare): the pair's copies were requested a pair earlier, into the two stages the pair
-    // before that used.  A tile is scheduled by hand in four phases of eight MFMAs, the softmax of one half
-    // sitting between the MFMAs of the other; LDS fragments are requested four MFMAs before their use (left
-    // alone, the compiler issues each read right before its MFMA and waits out the LDS latency every time).
+    // The normal pass is a software pipeline over halves of 32 entries, scheduled by hand.  Slot H holds
+    //     O^T update of half H-1   (8 independent MFMAs)    with the first half of the softmax of half H, then
+    //     S^T chain of half H+1    (8 dependent MFMAs)      with the second half of that softmax,
+    // so that matrix and vector instructions are mixed evenly wherever the wavefronts of a SIMD happen to be.
+    // Iteration T = slots 2T-1 and 2T: the chains read tile T, the O^T updates tile T-1.  One workgroup
+    // barrier per iteration: tile T was requested two iterations earlier; every wavefront is then done with
+    // tile T-2, whose stage takes tile T+2.  The O^T update comes first in a slot so that the K fragments
+    // requested right after the barrier have eight MFMAs to arrive.  LDS fragments travel in rings of four,
+    // requested four MFMAs before use (left alone, the compiler issues each read right before its MFMA and
+    // waits out the LDS latency every time).
     constexpr int RING = 4;
+    constexpr int LOADS_PER_TILE = 2 * NQ;
     for (int pass = 0;; ++pass) {
 #pragma unroll
         for (int i = 0; i < NDV; ++i)
@@ -184,143 +229,137 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa_kernel(const GqaParams kp
             for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
         l_run = 0.f;
         if (pass == 2) m_ref = m_seen;
-        const bool maxima_only = pass == 1;
         bool ref_missing = pass != 2;                           // wave-uniform: some row has no reference yet
         issue_copy(0);
         if (1 < n_tiles) issue_copy(1);
 
+        if (pass == 1) {                                        // exact row maxima
+            m_seen = NEG_BIG;
+            for (int tl = 0; tl < n_tiles; ++tl) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (tl + 2 < n_tiles) issue_copy(tl + 2);
+                const TileInfo ti = tile_info(tl);
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    floatx16 sv;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sv[r] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < NKS; ++ks) sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_k(half, ks), qf[ks], sv, 0, 0, 0);
+                    if (!ti.full) mask_half(sv, ti, half);
+                    m_seen = fmaxf(m_seen, row_max(sv, ti.bias));
+                }
+                advance_k(tl);
+            }
+            if (n_tiles & (NSTAGE - 1)) {
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) k_addr[ks] -= (n_tiles & (NSTAGE - 1)) * STAGE_BYTES;
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            continue;
+        }
+
+        floatx16 sacc[2];                                       // S^T of half H lives in sacc[H % 2]
+        union Pb { bf16x8 v[2]; bf16x2 p[8]; } pb[2];           // P^T of half H in pb[H % 2]
         bf16x8 kf[RING], vf[RING];
-        // one tile; `sub` = 0, 1: its place in the pair (a compile-time constant)
-        auto do_tile = [&](int tl, auto sub_c) {
-            constexpr int sub = decltype(sub_c)::value;
-            const bool is_rep = tl < n_rep_tiles;
-            const int e_tile = is_rep ? tl * BN : raw_lo_blk + (tl - n_rep_tiles) * BN;
-            const float bias = is_rep ? kp.bias_log2 : 0.f;
-            // every row of this wavefront sees all 64 entries: the steady state
-            const bool tile_full = is_rep ? (e_tile + BN <= mt_w_lo) : (e_tile + BN - 1 <= t_wfirst && e_tile >= mt_w_hi * g);
-            // K fragment f = (half f / 8 of the pair, k-step f % 8); V^T fragment f = (half f / 8 of the tile, fragment f % 8)
-            auto req_k = [&](int f) { if (f < 4 * NKS) kf[f % RING] = load_k(f / NKS, f % NKS); };
-            auto req_v = [&](int f) { if (f < 4 * NDV) vf[f % RING] = load_v(2 * sub + f / (2 * NDV), f % (2 * NDV)); };
-
-            floatx16 sacc[2];
-#pragma unroll
-            for (int half = 0; half < 2; ++half)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[half][r] = 0.f;
-            // boundary tiles: hide what a row must not see; rows without a reference take the maximum of what they see
-            auto mask_and_reference = [&](int half) {
-                if (!tile_full) {
-                    const int e0 = e_tile + half * 32;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int e = e0 + acc_entry(r, G);
-                        const bool vis = is_rep ? (e < mt_row) : (e >= raw_lo_row && e <= t_row);
-                        sacc[half][r] = vis ? sacc[half][r] : -INFINITY;
-                    }
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        float nb = 0.f;
+        // P^T = exp2(S^T * c + bias - reference) in bf16 and its row sums, two S^T registers at a time so that the
+        // work can sit between MFMAs.  Accumulator registers 0..7 / 8..15 are the B operands of the two k-steps of
+        // the second product as they are.  The sums are taken over the rounded values, the ones the second product
+        // sees.  A row that has seen nothing yet has reference -1e30 and only -inf logits: exact zeros.
+        auto softmax_pair = [&](int par, int i) {
+            bf16x2 pr;
+            pr[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[par][2 * i], c, nb));
+            pr[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[par][2 * i + 1], c, nb));
+            // (the empty statements pin the work to this place: otherwise the compiler sinks it past the
+            // branches of the next slot, out of the shadow of this slot's MFMAs)
+            unsigned bits = __builtin_bit_cast(unsigned, pr);
+            asm volatile("" : "+v"(bits));
+            pr = __builtin_bit_cast(bf16x2, bits);
+            pb[par].p[i] = pr;
+            l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_run, false);
+            asm volatile("" : "+v"(l_run));
+        };
+        // Slot H (par = H % 2), 16 MFMAs with one softmax pair after every second one:
+        //   PV: O^T update of half H-1 (V^T of half 1-par of the tile v_addr points to, tile t_v);
+        //   SM: softmax of half H, which is half `par` of tile `ti`;
+        //   CH: S^T chain of half H+1 (half 1-par of the tile k_addr points to).
+        // The last four requests of each ring are for the next slot (`more_v`: it has an O^T update).
+        auto slot = [&](auto par_c, auto pv_c, auto sm_c, auto ch_c, const TileInfo &ti, int t_v, bool more_v) {
+            constexpr int par = decltype(par_c)::value;
+            constexpr bool PV = decltype(pv_c)::value, SM = decltype(sm_c)::value, CH = decltype(ch_c)::value;
+            if (SM) {
+                if (!ti.full) mask_half(sacc[par], ti, par);
+                if (ref_missing) {                              // the first visible entries of a row fix its reference
+                    const float mx = row_max(sacc[par], ti.bias);
+                    m_ref = (m_ref == NEG_BIG) ? mx : m_ref;
+                    ref_missing = __builtin_amdgcn_ballot_w64(m_ref == NEG_BIG) != 0;
                 }
-                if (ref_missing || maxima_only) {
-                    float tmax = sacc[half][0];
+                nb = ti.bias - m_ref;
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[half][r]);
-                    tmax = fmaxf(fmaf(tmax, c, bias), NEG_BIG);
-                    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-                    m_seen = fmaxf(m_seen, tmax);
-                    if (!maxima_only) {
-                        m_ref = (m_ref == NEG_BIG) ? tmax : m_ref;
-                        ref_missing = __builtin_amdgcn_ballot_w64(m_ref == NEG_BIG) != 0;
-                    }
+            for (int i = 0; i < 2 * NDV; ++i) {
+                if (PV) {
+                    acc[i % NDV] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % RING], pb[1 - par].v[i / NDV], acc[i % NDV], 0, 0, 0);
+                    if (i < 2 * NDV - RING) vf[i % RING] = load_v(1 - par, i + RING);
                 }
-            };
-            // P^T = exp2(S^T * c + bias - reference) in bf16 and its row sums, two S^T registers at a time so that the
-            // work can sit between MFMAs.  Accumulator registers 0..7 / 8..15 are the B operands of the two k-steps of
-            // the second product as they are.  The sums are taken over the rounded values, the ones the second
-            // product sees.  A row that has seen nothing yet has reference -1e30 and only -inf logits: its
-            // probabilities are exact zeros.
-            union Pb { bf16x8 v[2]; bf16x2 p[8]; } pb[2];
-            const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-            float nb = 0.f;
-            auto softmax_pair = [&](int half, int i) {
-                bf16x2 pr;
-                pr[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[half][2 * i], c, nb));
-                pr[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[half][2 * i + 1], c, nb));
-                pb[half].p[i] = pr;
-                l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_run, false);
-            };
-
-            // phase 1: S^T of the first half
+                if (i >= 2 * NDV - RING) {
+                    // half H, the next slot's: the second half of the same tile (par == 1) or the first of the next one
+                    if (PV && par == 0 && i == 2 * NDV - RING) advance_v(t_v);
+                    if (more_v) vf[i % RING] = load_v(par, i - (2 * NDV - RING));
+                }
+                if (SM && i % 2 == 0) softmax_pair(par, i / 2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
-                sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % RING], qf[ks], sacc[0], 0, 0, 0);
-                req_k(2 * sub * NKS + ks + RING);
+                if (CH) {
+                    if (ks == 0) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) sacc[1 - par][r] = 0.f;
+                    }
+                    sacc[1 - par] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % RING], qf[ks], sacc[1 - par], 0, 0, 0);
+                    if (ks < NKS - RING) kf[ks % RING] = load_k(1 - par, ks + RING);
+                    else if (par == 1) kf[ks % RING] = load_k(1, ks - (NKS - RING));   // next slot's chain: second half of this tile
+                }
+                if (SM && ks % 2 == 0) softmax_pair(par, 4 + ks / 2);
                 __builtin_amdgcn_sched_barrier(0);
-            }
-            if (!tile_full || ref_missing || maxima_only) mask_and_reference(0);
-            nb = bias - m_ref;
-            __builtin_amdgcn_sched_barrier(0);
-            // phase 2: S^T of the second half, the first half's softmax between its MFMAs
-            if (maxima_only) {
-#pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) {
-                    sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % RING], qf[ks], sacc[1], 0, 0, 0);
-                    req_k((2 * sub + 1) * NKS + ks + RING);    // runs into the pair's second tile
-                }
-            } else {
-#pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) {
-                    sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks % RING], qf[ks], sacc[1], 0, 0, 0);
-                    if (ks < NKS - RING) req_k((2 * sub + 1) * NKS + ks + RING);
-                    else req_v(ks - (NKS - RING));
-                    softmax_pair(0, ks);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            if (!tile_full || ref_missing || maxima_only) mask_and_reference(1);
-            if (!maxima_only) {
-                nb = bias - m_ref;
-                __builtin_amdgcn_sched_barrier(0);
-                // phase 3: second product of the first half, the second half's softmax between its MFMAs
-#pragma unroll
-                for (int i = 0; i < 2 * NDV; ++i) {
-                    acc[i % NDV] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % RING], pb[0].v[i / NDV], acc[i % NDV], 0, 0, 0);
-                    req_v(i + RING);
-                    softmax_pair(1, i);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                // phase 4: second product of the second half; the first K fragments of the pair's second tile requested
-                // (if the pair has none, they are read from the stage all the same and never used)
-#pragma unroll
-                for (int i = 0; i < 2 * NDV; ++i) {
-                    acc[i % NDV] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % RING], pb[1].v[i / NDV], acc[i % NDV], 0, 0, 0);
-                    req_v(2 * NDV + i + RING);
-                    if (sub == 0 && i >= 2 * NDV - RING) req_k(2 * NKS + i - (2 * NDV - RING));
-                    __builtin_amdgcn_sched_barrier(0);
-                }
             }
         };
-
-        for (int tl = 0; tl < n_tiles; tl += 2) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's share of the pair has landed
-            __syncthreads();                                   // ... and everyone's; everyone is done with the pair before
+        // Iteration T: barrier for tile T, copy of tile T+2, slots 2T-1 and 2T.
+        auto iteration = [&](int T, auto first_c, auto last_c) {
+            constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
+            typedef std::integral_constant<bool, !FIRST> not_first;
+            typedef std::integral_constant<bool, !LAST> not_last;
+            if (!LAST) {
+                // this wavefront's share of tile T has landed (the copy of tile T+1 may be pending) ...
+                if (T + 1 < n_tiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_TILE) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();                               // ... and everyone's; everyone is done with tile T-2
 #pragma unroll
-            for (int f = 0; f < RING; ++f) kf[f] = load_k(0, f);
-            __builtin_amdgcn_sched_barrier(0);
-            if (tl + 2 < n_tiles) issue_copy(tl + 2);          // into the stages of the pair before
-            if (tl + 3 < n_tiles) issue_copy(tl + 3);
-            __builtin_amdgcn_sched_barrier(0);
-            do_tile(tl, std::integral_constant<int, 0>());
-            if (tl + 1 < n_tiles) do_tile(tl + 1, std::integral_constant<int, 1>());
-            // the other two stages next
-            const int flip = (tl & 2) ? -2 * STAGE_BYTES : 2 * STAGE_BYTES;
+                for (int f = 0; f < RING; ++f) kf[f] = load_k(0, f);
+                __builtin_amdgcn_sched_barrier(0);
+                if (T + 2 < n_tiles) issue_copy(T + 2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const TileInfo ti_prev = tile_info(FIRST ? 0 : T - 1), ti_cur = tile_info(LAST ? T - 1 : T);
+            slot(std::integral_constant<int, 1>(), not_first(), not_first(), not_last(), ti_prev, T - 1, true);
+            slot(std::integral_constant<int, 0>(), not_first(), not_last(), not_last(), ti_cur, T - 1, !LAST);
+            if (!LAST) advance_k(T);
+        };
+        iteration(0, std::true_type(), std::false_type());
+        for (int T = 1; T < n_tiles; ++T) iteration(T, std::false_type(), std::false_type());
+        iteration(n_tiles, std::false_type(), std::true_type());
+        if (n_tiles & (NSTAGE - 1)) {                           // back to stage 0 for another pass
+            const int back = (n_tiles & (NSTAGE - 1)) * STAGE_BYTES;
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) k_addr[ks] += flip;
+            for (int ks = 0; ks < NKS; ++ks) k_addr[ks] -= back;
 #pragma unroll
-            for (int i = 0; i < NDV; ++i) v_addr[i] += flip;
-        }
-        if (((n_tiles + 1) / 2) & 1) {                          // back to stage 0 for another pass
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) k_addr[ks] -= 2 * STAGE_BYTES;
-#pragma unroll
-            for (int i = 0; i < NDV; ++i) v_addr[i] -= 2 * STAGE_BYTES;
+            for (int i = 0; i < NDV; ++i) v_addr[i] -= back;
         }
 
         // every wavefront is done with the stages
@@ -329,7 +368,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa_kernel(const GqaParams kp
             if (!__syncthreads_or(!(l_chk <= 0x1p100f))) break;
         } else {
             __syncthreads();
-            if (pass == 2) break;
+            break;
         }
     }
 
