@@ -3,15 +3,16 @@
 // section 4.3, Eq. 10 with the per-query partition of appendix A.2) and, with dense = 1, plain causal
 // attention (section 3, Eq. 5).
 //
-// At d = 128 a (query, key) pair costs 512 MFMA flops and one exponential, so the vector ALU is as busy as
-// the matrix core; the kernel therefore keeps its register footprint small enough for two workgroups per
-// CU and lets the hardware overlap one wavefront's softmax with another's MFMAs.
+// At d = 128 a (query, key) pair costs 512 MFMA flops and one exponential, so the vector ALU is nearly as
+// busy as the matrix core; the kernel keeps its register footprint at 256 so that two wavefronts share a
+// SIMD, and mixes matrix and vector instructions evenly in program order (see the pass loop).
 //
-// Workgroup = 4 wavefronts; a wavefront owns 32 query rows of ONE query head, and the wavefronts of a
-// workgroup are the query heads of one KV head (4 heads x 32 rows at 4 heads per KV head), so they share
-// every key/value tile and see exactly the same keys.  Tiles of 64 entries (K and V rows of 256 B) are
-// copied by direct-to-LDS loads into two 32 KB stages, one tile ahead.  Rows sit at a 256-byte stride with
-// their 16-byte chunks XOR-swizzled by row, which keeps both read patterns bank-conflict-free:
+// Workgroup = 8 wavefronts; a wavefront owns 32 query rows of ONE query head, and the wavefronts of a
+// workgroup are (the query heads of one KV head) x (blocks of 32 rows): 4 heads x 64 rows at 4 heads per KV
+// head, so they share every key/value tile and see exactly the same keys.  Tiles of 64 entries (K and V
+// rows of 256 B) are copied by direct-to-LDS loads into four 32 KB stages, two tiles ahead.  Rows sit at a
+// 256-byte stride with their 16-byte chunks XOR-swizzled by row (at the source address of the copy), which
+// keeps both read patterns bank-conflict-free:
 //   S^T[key, query] = K Q^T      16-byte key reads, lane = S^T row m reads LDS row pi(m)
 //   O^T[dv, query] += V^T P^T    transpose reads (ds_read_b64_tr_b16), each 16-lane block touches rows 4 apart
 // with pi(8h + 4G + j) = 4j + 2h + G inside each 16 rows (the S^T accumulator registers then already are
