@@ -114,8 +114,23 @@ def decode_bench(wl, lca, hp, torch):
     ws = lca.alloc_workspace(desc)
     ms = time_kernel(lambda: lca.decode_attn(desc, q, pool_rep, sel_rep, pool_tail, sel_tail, O, ws), 20, 3)
     nbytes = B * wd.S * (m + k) * (wd.d_pool + wd.d_sel) * 2
-    return {"B": B, "L": wd.L, "m": m, "k": k, "ms_decode_step": ms, "algorithmic_bytes": nbytes,
-            "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    out = {"B": B, "L": wd.L, "m": m, "k": k, "ms_decode_step": ms, "algorithmic_bytes": nbytes,
+           "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    # the same step over a growing cache (spare rows, ring tail that wraps), and the online update that runs every g-th step
+    m_cap, k_cap = m + 64, wd.w + wd.g
+    lay = lca.CacheLayout(m_cap=m_cap, k_cap=k_cap, k_start=k_cap - 100)
+    pool_rep2, sel_rep2 = mk(B, wd.S, m_cap, wd.d_pool), mk(B, wd.S, m_cap, wd.d_sel)
+    pool_ring, sel_ring = mk(B, wd.kv_heads, k_cap, wd.d_pool), mk(B, wd.kv_heads, k_cap, wd.d_sel)
+    out["ms_decode_step_cached"] = time_kernel(
+        lambda: lca.decode_attn_cached(desc, lay, q, pool_rep2, sel_rep2, pool_ring, sel_ring, O, ws), 20, 3)
+    wu = wl.with_(B=B, L=wd.w + (m + 1) * wd.g)                     # the next length at which an update is due
+    du = hp.lca_desc(wu)
+    q_recent = mk(B, wd.g, wd.H, wd.d_qk) * 0.1
+    anchor = torch.zeros((B, wd.S, m_cap), dtype=torch.int32, device="cuda")
+    out["ms_cache_update"] = time_kernel(
+        lambda: lca.cache_update(du, lay, q_recent, pool_ring, sel_ring, pool_rep2, sel_rep2, anchor, ws), 20, 3)
+    out["ms_decode_step_amortised"] = out["ms_decode_step_cached"] + out["ms_cache_update"] / wd.g
+    return out
 
 
 def main():

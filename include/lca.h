@@ -26,7 +26,8 @@
  *   - Every call returns an lca_status.  On any status other than LCA_OK nothing was launched and no
  *     output was touched, except LCA_ERR_HIP, which reports a launch failure from the HIP runtime.
  *     lca_last_error() gives a thread-local message for the last non-OK status.
- *   - Invalid: NULL required pointer; B, L, H, S, g <= 0; w < 0; H % S != 0; n_q > L; a dtype or
+ *   - Invalid: NULL required pointer; B, L, H, S, g <= 0; w < 0; H % S != 0; n_q < 0, and n_q > L in
+ *     the calls that read the summary queries (lca_condense, lca_cache_update); a dtype or
  *     mode outside the enums; d_pool / d_sel not multiples of 8 (bf16) or 4 (f32) or above 1024;
  *     g > 64; workspace too small (LCA_ERR_WORKSPACE).  m = 0 (L < w + g) is valid: lca_condense
  *     writes nothing and lca_prefill_attn equals dense attention (section 4.3, fallback remark).
@@ -120,6 +121,49 @@ lca_status dense_mla_attn(const lca_desc *desc, const void *Q, const void *POOL,
 lca_status lca_decode_attn(const lca_desc *desc, const void *q, const void *pool_rep, const void *sel_rep,
                            const void *pool_tail, const void *sel_tail, void *O,
                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * A decoding batch's cache as it grows (section 4.3, "Decoding and Online Cache Update"): the buffers
+ * are allocated once with room for more rows than are in use, and the raw tail is a ring.
+ *   pool_rep [B,S,m_cap,d_pool], sel_rep [B,S,m_cap,d_sel], anchor_idx [B,S,m_cap]: rows [0, m) in use;
+ *   pool_tail [B,P,k_cap,d_pool], sel_tail [B,P,k_cap,d_sel]: raw token number i of the tail (0 = oldest)
+ *   sits in ring row (k_start + i) mod k_cap.
+ * Writing a new token's rows into the ring (row (k_start + k) mod k_cap before the step) is the
+ * caller's business, as in lca_decode_attn.
+ */
+typedef struct {
+    int32_t m_cap;      /* representative rows allocated per (sequence, set);  m <= m_cap            */
+    int32_t k_cap;      /* tail rows allocated per (sequence, KV head);        k <= k_cap            */
+    int32_t k_start;    /* ring row of the oldest raw token, 0 <= k_start < k_cap                    */
+} lca_cache_layout;
+
+/*
+ * lca_decode_attn over a cache with the layout above; m and k follow from desc->L as there.
+ * Invalid in addition: m > m_cap, k > k_cap, k_start outside [0, k_cap).
+ */
+lca_status lca_decode_attn_cached(const lca_desc *desc, const lca_cache_layout *layout, const void *q,
+                                  const void *pool_rep, const void *sel_rep, const void *pool_tail,
+                                  const void *sel_tail, void *O, void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
+/*
+ * Online cache update (section 4.3, same paragraph): once g new tokens have arrived, the g oldest
+ * raw tokens of the tail are condensed into one more representative, scored with the mean query of
+ * the last n_q (default g) tokens as in Eq. 6 and reduced by Eq. 7 and Eq. 8.
+ * desc->L = tokens so far INCLUDING the newest, already in the ring; the call is due exactly when
+ * L >= w + g and (L - w) mod g == 0.  With m = (L - w) / g, the ring holds the w + g tokens
+ * [(m-1)*g, L) before the call; the call writes row m-1 of pool_rep, sel_rep and anchor_idx (the
+ * anchor as an absolute token index) and touches nothing else.  Afterwards the cache is the one
+ * lca_decode_attn_cached expects for this L with k_start advanced by g (mod k_cap): m
+ * representatives and the w newest raw tokens; the g condensed ring rows are free for new tokens.
+ * In:  q_recent [B,n_q,H,d_qk], oldest first; pool_tail, sel_tail (the ring, read only).
+ * Out: row m-1 of pool_rep [B,S,m_cap,d_pool], sel_rep [B,S,m_cap,d_sel], anchor_idx [B,S,m_cap] (may be NULL).
+ * Invalid in addition: L < w + g or (L - w) mod g != 0; m > m_cap; w + g > k_cap; k_start outside [0, k_cap).
+ * Workspace: lca_workspace_size(desc) bytes are enough (unused by the current kernels).
+ */
+lca_status lca_cache_update(const lca_desc *desc, const lca_cache_layout *layout, const void *q_recent,
+                            const void *pool_tail, const void *sel_tail, void *pool_rep, void *sel_rep,
+                            int32_t *anchor_idx, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Message for the calling thread's last non-OK status; never NULL. */
 const char *lca_last_error(void);

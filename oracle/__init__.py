@@ -199,6 +199,30 @@ def decode_attn(d: Desc, q, pool_rep, sel_rep, pool_tail, sel_tail) -> np.ndarra
     return O
 
 
+def cache_update(d: Desc, q_recent, pool_old, sel_old):
+    """Online cache update during decoding (section 4.3, "Decoding and Online Cache Update"): the g oldest raw
+    tokens of the tail become one representative, scored with the mean of the last n_q queries (Eq. 6) and
+    reduced by Eq. 7 and Eq. 8 — i.e. the condensation of a one-group problem.
+
+    q_recent [B,n_q,H,d_qk] (oldest first); pool_old [B,P,g,d_pool], sel_old [B,P,g,d_sel] as the tail stores
+    them (P = 1 for MLA, S for GQA).  Returns dict(pool_rep [B,S,d_pool], sel_rep [B,S,d_sel],
+    anchor [B,S] (0..g-1 inside the g tokens), alpha [B,S,g], margin [B,S])."""
+    P = d.kv_heads
+    q_recent = _f64(q_recent, (d.B, d.nq, d.H, d.d_qk))
+    pool_old = _f64(pool_old, (d.B, P, d.g, d.d_pool))
+    sel_old = _f64(sel_old, (d.B, P, d.g, d.d_sel))
+    common = dict(B=d.B, H=d.H, S=d.S, d_pool=d.d_pool, d_sel=d.d_sel, g=d.g, mode=d.mode, scale=d.scale)
+    qbar = summary_query(Desc(L=d.nq, w=0, n_q=d.nq, **common), q_recent)
+    # the one-group problem in the prefill layout: tokens first, then KV heads
+    if d.mode == MODE_MLA:
+        POOL, SEL = pool_old[:, 0], sel_old[:, 0]
+    else:
+        POOL, SEL = pool_old.transpose(0, 2, 1, 3), sel_old.transpose(0, 2, 1, 3)
+    c = condense(Desc(L=d.g, w=0, n_q=d.g, **common), qbar, np.ascontiguousarray(POOL), np.ascontiguousarray(SEL))
+    return dict(pool_rep=c["pool_rep"][:, :, 0], sel_rep=c["sel_rep"][:, :, 0], anchor=c["anchor"][:, :, 0],
+                alpha=c["alpha"], margin=c["margin"][:, :, 0])
+
+
 def cache_bytes(d: Desc, elt_bytes: int):
     """(dense_bytes, condensed_bytes) of the KV cache for one attention layer."""
     a, b = ctypes.c_uint64(0), ctypes.c_uint64(0)

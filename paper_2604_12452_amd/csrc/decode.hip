@@ -52,7 +52,8 @@ template <typename T, int DP, int DS, bool MLA, int HPS>
 __global__ __launch_bounds__(WAVE *NWAVE) void decode_split_kernel(const T *__restrict__ q, const T *__restrict__ pool_rep,
                                                                    const T *__restrict__ sel_rep, const T *__restrict__ pool_tail,
                                                                    const T *__restrict__ sel_tail, float *__restrict__ part, int S, int P,
-                                                                   int m, int k, int splits, float scale, float rep_bias)
+                                                                   int m, int k, int splits, float scale, float rep_bias, int m_cap,
+                                                                   int k_cap, int k_start)
 {
     constexpr int EPC = DElt<T>::EPC;
     constexpr int DQK = MLA ? DP + DS : DS;
@@ -103,11 +104,13 @@ __global__ __launch_bounds__(WAVE *NWAVE) void decode_split_kernel(const T *__re
         const int ec = valid ? e : e_hi - 1;
         const T *prow, *srow;
         if (ec < m) {
-            prow = pool_rep + (((size_t)b * S + s) * m + ec) * DP;
-            srow = sel_rep + (((size_t)b * S + s) * m + ec) * DS;
+            prow = pool_rep + (((size_t)b * S + s) * m_cap + ec) * DP;
+            srow = sel_rep + (((size_t)b * S + s) * m_cap + ec) * DS;
         } else {
-            prow = pool_tail + (((size_t)b * P + p) * k + (ec - m)) * DP;
-            srow = sel_tail + (((size_t)b * P + p) * k + (ec - m)) * DS;
+            int r = k_start + (ec - m);                         // the tail is a ring of k_cap rows
+            r = r >= k_cap ? r - k_cap : r;
+            prow = pool_tail + (((size_t)b * P + p) * k_cap + r) * DP;
+            srow = sel_tail + (((size_t)b * P + p) * k_cap + r) * DS;
         }
         uint4 data[NSLOT];
 #pragma unroll
@@ -227,7 +230,8 @@ template <int HPS>
 __global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ pool_rep,
                                                                  const uint16_t *__restrict__ sel_rep, const uint16_t *__restrict__ pool_tail,
                                                                  const uint16_t *__restrict__ sel_tail, float *__restrict__ part, int S, int m,
-                                                                 int k, int splits, float scale, float rep_bias)
+                                                                 int k, int splits, float scale, float rep_bias, int m_cap, int k_cap,
+                                                                 int k_start)
 {
     constexpr int D = 128, H = HPS, RPW = 4;
     __shared__ float comb[H * (D + 2)];
@@ -246,8 +250,8 @@ __global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const uint16_t 
 #pragma unroll
         for (int x = 0; x < 8; ++x) qv[h][x] = f[x] * scale;
     }
-    const uint16_t *krep = sel_rep + ((size_t)b * S + s) * m * D, *vrep = pool_rep + ((size_t)b * S + s) * m * D;
-    const uint16_t *ktail = sel_tail + ((size_t)b * S + s) * k * D, *vtail = pool_tail + ((size_t)b * S + s) * k * D;
+    const uint16_t *krep = sel_rep + ((size_t)b * S + s) * m_cap * D, *vrep = pool_rep + ((size_t)b * S + s) * m_cap * D;
+    const uint16_t *ktail = sel_tail + ((size_t)b * S + s) * k_cap * D, *vtail = pool_tail + ((size_t)b * S + s) * k_cap * D;
 
     float mr[H], lr[H], acc[H][8];
 #pragma unroll
@@ -267,8 +271,10 @@ __global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const uint16_t 
             valid[u] = e < e_hi;
             const int ec = valid[u] ? e : e_hi - 1;
             rep[u] = ec < m;
-            const uint16_t *kp = rep[u] ? krep + (size_t)ec * D : ktail + (size_t)(ec - m) * D;
-            const uint16_t *vp = rep[u] ? vrep + (size_t)ec * D : vtail + (size_t)(ec - m) * D;
+            int r = k_start + (ec - m);                         // the tail is a ring of k_cap rows
+            r = r >= k_cap ? r - k_cap : r;
+            const uint16_t *kp = rep[u] ? krep + (size_t)ec * D : ktail + (size_t)r * D;
+            const uint16_t *vp = rep[u] ? vrep + (size_t)ec * D : vtail + (size_t)r * D;
             kd[u] = *reinterpret_cast<const uint4 *>(kp + sub * 8);
             vd[u] = *reinterpret_cast<const uint4 *>(vp + sub * 8);
         }
@@ -379,7 +385,7 @@ hipError_t run_gqa(const DecodeArgs &a, hipStream_t st)
     const Dims &d = a.d;
     decode_gqa_kernel<HPS><<<d.B * d.S * a.splits, WAVE * NWAVE, 0, st>>>(
         (const uint16_t *)a.q, (const uint16_t *)a.pool_rep, (const uint16_t *)a.sel_rep, (const uint16_t *)a.pool_tail,
-        (const uint16_t *)a.sel_tail, a.part, d.S, d.m, d.k, a.splits, d.scale, d.rep_logit_bias);
+        (const uint16_t *)a.sel_tail, a.part, d.S, d.m, d.k, a.splits, d.scale, d.rep_logit_bias, a.m_cap, a.k_cap, a.k_start);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     decode_merge_kernel<uint16_t><<<d.B * d.H, 128, 0, st>>>(a.part, (uint16_t *)a.O, HPS, 128, a.splits);
@@ -392,7 +398,7 @@ hipError_t run(const DecodeArgs &a, hipStream_t st)
     const Dims &d = a.d;
     decode_split_kernel<T, DP, DS, MLA, HPS><<<d.B * d.S * a.splits, WAVE * NWAVE, 0, st>>>(
         (const T *)a.q, (const T *)a.pool_rep, (const T *)a.sel_rep, (const T *)a.pool_tail, (const T *)a.sel_tail, a.part, d.S, d.P, d.m,
-        d.k, a.splits, d.scale, d.rep_logit_bias);
+        d.k, a.splits, d.scale, d.rep_logit_bias, a.m_cap, a.k_cap, a.k_start);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     decode_merge_kernel<T><<<d.B * d.H, 128, 0, st>>>(a.part, (T *)a.O, HPS, DP, a.splits);

@@ -37,7 +37,7 @@ lca_status make_dims(const lca_desc *desc, lca::Dims &d)
     const int d_qk = desc->mode == LCA_MODE_MLA ? desc->d_pool + desc->d_sel : desc->d_sel;
     if (d_qk > 1024 || desc->d_pool > 1024) return fail(LCA_ERR_UNSUPPORTED, "d_qk and d_pool above 1024 are not supported");
     const int n_q = desc->n_q == 0 ? desc->g : desc->n_q;
-    if (n_q < 0 || n_q > desc->L) return fail(LCA_ERR_INVALID_ARG, "n_q (%d) must be in [1, L]", n_q);
+    if (n_q < 0) return fail(LCA_ERR_INVALID_ARG, "n_q (%d) must not be negative", n_q);
     if (!(desc->scale == desc->scale) || !(desc->rep_logit_bias == desc->rep_logit_bias)) return fail(LCA_ERR_INVALID_ARG, "scale / bias is NaN");
     if ((long long)desc->B * desc->L * desc->H >= (1ll << 31)) return fail(LCA_ERR_UNSUPPORTED, "B*L*H must be below 2^31");
     d.B = desc->B; d.L = desc->L; d.H = desc->H; d.S = desc->S;
@@ -128,6 +128,7 @@ lca_status lca_condense(const lca_desc *desc, const void *Q, const void *POOL, c
 {
     lca::Dims d;
     LCA_TRY(make_dims(desc, d));
+    if (d.n_q > d.L) return fail(LCA_ERR_INVALID_ARG, "n_q (%d) must be in [1, L]", d.n_q);
     LCA_TRY(check_ptr(Q, "Q"));
     LCA_TRY(check_ptr(POOL, "POOL"));
     LCA_TRY(check_ptr(SEL, "SEL"));
@@ -175,13 +176,24 @@ lca_status dense_mla_attn(const lca_desc *desc, const void *Q, const void *POOL,
     return run_attn(a, static_cast<hipStream_t>(stream), "dense_mla_attn");
 }
 
-lca_status lca_decode_attn(const lca_desc *desc, const void *q, const void *pool_rep, const void *sel_rep, const void *pool_tail,
-                           const void *sel_tail, void *O, void *workspace, size_t workspace_bytes_, void *stream)
+static lca_status check_layout(const lca::Dims &d, const lca_cache_layout *layout, int k_needed)
+{
+    if (layout == nullptr) return fail(LCA_ERR_INVALID_ARG, "layout is NULL");
+    if (layout->m_cap < d.m) return fail(LCA_ERR_INVALID_ARG, "m_cap (%d) is below the number of representatives (%d)", layout->m_cap, d.m);
+    if (layout->k_cap < k_needed) return fail(LCA_ERR_INVALID_ARG, "k_cap (%d) is below the number of raw tail tokens (%d)", layout->k_cap, k_needed);
+    if (layout->k_start < 0 || layout->k_start >= layout->k_cap) return fail(LCA_ERR_INVALID_ARG, "k_start (%d) is outside [0, k_cap)", layout->k_start);
+    return LCA_OK;
+}
+
+static lca_status decode_common(const lca_desc *desc, const lca_cache_layout *layout, const void *q, const void *pool_rep, const void *sel_rep,
+                                const void *pool_tail, const void *sel_tail, void *O, void *workspace, size_t workspace_bytes_, void *stream,
+                                const char *what)
 {
     lca::Dims d;
     LCA_TRY(make_dims(desc, d));
     if (!lca::decode_supported(d))
-        return fail(LCA_ERR_UNSUPPORTED, "lca_decode_attn has no kernel for this mode / dtype / widths / heads-per-set combination");
+        return fail(LCA_ERR_UNSUPPORTED, "%s has no kernel for this mode / dtype / widths / heads-per-set combination", what);
+    if (layout != nullptr) LCA_TRY(check_layout(d, layout, d.k));
     LCA_TRY(check_ptr(q, "q"));
     LCA_TRY(check_ptr(pool_rep, "pool_rep", d.m > 0));
     LCA_TRY(check_ptr(sel_rep, "sel_rep", d.m > 0));
@@ -193,7 +205,46 @@ lca_status lca_decode_attn(const lca_desc *desc, const void *q, const void *pool
     a.d = d; a.q = q; a.pool_rep = pool_rep; a.sel_rep = sel_rep; a.pool_tail = pool_tail; a.sel_tail = sel_tail; a.O = O;
     a.part = static_cast<float *>(workspace);
     a.splits = lca::decode_splits(d);
-    return hip_status(lca::launch_decode(a, static_cast<hipStream_t>(stream)), "lca_decode_attn");
+    a.m_cap = layout ? layout->m_cap : d.m;
+    a.k_cap = layout ? layout->k_cap : d.k;
+    a.k_start = layout ? layout->k_start : 0;
+    return hip_status(lca::launch_decode(a, static_cast<hipStream_t>(stream)), what);
+}
+
+lca_status lca_decode_attn(const lca_desc *desc, const void *q, const void *pool_rep, const void *sel_rep, const void *pool_tail,
+                           const void *sel_tail, void *O, void *workspace, size_t workspace_bytes_, void *stream)
+{
+    return decode_common(desc, nullptr, q, pool_rep, sel_rep, pool_tail, sel_tail, O, workspace, workspace_bytes_, stream, "lca_decode_attn");
+}
+
+lca_status lca_decode_attn_cached(const lca_desc *desc, const lca_cache_layout *layout, const void *q, const void *pool_rep, const void *sel_rep,
+                                  const void *pool_tail, const void *sel_tail, void *O, void *workspace, size_t workspace_bytes_, void *stream)
+{
+    if (layout == nullptr) return fail(LCA_ERR_INVALID_ARG, "layout is NULL");
+    return decode_common(desc, layout, q, pool_rep, sel_rep, pool_tail, sel_tail, O, workspace, workspace_bytes_, stream, "lca_decode_attn_cached");
+}
+
+lca_status lca_cache_update(const lca_desc *desc, const lca_cache_layout *layout, const void *q_recent, const void *pool_tail,
+                            const void *sel_tail, void *pool_rep, void *sel_rep, int32_t *anchor_idx, void *workspace, size_t workspace_bytes_,
+                            void *stream)
+{
+    (void)workspace; (void)workspace_bytes_;
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    if (d.L < d.w + d.g || (d.L - d.w) % d.g != 0)
+        return fail(LCA_ERR_INVALID_ARG, "no update is due at L = %d (w = %d, g = %d): needs L >= w + g and (L - w) mod g == 0", d.L, d.w, d.g);
+    if (d.n_q > d.L) return fail(LCA_ERR_INVALID_ARG, "n_q (%d) must be in [1, L]", d.n_q);
+    LCA_TRY(check_layout(d, layout, d.w + d.g));
+    LCA_TRY(check_ptr(q_recent, "q_recent"));
+    LCA_TRY(check_ptr(pool_tail, "pool_tail"));
+    LCA_TRY(check_ptr(sel_tail, "sel_tail"));
+    LCA_TRY(check_ptr(pool_rep, "pool_rep"));
+    LCA_TRY(check_ptr(sel_rep, "sel_rep"));
+    if (anchor_idx != nullptr && (reinterpret_cast<uintptr_t>(anchor_idx) & 3)) return fail(LCA_ERR_INVALID_ARG, "anchor_idx is not 4-byte aligned");
+    lca::UpdateArgs a;
+    a.d = d; a.q_recent = q_recent; a.pool_tail = pool_tail; a.sel_tail = sel_tail; a.pool_rep = pool_rep; a.sel_rep = sel_rep;
+    a.anchor = anchor_idx; a.m_cap = layout->m_cap; a.k_cap = layout->k_cap; a.k_start = layout->k_start;
+    return hip_status(lca::launch_cache_update(a, static_cast<hipStream_t>(stream)), "lca_cache_update");
 }
 
 }  // extern "C"

@@ -41,6 +41,16 @@ struct DecodeArgs {
     void *O;
     float *part;              // workspace: split partials
     int splits;
+    int m_cap, k_cap, k_start;   // rows allocated per (sequence, set) / (sequence, KV head); ring row of the oldest tail token
+};
+
+// Online cache update: the g oldest ring rows become representative row m-1.
+struct UpdateArgs {
+    Dims d;                   // d.m = representatives AFTER the update
+    const void *q_recent, *pool_tail, *sel_tail;
+    void *pool_rep, *sel_rep;
+    int32_t *anchor;
+    int m_cap, k_cap, k_start;
 };
 
 // Launchers return hipSuccess or the launch error. They assume validated arguments.
@@ -56,5 +66,6 @@ bool decode_supported(const Dims &d);
 int decode_splits(const Dims &d);
 size_t decode_workspace_bytes(const Dims &d);
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t st);
+hipError_t launch_cache_update(const UpdateArgs &a, hipStream_t st);
 
 }  // namespace lca

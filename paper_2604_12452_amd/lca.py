@@ -19,7 +19,7 @@ MODE_MLA, MODE_GQA = 0, 1
 BF16, F32 = 0, 1
 
 EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condense", "lca_prefill_attn", "dense_mla_attn",
-           "lca_decode_attn", "lca_last_error")
+           "lca_decode_attn", "lca_decode_attn_cached", "lca_cache_update", "lca_last_error")
 
 
 class LcaError(RuntimeError):
@@ -31,6 +31,21 @@ class LcaError(RuntimeError):
 class _CDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("B", "L", "H", "S", "d_pool", "d_sel", "g", "w", "n_q", "mode", "dtype")] + [
         ("scale", ctypes.c_float), ("rep_logit_bias", ctypes.c_float)]
+
+
+class _CLayout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("m_cap", "k_cap", "k_start")]
+
+
+@dataclass
+class CacheLayout:
+    """Mirror of ``lca_cache_layout``: rows allocated for representatives / raw tail, ring row of the oldest tail token."""
+    m_cap: int
+    k_cap: int
+    k_start: int = 0
+
+    def c(self) -> _CLayout:
+        return _CLayout(self.m_cap, self.k_cap, self.k_start)
 
 
 @dataclass
@@ -157,6 +172,18 @@ def decode_attn(desc: Desc, q, pool_rep, sel_rep, pool_tail, sel_tail, O, worksp
     _check(load().lca_decode_attn(ctypes.byref(cd), _ptr(q), _ptr(pool_rep), _ptr(sel_rep), _ptr(pool_tail),
                                   _ptr(sel_tail), _ptr(O), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)),
                                   _stream(stream)))
+
+
+def decode_attn_cached(desc: Desc, layout: CacheLayout, q, pool_rep, sel_rep, pool_tail, sel_tail, O, workspace, stream=None):
+    cd, cl = desc.c(), layout.c()
+    _check(load().lca_decode_attn_cached(ctypes.byref(cd), ctypes.byref(cl), _ptr(q), _ptr(pool_rep), _ptr(sel_rep), _ptr(pool_tail),
+                                         _ptr(sel_tail), _ptr(O), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
+
+
+def cache_update(desc: Desc, layout: CacheLayout, q_recent, pool_tail, sel_tail, pool_rep, sel_rep, anchor_idx, workspace, stream=None):
+    cd, cl = desc.c(), layout.c()
+    _check(load().lca_cache_update(ctypes.byref(cd), ctypes.byref(cl), _ptr(q_recent), _ptr(pool_tail), _ptr(sel_tail), _ptr(pool_rep),
+                                   _ptr(sel_rep), _ptr(anchor_idx), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------

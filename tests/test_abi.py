@@ -27,7 +27,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared()
-    assert set(names) == set(lca.EXPORTS) and len(names) == 7
+    assert set(names) == set(lca.EXPORTS) and len(names) == 9
     for n in names:
         assert hasattr(lib, n)
 
@@ -48,7 +48,7 @@ def test_workspace_and_cache_bytes_are_host_only(lib):
     assert lca.workspace_size(lca.Desc(B=32, L=65537, H=32, S=8, d_pool=128, d_sel=128, g=16, w=1024, mode=lca.MODE_GQA)) > 0
 
 
-@pytest.mark.parametrize("kw", [dict(B=0), dict(L=0), dict(H=15, S=2), dict(g=0), dict(g=65), dict(w=-1), dict(n_q=9000),
+@pytest.mark.parametrize("kw", [dict(B=0), dict(L=0), dict(H=15, S=2), dict(g=0), dict(g=65), dict(w=-1), dict(n_q=-1),
                                 dict(mode=2), dict(dtype=7), dict(d_pool=100), dict(d_sel=4), dict(scale=float("nan")),
                                 dict(d_pool=2048)])
 def test_invalid_descriptors_are_rejected(lib, kw):
@@ -64,6 +64,11 @@ def test_null_misaligned_and_small_workspace_are_rejected_before_launch(lib):
     cd = d.c()
     ws = lca.workspace_size(d)
     vp, sz = ctypes.c_void_p, ctypes.c_size_t
+
+    # more summary queries than tokens: rejected by the calls that read them, fine for the others
+    big = _desc(n_q=9000).c()
+    assert lib.lca_condense(ctypes.byref(big), vp(A), vp(A), vp(A), vp(A), vp(A), vp(A), vp(0), vp(A), sz(1 << 30), vp(0)) == lca.ERR_INVALID_ARG
+    assert lca.workspace_size(_desc(n_q=9000)) > 0
 
     def condense(Q=A, POOL=A, SEL=A, pr=A, sr=A, an=A, ws_ptr=A, ws_bytes=ws):
         return lib.lca_condense(ctypes.byref(cd), vp(Q), vp(POOL), vp(SEL), vp(pr), vp(sr), vp(an), vp(0), vp(ws_ptr), sz(ws_bytes), vp(0))
