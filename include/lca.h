@@ -29,7 +29,7 @@
  *   - Invalid: NULL required pointer; B, L, H, S, g <= 0; w < 0; H % S != 0; n_q < 0, and n_q > L in
  *     the calls that read the summary queries (lca_condense, lca_cache_update); a dtype or
  *     mode outside the enums; d_pool / d_sel not multiples of 8 (bf16) or 4 (f32) or above 1024;
- *     g > 64; workspace too small (LCA_ERR_WORKSPACE).  m = 0 (L < w + g) is valid: lca_condense
+ *     g > 64; a reduce strategy outside the enum; workspace too small (LCA_ERR_WORKSPACE).  m = 0 (L < w + g) is valid: lca_condense
  *     writes nothing and lca_prefill_attn equals dense attention (section 4.3, fallback remark).
  */
 #ifndef LCA_H
@@ -53,6 +53,21 @@ typedef enum {
 typedef enum { LCA_MODE_MLA = 0, LCA_MODE_GQA = 1 } lca_mode;
 typedef enum { LCA_BF16 = 0, LCA_F32 = 1 } lca_dtype;
 
+/*
+ * How the g vectors of a group become the representative's component (the ablation of section 5.4,
+ * Table 5; appendix "Comparison with Alternative Pooling Strategies").  LCA_REDUCE_DEFAULT is the
+ * method: weighted pooling for the pooled component (Eq. 7), max selection for the selected one (Eq. 8).
+ *   WEIGHTED  sum_i alpha_i x_i with the group softmax alpha of Eq. 6
+ *   MEAN      (1/g) sum_i x_i
+ *   MAXSEL    x of the token with the largest importance score (lowest index on ties), copied
+ *   MAXPOOL   the x of largest Euclidean norm in the group (lowest index on ties), copied — the appendix
+ *             describes max pooling as keeping "the vector with the highest norm"
+ * Only lca_condense reads these fields; anchor_idx always reports the arg-max score token.
+ */
+typedef enum {
+    LCA_REDUCE_DEFAULT = 0, LCA_REDUCE_WEIGHTED = 1, LCA_REDUCE_MEAN = 2, LCA_REDUCE_MAXSEL = 3, LCA_REDUCE_MAXPOOL = 4
+} lca_reduce;
+
 typedef struct {
     int32_t B, L, H, S;     /* batch, tokens, query heads, condensed sets (H % S == 0)            */
     int32_t d_pool, d_sel;  /* widths of the pooled and of the selected component                  */
@@ -61,6 +76,8 @@ typedef struct {
     float scale;            /* multiplies q.k in the importance score and in the attention logits  */
     float rep_logit_bias;   /* added to representatives' logits: 0 = Algorithm 1; ln(g) = each
                                representative counted g times, the normaliser used in appendix A.2 */
+    int32_t pool_reduce;    /* lca_reduce for the pooled component   (0 = weighted pooling)        */
+    int32_t sel_reduce;     /* lca_reduce for the selected component (0 = max selection)           */
 } lca_desc;
 
 /* Bytes of workspace that any call below needs for this descriptor (host only, launches nothing). */

@@ -21,6 +21,7 @@ _LIB = os.path.join(_HERE, "liblca_oracle.so")
 
 MODE_MLA = 0
 MODE_GQA = 1
+RED_DEFAULT, RED_WEIGHTED, RED_MEAN, RED_MAXSEL, RED_MAXPOOL = range(5)
 
 
 def build(force: bool = False) -> str:
@@ -42,6 +43,7 @@ class _Desc(ctypes.Structure):
         ("g", ctypes.c_int32), ("w", ctypes.c_int32), ("n_q", ctypes.c_int32),
         ("mode", ctypes.c_int32),
         ("scale", ctypes.c_double), ("rep_logit_bias", ctypes.c_double),
+        ("pool_reduce", ctypes.c_int32), ("sel_reduce", ctypes.c_int32),
     ]
 
 
@@ -60,6 +62,8 @@ class Desc:
     mode: int = MODE_MLA
     scale: float = 1.0
     rep_logit_bias: float = 0.0
+    pool_reduce: int = 0   # 0 = the method (weighted pooling); 1 weighted, 2 mean, 3 max selection, 4 max pooling (Table 5)
+    sel_reduce: int = 0    # 0 = the method (max selection)
 
     @property
     def d_qk(self) -> int:
@@ -87,7 +91,7 @@ class Desc:
 
     def c(self) -> _Desc:
         return _Desc(self.B, self.L, self.H, self.S, self.d_pool, self.d_sel, self.g, self.w, self.nq,
-                     self.mode, float(self.scale), float(self.rep_logit_bias))
+                     self.mode, float(self.scale), float(self.rep_logit_bias), self.pool_reduce, self.sel_reduce)
 
 
 _lib = None

@@ -53,7 +53,12 @@ typedef struct {
     int32_t mode; /* 0 = MLA, 1 = GQA */
     double scale;
     double rep_logit_bias;
+    int32_t pool_reduce; /* how a group's vectors become the representative's pooled component: 0 = the method */
+    int32_t sel_reduce;  /* ... and its selected component (ablation of section 5.4, Table 5)                 */
 } oracle_desc;
+
+/* reduce strategies; 0 stands for the method's own: weighted pooling (Eq. 7) / max selection (Eq. 8) */
+enum { RED_DEFAULT = 0, RED_WEIGHTED = 1, RED_MEAN = 2, RED_MAXSEL = 3, RED_MAXPOOL = 4 };
 
 enum { ORACLE_OK = 0, ORACLE_BAD_ARG = 1 };
 
@@ -73,6 +78,7 @@ static int check_desc(const oracle_desc *d)
     if (d->B <= 0 || d->L <= 0 || d->H <= 0 || d->S <= 0 || d->g <= 0 || d->w < 0) return ORACLE_BAD_ARG;
     if (d->H % d->S != 0 || d->d_pool <= 0 || d->d_sel <= 0) return ORACLE_BAD_ARG;
     if (d->mode != 0 && d->mode != 1) return ORACLE_BAD_ARG;
+    if (d->pool_reduce < 0 || d->pool_reduce > 4 || d->sel_reduce < 0 || d->sel_reduce > 4) return ORACLE_BAD_ARG;
     return ORACLE_OK;
 }
 
@@ -128,6 +134,9 @@ int oracle_summary_query(const oracle_desc *d, const double *q_tail, double *qba
  *   alpha_i = exp(s_i) / sum_{k in G_j} exp(s_k)          (Eq. 6)
  *   c^rep_j = sum_i alpha_i * pool_i                      (Eq. 7)
  *   I_j     = lowest i with s_i = max                     (Eq. 8),  sel_rep_j = sel_{I_j}
+ * With the ablation's other strategies (section 5.4, Table 5; appendix on alternative pooling) a component is
+ * instead the plain mean, the alpha-weighted sum, the arg-max score token's vector, or ("max pooling", which the
+ * appendix describes as keeping the vector with the highest norm) the group's vector of largest Euclidean norm.
  *   margin_j = gap between the largest and second-largest score (0 when g == 1 is reported as +inf)
  * Outputs: pool_rep [B,S,m,d_pool], sel_rep [B,S,m,d_sel], anchor [B,S,m] (absolute token
  * index), alpha [B,S,m*g] (nullable), margin [B,S,m] (nullable).
@@ -157,20 +166,39 @@ int oracle_condense(const oracle_desc *d, const double *qbar, const double *POOL
         double z = 0.0;
         for (int r = 0; r < g; ++r) { al[r] = exp(sc[r] - mx); z += al[r]; }
         for (int r = 0; r < g; ++r) al[r] /= z;
-        /* weighted pooling, Eq. 7 */
-        double *cr = pool_rep + (size_t)u * d->d_pool;
-        for (int x = 0; x < d->d_pool; ++x) {
-            double acc = 0.0;
-            for (int r = 0; r < g; ++r) acc += al[r] * tok_row(POOL, d, b, j * g + r, p, d->d_pool)[x];
-            cr[x] = acc;
-        }
         /* anchor, Eq. 8: first index attaining the maximum */
         int best = 0;
         for (int r = 1; r < g; ++r) if (sc[r] > sc[best]) best = r;
         double second = -INFINITY;
         for (int r = 0; r < g; ++r) if (r != best && sc[r] > second) second = sc[r];
         anchor[u] = j * g + best;
-        memcpy(sel_rep + (size_t)u * d->d_sel, tok_row(SEL, d, b, j * g + best, p, d->d_sel), sizeof(double) * d->d_sel);
+        /* the two components of the representative: Eq. 7 and Eq. 8 unless the ablation asks otherwise */
+        for (int comp = 0; comp < 2; ++comp) {
+            const double *X = comp == 0 ? POOL : SEL;
+            const int width = comp == 0 ? d->d_pool : d->d_sel;
+            double *out = (comp == 0 ? pool_rep : sel_rep) + (size_t)u * width;
+            int strat = comp == 0 ? d->pool_reduce : d->sel_reduce;
+            if (strat == RED_DEFAULT) strat = comp == 0 ? RED_WEIGHTED : RED_MAXSEL;
+            if (strat == RED_WEIGHTED || strat == RED_MEAN) {
+                for (int x = 0; x < width; ++x) {
+                    double acc = 0.0;
+                    for (int r = 0; r < g; ++r) acc += (strat == RED_WEIGHTED ? al[r] : 1.0 / g) * tok_row(X, d, b, j * g + r, p, width)[x];
+                    out[x] = acc;
+                }
+            } else {
+                int pick = best;                                  /* max selection: the arg-max score token */
+                if (strat == RED_MAXPOOL) {                       /* max pooling: the vector of largest Euclidean norm */
+                    double nbest = -1.0;
+                    for (int r = 0; r < g; ++r) {
+                        const double *row = tok_row(X, d, b, j * g + r, p, width);
+                        double n2 = 0.0;
+                        for (int x = 0; x < width; ++x) n2 += row[x] * row[x];
+                        if (n2 > nbest) { nbest = n2; pick = r; }
+                    }
+                }
+                memcpy(out, tok_row(X, d, b, j * g + pick, p, width), sizeof(double) * width);
+            }
+        }
         if (margin) margin[u] = sc[best] - second;
         if (alpha) memcpy(alpha + (size_t)u * g, al, sizeof(double) * g);
         free(sc);

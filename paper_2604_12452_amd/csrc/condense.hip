@@ -287,14 +287,68 @@ void condense_reg_kernel(const T *__restrict__ POOL, const T *__restrict__ SEL, 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Generic condensation: one wave per (b, s, j), run-time sizes, g <= 64.
+// Generic condensation: one wave per (b, s, j), run-time sizes, g <= 64; any reduce strategy for either
+// component (the ablation grid of section 5.4, Table 5).
 // ---------------------------------------------------------------------------------------------
+// Lane r holds v_r (r < g); returns, in every lane, the row with the largest v (lowest row on ties).
+__device__ __forceinline__ int wave_argmax(float v, int lane, float *vmax_out)
+{
+    float bmax = v;
+    int brow = lane;
+    for (int mask = 32; mask >= 1; mask >>= 1) {
+        const float os = __shfl_xor(bmax, mask, WAVE);
+        const int orow = __shfl_xor(brow, mask, WAVE);
+        if (os > bmax || (os == bmax && orow < brow)) { bmax = os; brow = orow; }
+    }
+    if (vmax_out) *vmax_out = bmax;
+    return brow;
+}
+
+// One component of the representative: rows base + (j*g + r)*row_stride, r < g, `width` wide, into out.
+//   WEIGHTED / MEAN: sum of w_r x_r with lane r holding w_r;  MAXSEL / MAXPOOL: row `pick`, copied bit for bit.
+template <typename T>
+__device__ __forceinline__ void reduce_component(int strategy, const T *base, size_t row_stride, int j, int g, int width, float w_mine, int pick,
+                                                 T *out, int lane)
+{
+    if (strategy == LCA_REDUCE_MAXSEL || strategy == LCA_REDUCE_MAXPOOL) {
+        const T *src = base + (size_t)(j * g + pick) * row_stride;
+        for (int x = lane; x < width; x += WAVE) out[x] = src[x];
+        return;
+    }
+    for (int x0 = 0; x0 < width; x0 += WAVE) {      // every lane takes part in the broadcasts
+        const int x = x0 + lane;
+        float acc = 0.f;
+        for (int r = 0; r < g; ++r) {
+            const float wr = __shfl(w_mine, r, WAVE);
+            if (x < width) acc = fmaf(wr, Elt<T>::ld(base + (size_t)(j * g + r) * row_stride + x), acc);
+        }
+        if (x < width) Elt<T>::st(out + x, acc);
+    }
+}
+
+// Lane r gets the squared Euclidean norm of row r of the group (for MAXPOOL).
+template <typename T>
+__device__ __forceinline__ float row_norms(const T *base, size_t row_stride, int j, int g, int width, int lane)
+{
+    float mine = -INFINITY;
+    for (int r = 0; r < g; ++r) {
+        float a = 0.f;
+        for (int x = lane; x < width; x += WAVE) {
+            const float v = Elt<T>::ld(base + (size_t)(j * g + r) * row_stride + x);
+            a = fmaf(v, v, a);
+        }
+        for (int mask = 32; mask >= 1; mask >>= 1) a += __shfl_xor(a, mask, WAVE);
+        if (lane == r) mine = a;
+    }
+    return mine;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void condense_generic_kernel(const T *__restrict__ POOL, const T *__restrict__ SEL,
                                                                const float *__restrict__ qbar, T *__restrict__ pool_rep,
                                                                T *__restrict__ sel_rep, int32_t *__restrict__ anchor,
                                                                float *__restrict__ alpha_dbg, int B, int L, int S, int m, int g,
-                                                               int d_pool, int d_sel, int mla, float scale)
+                                                               int d_pool, int d_sel, int mla, float scale, int pool_reduce, int sel_reduce)
 {
     const int lane = threadIdx.x & (WAVE - 1);
     const long unit = (long)blockIdx.x * (blockDim.x / WAVE) + (threadIdx.x / WAVE);
@@ -304,11 +358,12 @@ __global__ __launch_bounds__(256) void condense_generic_kernel(const T *__restri
     const float *qb = qbar + ((size_t)b * S + s) * d_qk;
     const T *pool_base = POOL + ((size_t)b * L * P + p) * d_pool;
     const T *sel_base = SEL + ((size_t)b * L * P + p) * d_sel;
+    const size_t pool_stride = (size_t)P * d_pool, sel_stride = (size_t)P * d_sel;
 
     float my_score = -INFINITY;            // lane r holds the score of row r
     for (int r = 0; r < g; ++r) {
-        const T *pr = pool_base + (size_t)(j * g + r) * P * d_pool;
-        const T *sr = sel_base + (size_t)(j * g + r) * P * d_sel;
+        const T *pr = pool_base + (size_t)(j * g + r) * pool_stride;
+        const T *sr = sel_base + (size_t)(j * g + r) * sel_stride;
         float a = 0.f;
         if (mla)
             for (int x = lane; x < d_pool; x += WAVE) a = fmaf(Elt<T>::ld(pr + x), qb[x], a);
@@ -317,29 +372,22 @@ __global__ __launch_bounds__(256) void condense_generic_kernel(const T *__restri
         for (int mask = 32; mask >= 1; mask >>= 1) a += __shfl_xor(a, mask, WAVE);
         if (lane == r) my_score = scale * a;
     }
-    float bmax = my_score;
-    int brow = lane;
-    for (int mask = 32; mask >= 1; mask >>= 1) {
-        const float os = __shfl_xor(bmax, mask, WAVE);
-        const int orow = __shfl_xor(brow, mask, WAVE);
-        if (os > bmax || (os == bmax && orow < brow)) { bmax = os; brow = orow; }
-    }
+    float bmax;
+    const int brow = wave_argmax(my_score, lane, &bmax);
     const float pmine = lane < g ? __expf(my_score - bmax) : 0.f;
     float z = pmine;
     for (int mask = 32; mask >= 1; mask >>= 1) z += __shfl_xor(z, mask, WAVE);
     const float alpha = pmine / z;
-    for (int x0 = 0; x0 < d_pool; x0 += WAVE) {      // every lane takes part in the broadcasts
-        const int x = x0 + lane;
-        float acc = 0.f;
-        for (int r = 0; r < g; ++r) {
-            const float ar = __shfl(alpha, r, WAVE);
-            if (x < d_pool) acc = fmaf(ar, Elt<T>::ld(pool_base + (size_t)(j * g + r) * P * d_pool + x), acc);
-        }
-        if (x < d_pool) Elt<T>::st(pool_rep + (size_t)unit * d_pool + x, acc);
-    }
-    const int a_tok = j * g + brow;
-    for (int x = lane; x < d_sel; x += WAVE) sel_rep[(size_t)unit * d_sel + x] = sel_base[(size_t)a_tok * P * d_sel + x];
-    if (lane == 0) anchor[unit] = a_tok;
+    const float mean_w = lane < g ? 1.f / (float)g : 0.f;
+
+    int pick_pool = brow, pick_sel = brow;
+    if (pool_reduce == LCA_REDUCE_MAXPOOL) pick_pool = wave_argmax(row_norms(pool_base, pool_stride, j, g, d_pool, lane), lane, nullptr);
+    if (sel_reduce == LCA_REDUCE_MAXPOOL) pick_sel = wave_argmax(row_norms(sel_base, sel_stride, j, g, d_sel, lane), lane, nullptr);
+    reduce_component(pool_reduce, pool_base, pool_stride, j, g, d_pool, pool_reduce == LCA_REDUCE_MEAN ? mean_w : alpha, pick_pool,
+                     pool_rep + (size_t)unit * d_pool, lane);
+    reduce_component(sel_reduce, sel_base, sel_stride, j, g, d_sel, sel_reduce == LCA_REDUCE_MEAN ? mean_w : alpha, pick_sel,
+                     sel_rep + (size_t)unit * d_sel, lane);
+    if (lane == 0) anchor[unit] = j * g + brow;
     if (alpha_dbg != nullptr && lane < g) alpha_dbg[(size_t)unit * g + lane] = alpha;
 }
 
@@ -362,7 +410,7 @@ hipError_t run_generic(const CondenseArgs &a, hipStream_t st)
     const int blocks = (int)((units + 3) / 4);
     condense_generic_kernel<T><<<blocks, 256, 0, st>>>((const T *)a.POOL, (const T *)a.SEL, a.qbar, (T *)a.pool_rep, (T *)a.sel_rep,
                                                        a.anchor, a.alpha_dbg, d.B, d.L, d.S, d.m, d.g, d.d_pool, d.d_sel,
-                                                       d.mode == LCA_MODE_MLA, d.scale);
+                                                       d.mode == LCA_MODE_MLA, d.scale, d.pool_reduce, d.sel_reduce);
     return hipGetLastError();
 }
 
@@ -397,6 +445,9 @@ hipError_t launch_condense(const CondenseArgs &a, hipStream_t st)
     if (err != hipSuccess || d.m == 0) return err;
     // 2. groups
     const bool mla = d.mode == LCA_MODE_MLA;
+    // the register kernels implement the method's own strategies (weighted pooling, max selection); the ablation's others run generic
+    if (d.pool_reduce != LCA_REDUCE_WEIGHTED || d.sel_reduce != LCA_REDUCE_MAXSEL)
+        return d.dtype == LCA_BF16 ? run_generic<uint16_t>(a, st) : run_generic<float>(a, st);
     if (d.dtype == LCA_BF16 && mla && d.d_pool == 512 && d.d_sel == 64 && try_reg<uint16_t, 512, 64, true>(a, st, err)) return err;
     if (d.dtype == LCA_BF16 && !mla && d.d_pool == 128 && d.d_sel == 128 && try_reg<uint16_t, 128, 128, false>(a, st, err)) return err;
     if (d.dtype == LCA_F32 && mla && d.d_pool == 128 && d.d_sel == 32 && try_reg<float, 128, 32, true>(a, st, err)) return err;

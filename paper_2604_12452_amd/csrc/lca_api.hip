@@ -48,6 +48,10 @@ lca_status make_dims(const lca_desc *desc, lca::Dims &d)
     d.k = desc->L - d.m * desc->g;
     d.mode = desc->mode; d.dtype = desc->dtype; d.elt = desc->dtype == LCA_BF16 ? 2 : 4;
     d.scale = desc->scale; d.rep_logit_bias = desc->rep_logit_bias;
+    if (desc->pool_reduce < 0 || desc->pool_reduce > LCA_REDUCE_MAXPOOL || desc->sel_reduce < 0 || desc->sel_reduce > LCA_REDUCE_MAXPOOL)
+        return fail(LCA_ERR_INVALID_ARG, "unknown reduce strategy (%d, %d)", desc->pool_reduce, desc->sel_reduce);
+    d.pool_reduce = desc->pool_reduce == LCA_REDUCE_DEFAULT ? LCA_REDUCE_WEIGHTED : desc->pool_reduce;
+    d.sel_reduce = desc->sel_reduce == LCA_REDUCE_DEFAULT ? LCA_REDUCE_MAXSEL : desc->sel_reduce;
     return LCA_OK;
 }
 
@@ -234,6 +238,8 @@ lca_status lca_cache_update(const lca_desc *desc, const lca_cache_layout *layout
     if (d.L < d.w + d.g || (d.L - d.w) % d.g != 0)
         return fail(LCA_ERR_INVALID_ARG, "no update is due at L = %d (w = %d, g = %d): needs L >= w + g and (L - w) mod g == 0", d.L, d.w, d.g);
     if (d.n_q > d.L) return fail(LCA_ERR_INVALID_ARG, "n_q (%d) must be in [1, L]", d.n_q);
+    if (d.pool_reduce != LCA_REDUCE_WEIGHTED || d.sel_reduce != LCA_REDUCE_MAXSEL)
+        return fail(LCA_ERR_UNSUPPORTED, "lca_cache_update is built for the method's own strategies only (weighted pooling, max selection)");
     LCA_TRY(check_layout(d, layout, d.w + d.g));
     LCA_TRY(check_ptr(q_recent, "q_recent"));
     LCA_TRY(check_ptr(pool_tail, "pool_tail"));

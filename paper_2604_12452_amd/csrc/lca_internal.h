@@ -15,6 +15,7 @@ struct Dims {
     int g, w, n_q, m, k;      // m groups, k raw tail tokens
     int mode, dtype, elt;     // elt = bytes per element
     float scale, rep_logit_bias;
+    int pool_reduce, sel_reduce;   // resolved lca_reduce (never DEFAULT)
 };
 
 // Where one attention launch finds its keys/values.

@@ -17,6 +17,7 @@ LIB_PATH = os.environ.get("LCA_LIB_PATH", os.path.join(_PKG, "liblca.so"))   # o
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 MODE_MLA, MODE_GQA = 0, 1
 BF16, F32 = 0, 1
+REDUCE_DEFAULT, REDUCE_WEIGHTED, REDUCE_MEAN, REDUCE_MAXSEL, REDUCE_MAXPOOL = range(5)
 
 EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condense", "lca_prefill_attn", "dense_mla_attn",
            "lca_decode_attn", "lca_decode_attn_cached", "lca_cache_update", "lca_last_error")
@@ -30,7 +31,7 @@ class LcaError(RuntimeError):
 
 class _CDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("B", "L", "H", "S", "d_pool", "d_sel", "g", "w", "n_q", "mode", "dtype")] + [
-        ("scale", ctypes.c_float), ("rep_logit_bias", ctypes.c_float)]
+        ("scale", ctypes.c_float), ("rep_logit_bias", ctypes.c_float), ("pool_reduce", ctypes.c_int32), ("sel_reduce", ctypes.c_int32)]
 
 
 class _CLayout(ctypes.Structure):
@@ -64,6 +65,8 @@ class Desc:
     dtype: int = BF16
     scale: float = 1.0
     rep_logit_bias: float = 0.0
+    pool_reduce: int = 0      # REDUCE_*: 0 = the method's own (weighted pooling / max selection)
+    sel_reduce: int = 0
 
     @property
     def d_qk(self) -> int:
@@ -83,7 +86,7 @@ class Desc:
 
     def c(self) -> _CDesc:
         return _CDesc(self.B, self.L, self.H, self.S, self.d_pool, self.d_sel, self.g, self.w, self.n_q, self.mode,
-                      self.dtype, float(self.scale), float(self.rep_logit_bias))
+                      self.dtype, float(self.scale), float(self.rep_logit_bias), self.pool_reduce, self.sel_reduce)
 
 
 _lib = None

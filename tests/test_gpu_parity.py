@@ -225,3 +225,46 @@ def test_gqa_logits_far_above_first_tile(oracle, dense_only):
     else:
         run.prefill()
         hp.check_prefill(oracle, wl, run, rows, Qf, POOLf, SELf, ref, differ)
+
+
+# ---- the ablation's alternative pooling strategies (section 5.4, Table 5) ---------------------------------
+REDUCE_NAMES = {1: "weighted", 2: "mean", 3: "maxsel", 4: "maxpool"}
+
+
+@pytest.mark.parametrize("dtype,mode", [("f32", inputs.MODE_MLA), ("bf16", inputs.MODE_GQA), ("bf16", inputs.MODE_MLA)])
+@pytest.mark.parametrize("pool_reduce", [1, 2, 3, 4])
+@pytest.mark.parametrize("sel_reduce", [1, 2, 3, 4])
+def test_condense_reduce_strategies(oracle, dtype, mode, pool_reduce, sel_reduce):
+    """Every cell of the grid: lca_condense with the given strategies against the oracle with the same ones.
+    Summed components within tolerance; selected components are bit-exact copies of a row of the group —
+    the anchor's row for max selection, a row of (numerically) largest norm for max pooling."""
+    wl = _wl("reduce", L=203, g=8, w=11, H=4, S=2, dtype=dtype, mode=mode, d_pool=24, d_sel=16, B=2)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    Qf, POOLf, SELf = (inputs.to_f64(x, wl.dtype) for x in (Q, POOL, SEL))
+    run = hp.GpuRun(wl, Q, POOL, SEL)
+    run.desc.pool_reduce, run.desc.sel_reduce = pool_reduce, sel_reduce
+    run.condense()
+    od = hp.oracle_desc(oracle, wl, pool_reduce=pool_reduce, sel_reduce=sel_reduce)
+    ref = oracle.condense(od, oracle.summary_query(od, Qf[:, wl.L - wl.nq:]), POOLf, SELf)
+    anchor = run.anchor.cpu().numpy()
+    differ = anchor != ref["anchor"]
+    assert not (differ & (ref["margin"] > hp.ANCHOR_MARGIN)).any(), "anchor mismatch above the score margin"
+    for name, strat, X, got_t, want in (("pool", pool_reduce, POOLf, run.pool_rep, ref["pool_rep"]),
+                                        ("sel", sel_reduce, SELf, run.sel_rep, ref["sel_rep"])):
+        got = hp.from_dev(got_t, wl.dtype)
+        if strat in (1, 2):
+            keep = ~differ if strat == 1 else np.ones_like(differ)
+            err = hp.vec_rel_err(got[keep], want[keep])
+            assert err <= hp.TOL[wl.dtype], f"{name} component ({REDUCE_NAMES[strat]}) rel err {err:.3e}"
+            continue
+        for b in range(wl.B):
+            for s in range(wl.S):
+                rows_all = X[b] if wl.mode == inputs.MODE_MLA else X[b, :, s]
+                for j in range(od.m):
+                    grp = rows_all[j * wl.g:(j + 1) * wl.g]
+                    if strat == 3:
+                        np.testing.assert_array_equal(got[b, s, j], rows_all[anchor[b, s, j]])
+                    else:
+                        n2 = (grp * grp).sum(-1)
+                        hits = [r for r in range(wl.g) if (got[b, s, j] == grp[r]).all()]
+                        assert hits and n2[hits[0]] >= n2.max() * (1 - 1e-5), f"{name} component: not a row of largest norm"
