@@ -176,7 +176,7 @@ lca_status lca_decode_attn_cached(const lca_desc *desc, const lca_cache_layout *
  * In:  q_recent [B,n_q,H,d_qk], oldest first; pool_tail, sel_tail (the ring, read only).
  * Out: row m-1 of pool_rep [B,S,m_cap,d_pool], sel_rep [B,S,m_cap,d_sel], anchor_idx [B,S,m_cap] (may be NULL).
  * Invalid in addition: L < w + g or (L - w) mod g != 0; m > m_cap; w + g > k_cap; k_start outside [0, k_cap).
- * Workspace: lca_workspace_size(desc) bytes are enough (unused by the current kernels).
+ * Workspace: lca_workspace_size(desc) bytes (the summary query lives there).
  */
 lca_status lca_cache_update(const lca_desc *desc, const lca_cache_layout *layout, const void *q_recent,
                             const void *pool_tail, const void *sel_tail, void *pool_rep, void *sel_rep,

@@ -3,8 +3,11 @@
 // the mean query of the last n_q tokens (Eq. 6), softmax-weighted pooling of the pooled component (Eq. 7),
 // the selected component copied from the arg-max token (Eq. 8; lowest index on ties).
 //
-// One wavefront per (sequence, set): g rows of at most 2 KB each — the step is bound by launch latency, not
-// by bandwidth, and runs once every g decode steps.  Any widths, both element types, both modes.
+// The summary query comes from the condensation's own summary_query_kernel (the g recent queries are a
+// sequence of length n_q to it).  Then one workgroup of four wavefronts per (sequence, set): the wavefronts
+// split the g rows for the scores, the threads split the columns for the pooled row.  g rows of at most 2 KB
+// each — the step is bound by launch latency, not by bandwidth, and runs once every g decode steps.  Any
+// widths, both element types, both modes.
 #include "lca_internal.h"
 
 namespace lca {
@@ -33,26 +36,21 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
+constexpr int UPD_THREADS = 256;
+
 // dynamic LDS: qbar[d_qk] then score[g]
 template <typename T>
-__global__ __launch_bounds__(64) void cache_update_kernel(const T *__restrict__ q_recent, const T *__restrict__ pool_tail,
-                                                          const T *__restrict__ sel_tail, T *__restrict__ pool_rep, T *__restrict__ sel_rep,
-                                                          int32_t *__restrict__ anchor, int H, int S, int P, int d_pool, int d_sel, int d_qk,
-                                                          int g, int n_q, int m, int mla, float scale, int m_cap, int k_cap, int k_start)
+__global__ __launch_bounds__(UPD_THREADS) void cache_update_kernel(const float *__restrict__ qbar_g, const T *__restrict__ pool_tail,
+                                                                   const T *__restrict__ sel_tail, T *__restrict__ pool_rep,
+                                                                   T *__restrict__ sel_rep, int32_t *__restrict__ anchor, int S, int P, int d_pool,
+                                                                   int d_sel, int d_qk, int g, int m, int mla, float scale, int m_cap, int k_cap,
+                                                                   int k_start)
 {
     extern __shared__ float lds[];
     float *qbar = lds, *score = lds + d_qk;
-    const int lane = threadIdx.x, s = blockIdx.x, b = blockIdx.y;
-    const int hps = H / S, p = mla ? 0 : s;
-
-    // summary query of set s: mean over the n_q recent tokens and the set's heads
-    const float inv_n = 1.f / (float)(n_q * hps);
-    for (int col = lane; col < d_qk; col += 64) {
-        float a = 0.f;
-        for (int t = 0; t < n_q; ++t)
-            for (int h = 0; h < hps; ++h) a += Elt<T>::ld(q_recent + (((size_t)b * n_q + t) * H + s * hps + h) * d_qk + col);
-        qbar[col] = a * inv_n;
-    }
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, s = blockIdx.x, b = blockIdx.y;
+    const int p = mla ? 0 : s;
+    for (int col = tid; col < d_qk; col += UPD_THREADS) qbar[col] = qbar_g[((size_t)b * S + s) * d_qk + col];
     __syncthreads();
 
     auto ring_row = [&](int i) { const int r = k_start + i; return r >= k_cap ? r - k_cap : r; };
@@ -60,7 +58,7 @@ __global__ __launch_bounds__(64) void cache_update_kernel(const T *__restrict__ 
     const T *stail = sel_tail + ((size_t)b * P + p) * k_cap * d_sel;
 
     // scores of the g oldest tail tokens: key = [pooled ; selected] (MLA, absorbed form) or the selected component (GQA)
-    for (int i = 0; i < g; ++i) {
+    for (int i = wave; i < g; i += UPD_THREADS / 64) {
         const int r = ring_row(i);
         float a = 0.f;
         if (mla)
@@ -71,7 +69,7 @@ __global__ __launch_bounds__(64) void cache_update_kernel(const T *__restrict__ 
     }
     __syncthreads();
 
-    // group softmax and arg-max (every lane redundantly: g <= 64 values)
+    // group softmax and arg-max (every thread redundantly: g <= 64 values)
     float mx = -INFINITY;
     int best = 0;
     for (int i = 0; i < g; ++i)
@@ -83,14 +81,14 @@ __global__ __launch_bounds__(64) void cache_update_kernel(const T *__restrict__ 
     // pooled component: softmax-weighted sum; selected component: the arg-max token's, copied
     T *prep = pool_rep + (((size_t)b * S + s) * m_cap + (m - 1)) * d_pool;
     T *srep = sel_rep + (((size_t)b * S + s) * m_cap + (m - 1)) * d_sel;
-    for (int col = lane; col < d_pool; col += 64) {
+    for (int col = tid; col < d_pool; col += UPD_THREADS) {
         float a = 0.f;
         for (int i = 0; i < g; ++i) a += __expf(score[i] - mx) * inv_z * Elt<T>::ld(ptail + (size_t)ring_row(i) * d_pool + col);
         Elt<T>::st(prep + col, a);
     }
     const int rb = ring_row(best);
-    for (int col = lane; col < d_sel; col += 64) srep[col] = stail[(size_t)rb * d_sel + col];
-    if (anchor != nullptr && lane == 0) anchor[((size_t)b * S + s) * m_cap + (m - 1)] = (m - 1) * g + best;
+    for (int col = tid; col < d_sel; col += UPD_THREADS) srep[col] = stail[(size_t)rb * d_sel + col];
+    if (anchor != nullptr && tid == 0) anchor[((size_t)b * S + s) * m_cap + (m - 1)] = (m - 1) * g + best;
 }
 
 template <typename T>
@@ -98,9 +96,9 @@ hipError_t run(const UpdateArgs &a, hipStream_t st)
 {
     const Dims &d = a.d;
     const size_t lds_bytes = (size_t)(d.d_qk + d.g) * sizeof(float);
-    cache_update_kernel<T><<<dim3(d.S, d.B), 64, lds_bytes, st>>>(
-        (const T *)a.q_recent, (const T *)a.pool_tail, (const T *)a.sel_tail, (T *)a.pool_rep, (T *)a.sel_rep, a.anchor, d.H, d.S, d.P, d.d_pool,
-        d.d_sel, d.d_qk, d.g, d.n_q, d.m, d.mode == LCA_MODE_MLA ? 1 : 0, d.scale, a.m_cap, a.k_cap, a.k_start);
+    cache_update_kernel<T><<<dim3(d.S, d.B), UPD_THREADS, lds_bytes, st>>>(
+        a.qbar, (const T *)a.pool_tail, (const T *)a.sel_tail, (T *)a.pool_rep, (T *)a.sel_rep, a.anchor, d.S, d.P, d.d_pool, d.d_sel, d.d_qk, d.g,
+        d.m, d.mode == LCA_MODE_MLA ? 1 : 0, d.scale, a.m_cap, a.k_cap, a.k_start);
     return hipGetLastError();
 }
 
@@ -108,6 +106,9 @@ hipError_t run(const UpdateArgs &a, hipStream_t st)
 
 hipError_t launch_cache_update(const UpdateArgs &a, hipStream_t st)
 {
+    // the n_q recent queries are, to the summary-query kernel, a sequence of n_q tokens of which it averages the last n_q
+    const hipError_t e = launch_summary_query(a.d, a.q_recent, a.d.n_q, a.qbar, st);
+    if (e != hipSuccess) return e;
     return a.d.dtype == LCA_BF16 ? run<uint16_t>(a, st) : run<float>(a, st);
 }
 

@@ -430,18 +430,24 @@ bool try_reg(const CondenseArgs &a, hipStream_t st, hipError_t &err)
 
 }  // namespace
 
+// qbar [B,S,d_qk] = mean of the last n_q of the L queries in Q [B,L,H,d_qk] (and of each set's heads)
+hipError_t launch_summary_query(const Dims &d, const void *Q, int L, float *qbar, hipStream_t st)
+{
+    if (d.dtype == LCA_BF16) {
+        const int sq_blocks = d.B * d.S * ((d.d_qk / 8 + WAVE - 1) / WAVE);
+        summary_query_kernel<uint16_t><<<sq_blocks, SQ_WAVES * WAVE, 0, st>>>((const uint16_t *)Q, qbar, L, d.H, d.S, d.d_qk, d.n_q);
+    } else {
+        const int sq_blocks = d.B * d.S * ((d.d_qk / 4 + WAVE - 1) / WAVE);
+        summary_query_kernel<float><<<sq_blocks, SQ_WAVES * WAVE, 0, st>>>((const float *)Q, qbar, L, d.H, d.S, d.d_qk, d.n_q);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_condense(const CondenseArgs &a, hipStream_t st)
 {
     const Dims &d = a.d;
     // 1. summary query (Algorithm 1, first step)
-    if (d.dtype == LCA_BF16) {
-        const int sq_blocks = d.B * d.S * ((d.d_qk / 8 + WAVE - 1) / WAVE);
-        summary_query_kernel<uint16_t><<<sq_blocks, SQ_WAVES * WAVE, 0, st>>>((const uint16_t *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
-    } else {
-        const int sq_blocks = d.B * d.S * ((d.d_qk / 4 + WAVE - 1) / WAVE);
-        summary_query_kernel<float><<<sq_blocks, SQ_WAVES * WAVE, 0, st>>>((const float *)a.Q, a.qbar, d.L, d.H, d.S, d.d_qk, d.n_q);
-    }
-    hipError_t err = hipGetLastError();
+    hipError_t err = launch_summary_query(d, a.Q, d.L, a.qbar, st);
     if (err != hipSuccess || d.m == 0) return err;
     // 2. groups
     const bool mla = d.mode == LCA_MODE_MLA;

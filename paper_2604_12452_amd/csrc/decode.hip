@@ -360,22 +360,61 @@ __global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const uint16_t 
     for (int x = tid; x < H * (D + 2); x += WAVE * NWAVE) dst[x] = comb[x];
 }
 
+// One workgroup per (b, set, head-in-set): blockIdx.x = (b*S + s)*HPS + h.  The weights of the splits,
+// exp(max_sp - max) / sum, are computed once into LDS; then every thread owns two adjacent columns and sums
+// the splits' rows with 8-byte loads, eight of them in flight.  DP is even; rows start 8 bytes into a
+// (DP + 2)-float record, so 8 bytes is the alignment there is.
+constexpr int MERGE_THREADS = 256;
 template <typename T>
-__global__ void decode_merge_kernel(const float *__restrict__ part, T *__restrict__ O, int HPS, int DP, int splits)
+__global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(const float *__restrict__ part, T *__restrict__ O, int HPS, int DP, int splits)
 {
-    // one workgroup per (b, set, head-in-set): blockIdx.x = (b*S + s)*HPS + h
+    extern __shared__ float wgt[];                        // [splits]
+    __shared__ float red[MERGE_THREADS / WAVE];
     const size_t bs = blockIdx.x / HPS;
-    const int h = blockIdx.x % HPS;
+    const int h = blockIdx.x % HPS, tid = threadIdx.x;
     const float *base = part + (bs * splits * HPS + h) * (size_t)(DP + 2);
     const size_t stride = (size_t)HPS * (DP + 2);
+    auto block_reduce = [&](float v, bool is_max) {
+        for (int o = 32; o > 0; o >>= 1) {
+            const float u = __shfl_xor(v, o, WAVE);
+            v = is_max ? fmaxf(v, u) : v + u;
+        }
+        __syncthreads();                                  // red[] free again
+        if ((tid & (WAVE - 1)) == 0) red[tid / WAVE] = v;
+        __syncthreads();
+        float r = red[0];
+        for (int i = 1; i < MERGE_THREADS / WAVE; ++i) r = is_max ? fmaxf(r, red[i]) : r + red[i];
+        return r;
+    };
     float mx = -INFINITY;
-    for (int sp = 0; sp < splits; ++sp) mx = fmaxf(mx, base[sp * stride]);
+    for (int sp = tid; sp < splits; sp += MERGE_THREADS) mx = fmaxf(mx, base[sp * stride]);
+    mx = block_reduce(mx, true);
     float l = 0.f;
-    for (int sp = 0; sp < splits; ++sp) l += base[sp * stride + 1] * __expf(base[sp * stride] - mx);
-    for (int x = threadIdx.x; x < DP; x += blockDim.x) {
-        float a = 0.f;
-        for (int sp = 0; sp < splits; ++sp) a += base[sp * stride + 2 + x] * __expf(base[sp * stride] - mx);
-        DElt<T>::st(O + (size_t)blockIdx.x * DP + x, a / l);
+    for (int sp = tid; sp < splits; sp += MERGE_THREADS) {
+        const float e = __expf(base[sp * stride] - mx);
+        wgt[sp] = e;
+        l += base[sp * stride + 1] * e;
+    }
+    l = block_reduce(l, false);                           // (its barriers also publish wgt[])
+    const float inv = 1.f / l;
+    for (int x = 2 * tid; x < DP; x += 2 * MERGE_THREADS) {
+        float a0 = 0.f, a1 = 0.f;
+        const float *col = base + 2 + x;
+        int sp = 0;
+        for (; sp + 8 <= splits; sp += 8) {
+            float2 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float2 *>(col + (sp + u) * stride);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { a0 = fmaf(v[u].x, wgt[sp + u], a0); a1 = fmaf(v[u].y, wgt[sp + u], a1); }
+        }
+        for (; sp < splits; ++sp) {
+            const float2 v = *reinterpret_cast<const float2 *>(col + sp * stride);
+            a0 = fmaf(v.x, wgt[sp], a0);
+            a1 = fmaf(v.y, wgt[sp], a1);
+        }
+        DElt<T>::st(O + (size_t)blockIdx.x * DP + x, a0 * inv);
+        DElt<T>::st(O + (size_t)blockIdx.x * DP + x + 1, a1 * inv);
     }
 }
 
@@ -388,7 +427,7 @@ hipError_t run_gqa(const DecodeArgs &a, hipStream_t st)
         (const uint16_t *)a.sel_tail, a.part, d.S, d.m, d.k, a.splits, d.scale, d.rep_logit_bias, a.m_cap, a.k_cap, a.k_start);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    decode_merge_kernel<uint16_t><<<d.B * d.H, 128, 0, st>>>(a.part, (uint16_t *)a.O, HPS, 128, a.splits);
+    decode_merge_kernel<uint16_t><<<d.B * d.H, MERGE_THREADS, a.splits * sizeof(float), st>>>(a.part, (uint16_t *)a.O, HPS, 128, a.splits);
     return hipGetLastError();
 }
 
@@ -401,7 +440,7 @@ hipError_t run(const DecodeArgs &a, hipStream_t st)
         d.k, a.splits, d.scale, d.rep_logit_bias, a.m_cap, a.k_cap, a.k_start);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    decode_merge_kernel<T><<<d.B * d.H, 128, 0, st>>>(a.part, (T *)a.O, HPS, DP, a.splits);
+    decode_merge_kernel<T><<<d.B * d.H, MERGE_THREADS, a.splits * sizeof(float), st>>>(a.part, (T *)a.O, HPS, DP, a.splits);
     return hipGetLastError();
 }
 
@@ -418,10 +457,11 @@ int shape_id(const Dims &d)
 
 }  // namespace
 
-bool decode_supported(const Dims &d) { return shape_id(d) != 0; }
+bool decode_supported(const Dims &d) { return decode_mla_supported(d) || shape_id(d) != 0; }
 
 int decode_splits(const Dims &d)
 {
+    if (decode_mla_supported(d)) return decode_mla_parts(d);
     const int n = d.m + d.k;
     int splits = (TARGET_BLOCKS + d.B * d.S - 1) / (d.B * d.S);
     const int max_splits = (n + 63) / 64;
@@ -432,12 +472,18 @@ int decode_splits(const Dims &d)
 
 size_t decode_workspace_bytes(const Dims &d)
 {
-    if (shape_id(d) == 0) return 0;
+    if (!decode_supported(d)) return 0;
     return (size_t)d.B * d.S * decode_splits(d) * (d.H / d.S) * (d.d_pool + 2) * sizeof(float);
 }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t st)
 {
+    if (decode_mla_supported(a.d)) {     // matrix-core kernel at the MLA widths, then the common merge
+        const hipError_t e = launch_decode_mla(a, st);
+        if (e != hipSuccess) return e;
+        decode_merge_kernel<uint16_t><<<a.d.B * a.d.H, MERGE_THREADS, a.splits * sizeof(float), st>>>(a.part, (uint16_t *)a.O, a.d.H / a.d.S, a.d.d_pool, a.splits);
+        return hipGetLastError();
+    }
     switch (shape_id(a.d)) {
     case 101: return run_gqa<1>(a, st);
     case 102: return run_gqa<2>(a, st);

@@ -1,0 +1,282 @@
+// Decode step over a condensed cache at the MLA widths (d_c = 512, d_R = 64, bf16; section 4.3 of the paper,
+// decoding paragraph; absorbed form of section 3): the new token's query attends the m representatives and the
+// k raw tail rows, and the (up to 16) heads of a condensed set share every cache row.
+//
+// One cache row of 1152 bytes feeds 16 heads x (576 + 512) multiply-adds, about 30 flops per byte: at HBM speed
+// that is beyond the vector ALU, so the products run on the matrix cores with the heads as the 16 columns of
+// 16x16x32 MFMAs:
+//   S^T[key, head]  = K Q^T       A = 16 key rows from LDS (16-byte reads), B = Q^T in registers (18 k-steps)
+//   O^T[dv, head]  += V^T P^T     A = V^T through LDS transpose reads,       B = P^T = exp2(S^T - ref)
+// Every WAVEFRONT works alone on its own range of entries with its own 36.5 KB LDS buffer (no barriers): it
+// copies a tile of 32 entries with direct-to-LDS loads (32 latent rows of 1 KB at a 1040-byte stride, the RoPE
+// parts XOR-swizzled), waits for it, and uses it twice — all 576 columns as keys, the first 512 as values.  The
+// other wavefronts of the CU cover the wait.  S^T row m of a block of 16 comes from LDS row 4(m%4) + m/4, so that
+// the S^T accumulators already are the B fragments of the second product when the transpose reads of a 16-lane
+// block take rows 4 apart (conflict-free on the 1040-byte stride).  Softmax keeps one fixed reference per head
+// (taken at the first tile), so the 128 accumulation registers are never rescaled; if a row sum ends beyond
+// 2^100 the wavefront collects the exact maximum of its range and runs it again.  The wavefronts' partial
+// results (reference, sum, unnormalised output per head) are merged by decode_merge_kernel.
+#include "lca_internal.h"
+
+namespace lca {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int DP = 512, DS = 64, DQK = 576;
+constexpr int BN = 32;                          // entries per tile
+constexpr int RSB = 1040;                       // LDS row stride of the latent part: 1024 + 16
+constexpr int SEL_OFF = BN * RSB;               // RoPE part: 32 rows x 128 B, chunks swizzled by row & 7
+constexpr int BUF_BYTES = SEL_OFF + BN * DS * 2;   // 37 376 per wavefront
+constexpr int NKS = DQK / 32;                   // 18 k-steps of S^T
+constexpr int NDT = DP / 16;                    // 32 value tiles
+constexpr int PV_GROUP = 8;                     // value tiles whose V^T fragments are requested together
+constexpr float NEG_BIG = -1.0e30f;
+constexpr float LN2 = 0.6931471805599453f;
+
+struct DmParams {
+    const uint16_t *q, *pool_rep, *sel_rep, *pool_tail, *sel_tail;
+    float *part;
+    int S, hps, m, k, n_parts, m_cap, k_cap, k_start;
+    float scale_log2, bias_log2;
+};
+
+__device__ __forceinline__ unsigned lds_address(const char *p) { return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char *)p; }
+
+// Direct-to-LDS loads of 64 x 16 bytes (lane l -> LDS [lds_addr + 16 l, +16)); inline assembly so that the compiler
+// does not tie later LDS reads to them — the wavefront waits for its copies by hand (s_waitcnt vmcnt(0)).
+__device__ __forceinline__ void dma_row(unsigned voff, const void *base, unsigned lds_addr)      // uniform base + per-lane offset
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds_addr));
+}
+__device__ __forceinline__ void dma_lanes(const void *addr, unsigned lds_addr)                    // per-lane addresses
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(addr), "s"(lds_addr));
+}
+
+__global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
+{
+    __shared__ __attribute__((aligned(1024))) char bufs[4][BUF_BYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 15, q4 = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wg_per_bs = kp.n_parts / 4;
+    const int part = (blockIdx.x % wg_per_bs) * 4 + wave, bs = blockIdx.x / wg_per_bs;
+    const int b = bs / kp.S;
+    const int m = kp.m, n = kp.m + kp.k;
+    const int tiles_total = (n + BN - 1) / BN, tiles_per_part = (tiles_total + kp.n_parts - 1) / kp.n_parts;
+    const int t_lo = min(part * tiles_per_part, tiles_total), t_hi = min(t_lo + tiles_per_part, tiles_total);
+    const int e_hi = min(n, t_hi * BN);
+    char *buf = bufs[wave];
+    const unsigned buf_lds = lds_address(buf);
+
+    // source rows: entry e < m is representative e, else tail token e - m in ring row (k_start + e - m) mod k_cap
+    const uint16_t *prep = kp.pool_rep + (size_t)bs * kp.m_cap * DP, *srep = kp.sel_rep + (size_t)bs * kp.m_cap * DS;
+    const uint16_t *ptail = kp.pool_tail + (size_t)b * kp.k_cap * DP, *stail = kp.sel_tail + (size_t)b * kp.k_cap * DS;
+    auto ring_row = [&](int e) { const int t = kp.k_start + e - m; return t >= kp.k_cap ? t - kp.k_cap : t; };
+
+    // Q^T fragments: lane (col = head of the set, q4) holds q[head, 32 ks + 8 q4 .. +7]; columns past the set's heads are zero
+    bf16x8 qf[NKS];
+    {
+        const uint16_t *qp = kp.q + ((size_t)bs * kp.hps + min(col, kp.hps - 1)) * DQK + 8 * q4;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + 32 * ks);
+            if (col >= kp.hps) qf[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[ks]));   // loaded before the copies start (see the wait below)
+    }
+
+    // per-lane LDS offsets
+    const int krow = 4 * (col & 3) + (col >> 2);                            // LDS row behind S^T row `col` of a block of 16
+    const int k_off = krow * RSB + 16 * q4;                                 // + 16*blk*RSB + 64*ks
+    const int ksel_row = SEL_OFF + krow * (DS * 2);                         // + 16*blk*128, chunk c at slot c ^ (row & 7)
+    const int v_off = (4 * (col >> 2) + q4) * RSB + 8 * (col & 3);          // + 16*hh*RSB + 32*t: transpose read of 4 keys x 4 columns
+
+    floatx4 acc[NDT];
+    float m_ref = NEG_BIG, l_run = 0.f, m_seen = NEG_BIG;
+    const float c = kp.scale_log2;
+    typedef __attribute__((address_space(3))) bf16x4 *lds_b64_ptr;
+
+    // copy of tile tl into this wavefront's buffer, S^T = K Q^T for its two blocks of 16 entries, and the logits in base 2
+    // (scale, bias of the representatives, entries past the range hidden)
+    auto tile_logits = [&](int tl, float (&lg)[2][4]) {
+        const int e0 = tl * BN;
+        // 32 latent rows (one load each), RoPE parts of 8 rows per load; rows past the range repeat its last row
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                  // this wavefront's reads of the previous tile are done
+        const int e_last = e0 + BN - 1;
+        // the usual tile: 32 consecutive rows of one buffer (no end of range, no rep/tail seam, no wrap of the ring)
+        const bool in_rep = e_last < m, in_tail = e0 >= m && ring_row(e0) + BN <= kp.k_cap;
+        if (e_last < e_hi && (in_rep || in_tail)) {
+            const size_t row0 = in_rep ? e0 : ring_row(e0);
+            const char *pb0 = (const char *)((in_rep ? prep : ptail) + row0 * DP);
+            const char *sb0 = (const char *)((in_rep ? srep : stail) + row0 * DS);
+#pragma unroll
+            for (int r = 0; r < BN; ++r) dma_row(lane * 16, pb0 + r * (DP * 2), buf_lds + r * RSB);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = 8 * j + (lane >> 3);
+                dma_row(r * (DS * 2) + (((lane & 7) ^ (r & 7)) << 4), sb0, buf_lds + SEL_OFF + 8 * j * (DS * 2));
+            }
+        } else {
+#pragma unroll 4
+            for (int r = 0; r < BN; ++r) {
+                const int e = min(e0 + r, e_hi - 1);
+                const uint16_t *src = e < m ? prep + (size_t)e * DP : ptail + (size_t)ring_row(e) * DP;
+                dma_row(lane * 16, src, buf_lds + r * RSB);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = 8 * j + (lane >> 3);
+                const int e = min(e0 + r, e_hi - 1);
+                const uint16_t *src = (e < m ? srep + (size_t)e * DS : stail + (size_t)ring_row(e) * DS) + (((lane & 7) ^ (r & 7)) << 3);
+                dma_lanes(src, buf_lds + SEL_OFF + 8 * j * (DS * 2));
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                   // ... has landed (the other wavefronts of the CU cover the wait)
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            bf16x8 kf[NKS];
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                const char *p = ks < DP / 32 ? buf + k_off + blk * 16 * RSB + 64 * ks
+                                             : buf + ksel_row + blk * 16 * (DS * 2) + (((4 * (ks - DP / 32) + q4) ^ (krow & 7)) << 4);
+                kf[ks] = *reinterpret_cast<const bf16x8 *>(p);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            floatx4 sacc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[ks], sacc, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int e = e0 + blk * 16 + 4 * r + q4;                   // accumulator row 4 q4 + r sits in LDS row 4 r + q4
+                lg[blk][r] = e < e_hi ? fmaf(sacc[r], c, e < m ? kp.bias_log2 : 0.f) : -INFINITY;
+            }
+        }
+    };
+    auto head_max = [&](const float (&lg)[2][4]) {
+        float mx = NEG_BIG;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mx = fmaxf(mx, lg[blk][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        return fmaxf(mx, __shfl_xor(mx, 32, 64));
+    };
+
+    float l_tot = 0.f;
+    for (bool again = false;;) {                                            // normally one pass; a second one from the exact maxima
+#pragma unroll
+        for (int t = 0; t < NDT; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+        l_run = 0.f;
+        m_ref = again ? m_seen : NEG_BIG;
+        bool ref_missing = !again;
+
+        for (int tl = t_lo; tl < t_hi; ++tl) {
+            float lg[2][4];
+            tile_logits(tl, lg);
+            if (ref_missing) {                                              // the first tile fixes the reference
+                const float mx = head_max(lg);
+                m_ref = (m_ref == NEG_BIG) ? mx : m_ref;
+                ref_missing = __builtin_amdgcn_ballot_w64(m_ref == NEG_BIG) != 0;
+            }
+            // P^T in bf16 (B fragment: k-slot i < 4 is the key of block 0 register i, i >= 4 of block 1 register i-4) and its sum
+            bf16x8 pb;
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    pb[blk * 4 + r] = (__bf16)__builtin_amdgcn_exp2f(lg[blk][r] - m_ref);
+                    l_run += (float)pb[blk * 4 + r];                       // the rounded value, the one the second product sees
+                }
+            // O^T += V^T P^T: fragments of PV_GROUP value tiles requested together, one group ahead
+            bf16x4 vlo[2][PV_GROUP], vhi[2][PV_GROUP];
+            auto request = [&](int grp, int bsel) {
+#pragma unroll
+                for (int i = 0; i < PV_GROUP; ++i) {
+                    const char *vp = buf + v_off + 32 * (grp * PV_GROUP + i);
+                    vlo[bsel][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp));
+                    vhi[bsel][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp + 16 * RSB));
+                }
+            };
+            request(0, 0);
+#pragma unroll
+            for (int grp = 0; grp < NDT / PV_GROUP; ++grp) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (grp + 1 < NDT / PV_GROUP) request(grp + 1, (grp + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < PV_GROUP; ++i) {
+                    const bf16x8 a = __builtin_shufflevector(vlo[grp & 1][i], vhi[grp & 1][i], 0, 1, 2, 3, 4, 5, 6, 7);
+                    acc[grp * PV_GROUP + i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb, acc[grp * PV_GROUP + i], 0, 0, 0);
+                }
+            }
+        }
+
+        l_tot = l_run + __shfl_xor(l_run, 16, 64);
+        l_tot += __shfl_xor(l_tot, 32, 64);
+        if (again || __builtin_amdgcn_ballot_w64(!(l_tot <= 0x1p100f)) == 0) break;
+        // (wave-uniform) a head ran out of exponent headroom: exact maxima of the range, then the pass again
+        m_seen = NEG_BIG;
+        for (int tl = t_lo; tl < t_hi; ++tl) {
+            float lg[2][4];
+            tile_logits(tl, lg);
+            m_seen = fmaxf(m_seen, head_max(lg));
+        }
+        again = true;
+    }
+
+    // partial result of this wavefront: (reference, sum, unnormalised output) per head, natural-log units
+    if (col < kp.hps) {
+        float *dst = kp.part + (((size_t)bs * kp.n_parts + part) * kp.hps + col) * (DP + 2);
+        const bool any = t_lo < t_hi;
+        if (q4 == 0) {
+            dst[0] = any ? m_ref * LN2 : -INFINITY;
+            dst[1] = any ? l_tot : 0.f;
+        }
+#pragma unroll
+        for (int t = 0; t < NDT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dst[2 + 16 * t + 4 * q4 + r] = acc[t][r];
+    }
+}
+
+}  // namespace
+
+bool decode_mla_supported(const Dims &d)
+{
+    const int hps = d.H / d.S;
+    return d.dtype == LCA_BF16 && d.mode == LCA_MODE_MLA && d.d_pool == DP && d.d_sel == DS && hps <= 16 && d.scale > 0.f;
+}
+
+// partial results per (sequence, set): a multiple of 4 (one per wavefront), enough workgroups to fill the chip,
+// at least two tiles per wavefront where the cache is long enough
+int decode_mla_parts(const Dims &d)
+{
+    const int tiles = (d.m + d.k + BN - 1) / BN;
+    int wgs = (256 + d.B * d.S - 1) / (d.B * d.S);
+    const int max_wgs = (tiles + 7) / 8;
+    if (wgs > max_wgs) wgs = max_wgs;
+    if (wgs < 1) wgs = 1;
+    return 4 * wgs;
+}
+
+hipError_t launch_decode_mla(const DecodeArgs &a, hipStream_t st)
+{
+    const Dims &d = a.d;
+    DmParams kp;
+    kp.q = (const uint16_t *)a.q; kp.pool_rep = (const uint16_t *)a.pool_rep; kp.sel_rep = (const uint16_t *)a.sel_rep;
+    kp.pool_tail = (const uint16_t *)a.pool_tail; kp.sel_tail = (const uint16_t *)a.sel_tail; kp.part = a.part;
+    kp.S = d.S; kp.hps = d.H / d.S; kp.m = d.m; kp.k = d.k; kp.n_parts = a.splits;
+    kp.m_cap = a.m_cap; kp.k_cap = a.k_cap; kp.k_start = a.k_start;
+    kp.scale_log2 = d.scale * 1.4426950408889634f;
+    kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
+    decode_mla_kernel<<<d.B * d.S * (a.splits / 4), 256, 0, st>>>(kp);
+    return hipGetLastError();
+}
+
+}  // namespace lca

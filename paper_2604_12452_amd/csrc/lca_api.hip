@@ -232,7 +232,6 @@ lca_status lca_cache_update(const lca_desc *desc, const lca_cache_layout *layout
                             const void *sel_tail, void *pool_rep, void *sel_rep, int32_t *anchor_idx, void *workspace, size_t workspace_bytes_,
                             void *stream)
 {
-    (void)workspace; (void)workspace_bytes_;
     lca::Dims d;
     LCA_TRY(make_dims(desc, d));
     if (d.L < d.w + d.g || (d.L - d.w) % d.g != 0)
@@ -247,7 +246,9 @@ lca_status lca_cache_update(const lca_desc *desc, const lca_cache_layout *layout
     LCA_TRY(check_ptr(pool_rep, "pool_rep"));
     LCA_TRY(check_ptr(sel_rep, "sel_rep"));
     if (anchor_idx != nullptr && (reinterpret_cast<uintptr_t>(anchor_idx) & 3)) return fail(LCA_ERR_INVALID_ARG, "anchor_idx is not 4-byte aligned");
+    LCA_TRY(check_ws(d, workspace, workspace_bytes_));
     lca::UpdateArgs a;
+    a.qbar = static_cast<float *>(workspace);
     a.d = d; a.q_recent = q_recent; a.pool_tail = pool_tail; a.sel_tail = sel_tail; a.pool_rep = pool_rep; a.sel_rep = sel_rep;
     a.anchor = anchor_idx; a.m_cap = layout->m_cap; a.k_cap = layout->k_cap; a.k_start = layout->k_start;
     return hip_status(lca::launch_cache_update(a, static_cast<hipStream_t>(stream)), "lca_cache_update");

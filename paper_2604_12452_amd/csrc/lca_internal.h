@@ -51,11 +51,13 @@ struct UpdateArgs {
     const void *q_recent, *pool_tail, *sel_tail;
     void *pool_rep, *sel_rep;
     int32_t *anchor;
+    float *qbar;              // workspace, [B, S, d_qk] float
     int m_cap, k_cap, k_start;
 };
 
 // Launchers return hipSuccess or the launch error. They assume validated arguments.
 hipError_t launch_condense(const CondenseArgs &a, hipStream_t st);
+hipError_t launch_summary_query(const Dims &d, const void *Q, int L, float *qbar, hipStream_t st);
 hipError_t launch_attn_simple(const AttnArgs &a, hipStream_t st);
 bool attn_mla_supported(const Dims &d);
 hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st);
@@ -67,6 +69,9 @@ bool decode_supported(const Dims &d);
 int decode_splits(const Dims &d);
 size_t decode_workspace_bytes(const Dims &d);
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t st);
+bool decode_mla_supported(const Dims &d);
+int decode_mla_parts(const Dims &d);
+hipError_t launch_decode_mla(const DecodeArgs &a, hipStream_t st);
 hipError_t launch_cache_update(const UpdateArgs &a, hipStream_t st);
 
 }  // namespace lca
