@@ -132,6 +132,8 @@ def test_results_are_deterministic(oracle):
     (inputs.MODE_GQA, 128, 128, 8, 2, "bf16"),
     (inputs.MODE_GQA, 128, 128, 4, 4, "bf16"),
     (inputs.MODE_MLA, 512, 64, 16, 1, "bf16"),
+    (inputs.MODE_MLA, 512, 64, 16, 4, "bf16"),
+    (inputs.MODE_MLA, 512, 64, 8, 8, "bf16"),
     (inputs.MODE_MLA, 128, 32, 4, 1, "f32"),
 ])
 @pytest.mark.parametrize("L,g,w", [(1000, 16, 100), (77, 4, 9), (50, 16, 64)])
