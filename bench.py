@@ -218,6 +218,14 @@ def main():
     extra["kv_cache_bytes_dense"], extra["kv_cache_bytes_lca"] = dense_b, cond_b
     extra["kv_cache_saved_frac"] = 1.0 - cond_b / dense_b
 
+    # ---- per-token deviations of the emitted cache (Theorem 1's delta_k, delta_v; the statistic of the paper's Tables 9-10) ----
+    stats = torch.zeros((d.B, d.S, 6), dtype=torch.float32, device="cuda")
+    ms_dev = time_kernel(lambda: lca.deviation_stats(d, run.POOL, run.SEL, run.pool_rep, run.sel_rep, stats, run.ws), 5, 1)
+    st = stats.cpu().numpy().mean(axis=(0, 1))
+    extra["deviation"] = {"mean_dk": float(st[0]), "mean_dk_rel": float(st[1]), "max_dk": float(st[2]), "mean_dv": float(st[3]),
+                          "mean_dv_rel": float(st[4]), "max_dv": float(st[5]), "ms": ms_dev,
+                          "note": "synthetic AR(1) inputs, not model activations"}
+
     # ---- parity spot-check + CPU baseline on a bounded sample ----
     base, rows, O_ref, cref = cpu_baseline(wl, Q, POOL, SEL, args.oracle_rows)
     O_gpu = hp.from_dev(O[:, rows.tolist()], wl.dtype)

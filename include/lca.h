@@ -182,6 +182,21 @@ lca_status lca_cache_update(const lca_desc *desc, const lca_cache_layout *layout
                             const void *pool_tail, const void *sel_tail, void *pool_rep, void *sel_rep,
                             int32_t *anchor_idx, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Per-token deviations between the original keys / values and the representative standing for them:
+ * the delta_k, delta_v of the error bound (section 4.4, Theorem 1), measured as in the appendix on
+ * empirical per-token deviations (Tables 9-10).  For every condensed token i of group j (i < m*g):
+ *     dk_i = || key_i - key^rep_j ||_2,   dv_i = || value_i - value^rep_j ||_2,
+ * key = [pool ; sel] (MLA, the absorbed space attention works in) or sel (GQA), value = pool.
+ * In:  POOL, SEL, pool_rep, sel_rep as for lca_prefill_attn.
+ * Out: stats [B,S,6] float = mean dk, mean dk/||key_i||, max dk, mean dv, mean dv/||value_i||, max dv over
+ *      those tokens (a ratio with a zero denominator counts as 0; all zeros when m = 0).
+ * Deterministic: per-group sums go through the workspace and are added in a fixed order.
+ */
+lca_status lca_deviation_stats(const lca_desc *desc, const void *POOL, const void *SEL, const void *pool_rep,
+                               const void *sel_rep, float *stats, void *workspace, size_t workspace_bytes,
+                               void *stream);
+
 /* Message for the calling thread's last non-OK status; never NULL. */
 const char *lca_last_error(void);
 

@@ -227,6 +227,19 @@ def cache_update(d: Desc, q_recent, pool_old, sel_old):
                 alpha=c["alpha"], margin=c["margin"][:, :, 0])
 
 
+def deviation_stats(d: Desc, POOL, SEL, pool_rep, sel_rep) -> np.ndarray:
+    """Theorem 1's per-token deviations (appendix, Tables 9-10): [B,S,6] = mean dk, mean dk/||k||, max dk, mean dv,
+    mean dv/||v||, max dv over the condensed tokens, keys and values in the space attention works in."""
+    POOL = _f64(POOL, _kv_shape(d, d.d_pool))
+    SEL = _f64(SEL, _kv_shape(d, d.d_sel))
+    pool_rep = _f64(pool_rep, (d.B, d.S, d.m, d.d_pool))
+    sel_rep = _f64(sel_rep, (d.B, d.S, d.m, d.d_sel))
+    stats = np.zeros((d.B, d.S, 6), dtype=np.float64)
+    cd = d.c()
+    _check(_load().oracle_deviation_stats(ctypes.byref(cd), _p(POOL), _p(SEL), _p(pool_rep), _p(sel_rep), _p(stats)), "deviation_stats")
+    return stats
+
+
 def cache_bytes(d: Desc, elt_bytes: int):
     """(dense_bytes, condensed_bytes) of the KV cache for one attention layer."""
     a, b = ctypes.c_uint64(0), ctypes.c_uint64(0)

@@ -348,6 +348,45 @@ int oracle_decode_attn(const oracle_desc *d, const double *q, const double *pool
 }
 
 /*
+ * Per-token deviations between the original keys / values and the representative that stands for them
+ * (Theorem 1's delta_k, delta_v; measured in appendix "Empirical per-token deviations", Tables 9-10):
+ * for every condensed token i of group j (i < m*g),
+ *     dk_i = || key_i - key^rep_j ||_2,   dv_i = || value_i - value^rep_j ||_2,
+ * with key = [pool ; sel] (MLA, absorbed space) or sel (GQA) and value = pool.
+ * stats [B, S, 6] = mean dk, mean dk / ||key_i||, max dk, mean dv, mean dv / ||value_i||, max dv over those
+ * tokens (a ratio with a zero denominator counts as 0; all zeros when m = 0).
+ */
+int oracle_deviation_stats(const oracle_desc *d, const double *POOL, const double *SEL, const double *pool_rep,
+                           const double *sel_rep, double *stats)
+{
+    if (check_desc(d) || !POOL || !SEL || !stats) return ORACLE_BAD_ARG;
+    const int m = num_groups(d->L, d->w, d->g), g = d->g;
+    if (m > 0 && (!pool_rep || !sel_rep)) return ORACLE_BAD_ARG;
+    for (int b = 0; b < d->B; ++b)
+        for (int s = 0; s < d->S; ++s) {
+            const int p = kv_head_of_set(d, s);
+            double sum_dk = 0, sum_rk = 0, max_dk = 0, sum_dv = 0, sum_rv = 0, max_dv = 0;
+            for (int i = 0; i < m * g; ++i) {
+                const int j = i / g;
+                const double *pr = tok_row(POOL, d, b, i, p, d->d_pool), *sr = tok_row(SEL, d, b, i, p, d->d_sel);
+                const double *prr = pool_rep + (((size_t)b * d->S + s) * m + j) * d->d_pool;
+                const double *srr = sel_rep + (((size_t)b * d->S + s) * m + j) * d->d_sel;
+                double dp2 = 0, np2 = 0, ds2 = 0, ns2 = 0;
+                for (int x = 0; x < d->d_pool; ++x) { dp2 += (pr[x] - prr[x]) * (pr[x] - prr[x]); np2 += pr[x] * pr[x]; }
+                for (int x = 0; x < d->d_sel; ++x) { ds2 += (sr[x] - srr[x]) * (sr[x] - srr[x]); ns2 += sr[x] * sr[x]; }
+                const double dk = d->mode == 0 ? sqrt(dp2 + ds2) : sqrt(ds2), nk = d->mode == 0 ? sqrt(np2 + ns2) : sqrt(ns2);
+                const double dv = sqrt(dp2), nv = sqrt(np2);
+                sum_dk += dk; sum_rk += nk > 0 ? dk / nk : 0; if (dk > max_dk) max_dk = dk;
+                sum_dv += dv; sum_rv += nv > 0 ? dv / nv : 0; if (dv > max_dv) max_dv = dv;
+            }
+            double *o = stats + ((size_t)b * d->S + s) * 6;
+            const double n = m * g > 0 ? (double)(m * g) : 1.0;
+            o[0] = sum_dk / n; o[1] = sum_rk / n; o[2] = max_dk; o[3] = sum_dv / n; o[4] = sum_rv / n; o[5] = max_dv;
+        }
+    return ORACLE_OK;
+}
+
+/*
  * KV-cache footprint (section 4.3 decoding paragraph; appendix B): the dense cache holds one
  * (pool, sel) row per token and KV head; the condensed cache holds m representatives per set
  * plus the k raw tail tokens per KV head.

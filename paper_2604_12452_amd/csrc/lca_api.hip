@@ -60,8 +60,9 @@ size_t qbar_bytes(const lca::Dims &d) { return (((size_t)d.B * d.S * d.d_qk * si
 size_t workspace_bytes(const lca::Dims &d)
 {
     size_t need = qbar_bytes(d);
-    const size_t dec = lca::decode_workspace_bytes(d);
-    return need > dec ? need : dec;
+    const size_t dec = lca::decode_workspace_bytes(d), dev = lca::deviation_workspace_bytes(d);
+    need = need > dec ? need : dec;
+    return need > dev ? need : dev;
 }
 
 lca_status check_ptr(const void *p, const char *name, bool required = true)
@@ -252,6 +253,23 @@ lca_status lca_cache_update(const lca_desc *desc, const lca_cache_layout *layout
     a.d = d; a.q_recent = q_recent; a.pool_tail = pool_tail; a.sel_tail = sel_tail; a.pool_rep = pool_rep; a.sel_rep = sel_rep;
     a.anchor = anchor_idx; a.m_cap = layout->m_cap; a.k_cap = layout->k_cap; a.k_start = layout->k_start;
     return hip_status(lca::launch_cache_update(a, static_cast<hipStream_t>(stream)), "lca_cache_update");
+}
+
+lca_status lca_deviation_stats(const lca_desc *desc, const void *POOL, const void *SEL, const void *pool_rep, const void *sel_rep, float *stats,
+                               void *workspace, size_t workspace_bytes_, void *stream)
+{
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    LCA_TRY(check_ptr(POOL, "POOL"));
+    LCA_TRY(check_ptr(SEL, "SEL"));
+    LCA_TRY(check_ptr(pool_rep, "pool_rep", d.m > 0));
+    LCA_TRY(check_ptr(sel_rep, "sel_rep", d.m > 0));
+    if (stats == nullptr || (reinterpret_cast<uintptr_t>(stats) & 3)) return fail(LCA_ERR_INVALID_ARG, "stats is NULL or not 4-byte aligned");
+    LCA_TRY(check_ws(d, workspace, workspace_bytes_));
+    lca::DeviationArgs a;
+    a.d = d; a.POOL = POOL; a.SEL = SEL; a.pool_rep = pool_rep; a.sel_rep = sel_rep; a.stats = stats;
+    a.partial = static_cast<float *>(workspace);
+    return hip_status(lca::launch_deviation_stats(a, static_cast<hipStream_t>(stream)), "lca_deviation_stats");
 }
 
 }  // extern "C"

@@ -74,4 +74,13 @@ int decode_mla_parts(const Dims &d);
 hipError_t launch_decode_mla(const DecodeArgs &a, hipStream_t st);
 hipError_t launch_cache_update(const UpdateArgs &a, hipStream_t st);
 
+// Deviation statistics: per-group partial sums [B,S,m,6] in the workspace, then one reduction per (sequence, set).
+struct DeviationArgs {
+    Dims d;
+    const void *POOL, *SEL, *pool_rep, *sel_rep;
+    float *stats, *partial;
+};
+size_t deviation_workspace_bytes(const Dims &d);
+hipError_t launch_deviation_stats(const DeviationArgs &a, hipStream_t st);
+
 }  // namespace lca

@@ -20,7 +20,7 @@ BF16, F32 = 0, 1
 REDUCE_DEFAULT, REDUCE_WEIGHTED, REDUCE_MEAN, REDUCE_MAXSEL, REDUCE_MAXPOOL = range(5)
 
 EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condense", "lca_prefill_attn", "dense_mla_attn",
-           "lca_decode_attn", "lca_decode_attn_cached", "lca_cache_update", "lca_last_error")
+           "lca_decode_attn", "lca_decode_attn_cached", "lca_cache_update", "lca_deviation_stats", "lca_last_error")
 
 
 class LcaError(RuntimeError):
@@ -187,6 +187,12 @@ def cache_update(desc: Desc, layout: CacheLayout, q_recent, pool_tail, sel_tail,
     cd, cl = desc.c(), layout.c()
     _check(load().lca_cache_update(ctypes.byref(cd), ctypes.byref(cl), _ptr(q_recent), _ptr(pool_tail), _ptr(sel_tail), _ptr(pool_rep),
                                    _ptr(sel_rep), _ptr(anchor_idx), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
+
+
+def deviation_stats(desc: Desc, POOL, SEL, pool_rep, sel_rep, stats, workspace, stream=None):
+    cd = desc.c()
+    _check(load().lca_deviation_stats(ctypes.byref(cd), _ptr(POOL), _ptr(SEL), _ptr(pool_rep), _ptr(sel_rep), _ptr(stats), _ptr(workspace),
+                                      ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------

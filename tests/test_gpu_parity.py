@@ -270,3 +270,26 @@ def test_condense_reduce_strategies(oracle, dtype, mode, pool_reduce, sel_reduce
                         n2 = (grp * grp).sum(-1)
                         hits = [r for r in range(wl.g) if (got[b, s, j] == grp[r]).all()]
                         assert hits and n2[hits[0]] >= n2.max() * (1 - 1e-5), f"{name} component: not a row of largest norm"
+
+
+# ---- per-token deviation statistics (Theorem 1's delta_k, delta_v; appendix, Tables 9-10) --------------------
+@pytest.mark.parametrize("dtype,mode,d_pool,d_sel,L,g,w,S", [
+    ("f32", inputs.MODE_MLA, 24, 16, 333, 4, 10, 2), ("bf16", inputs.MODE_GQA, 128, 128, 700, 16, 100, 2),
+    ("bf16", inputs.MODE_MLA, 512, 64, 1200, 16, 64, 1), ("bf16", inputs.MODE_MLA, 24, 16, 40, 16, 64, 1)])
+def test_deviation_stats(oracle, dtype, mode, d_pool, d_sel, L, g, w, S):
+    """lca_deviation_stats on the cache lca_condense emitted against the oracle on the same (rounded) cache."""
+    import torch
+    from paper_2604_12452_amd import lca
+    wl = _wl("deviation", L=L, g=g, w=w, H=4, S=S, dtype=dtype, mode=mode, d_pool=d_pool, d_sel=d_sel, B=2)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense(alpha=False)
+    stats = torch.full((wl.B, wl.S, 6), float("nan"), dtype=torch.float32, device="cuda")
+    lca.deviation_stats(run.desc, run.POOL, run.SEL, run.pool_rep, run.sel_rep, stats, run.ws)
+    torch.cuda.synchronize()
+    od = hp.oracle_desc(oracle, wl)
+    ref = oracle.deviation_stats(od, inputs.to_f64(POOL, dtype), inputs.to_f64(SEL, dtype), hp.from_dev(run.pool_rep, dtype),
+                                 hp.from_dev(run.sel_rep, dtype))
+    got = stats.cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(got, ref, rtol=2e-5, atol=1e-7)      # fp32 sums of at most a few thousand terms against fp64
+    if od.m == 0:
+        assert (got == 0).all()
