@@ -86,3 +86,15 @@ def test_null_misaligned_and_small_workspace_are_rejected_before_launch(lib):
     und = lca.Desc(B=1, L=100, H=3, S=1, d_pool=64, d_sel=64, g=4, w=4).c()    # no decode kernel for this shape
     assert lib.lca_decode_attn(ctypes.byref(und), vp(A), vp(A), vp(A), vp(A), vp(A), vp(A), vp(A), sz(1 << 20), vp(0)) == lca.ERR_UNSUPPORTED
     assert lib.lca_workspace_size(None, None) == lca.ERR_INVALID_ARG
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/lca.h must be usable from C (no C++-only constructs): gcc -std=c99 -pedantic compiles a translation unit
+    that includes it and takes the address of every declared entry point."""
+    import subprocess
+    names = _declared()
+    src = tmp_path / "use_lca.c"
+    src.write_text('#include "lca.h"\n' + "void *table[] = {" + ", ".join(f"(void *){n}" for n in names) + "};\n"
+                   "int main(void) { lca_desc d; lca_cache_layout l; (void)d; (void)l; return sizeof(table) ? 0 : 1; }\n")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-Wno-pedantic", "-I", os.path.join(ROOT, "include"), "-c", str(src),
+                    "-o", str(tmp_path / "use_lca.o")], check=True)
