@@ -4,7 +4,7 @@
 //
 // One workgroup = 4 wavefronts = 128 query rows of one (sequence, head); each wavefront owns 32 rows
 // and the whole 512-wide output, one wavefront per SIMD with the full 512-register budget:
-//   Q^T fragments   144 VGPRs (held for the whole kernel)
+//   Q^T fragments   144 VGPRs (held for a whole work item)
 //   O^T accumulator 256 AGPRs (16 tiles of 32 value columns x 32 queries)
 // Key tiles of 32 entries x 576 columns are copied global -> LDS by direct-to-LDS loads into four
 // 36.5 KB stages; copies run three tiles ahead of their use.  A stage holds the latent part as 32 rows
@@ -13,7 +13,7 @@
 // permutation inside each half of 16 rows (pi(8h + 4G + j) = 4j + 2h + G): with it both the
 // row-strided 16-byte key reads (16 lanes = 16 rows that differ mod 16) and the transpose reads of the
 // value operand (each 16-lane block touches 4 rows that are 4 apart) spread over all 64 banks.  A tile is used
-// twice from LDS: all 576 columns as keys, the first 512 as values — the absorbed MLA form needs no
+// twice from LDS: all 576 columns as keys, the first 512 as values -- the absorbed MLA form needs no
 // separate value tile.
 //
 // Products are computed transposed so that nothing changes lanes between the two MFMA stages:
@@ -23,15 +23,20 @@
 // and the S^T registers already are the B fragments of the second product when the V^T operand
 // enumerates keys in accumulator order.
 //
-// Software pipeline: while the matrix core runs the S^T chain of tile t+1, the vector ALU turns the
-// S^T of tile t into P^T (its instructions are placed between the MFMAs of the chain); then the O^T
-// update of tile t runs.  One workgroup barrier per tile.
+// With one wavefront per SIMD every instruction the wavefront issues costs about five cycles of its
+// time (nine for an exponential), and an MFMA occupies the matrix core for 32: the loop is written so
+// that each MFMA is followed by at most five or six other instructions.  Software pipeline, one workgroup
+// barrier per tile: after the barrier of iteration t the wavefront requests the first key fragments of
+// tile t+1 and meanwhile runs the last four MFMAs of the O^T update of tile t-1 (their V^T fragments are
+// already in registers); then the S^T chain of tile t+1 (36 MFMAs) with the softmax of tile t between
+// its MFMAs and the copy of tile t+3 in its last slots; then the O^T update of tile t (28 MFMAs), whose
+// free issue slots take the loop's scalar bookkeeping for iteration t+1, a few instructions per MFMA.
 //
-// Softmax reference: each query row fixes its reference maximum at the first key tile it sees and keeps
-// it; numerator and denominator use the same reference, so the result does not depend on it, and O^T is
-// never rescaled (no vector arithmetic ever touches the 256 accumulation registers inside the loop).
-// Exponents are safe while later logits stay within 2^60 of that reference; if one does not, the
-// workgroup repeats its pass once with the row maxima it has by then seen as references.
+// Softmax reference: each query row fixes its reference at the first entries it sees and never looks at
+// maxima again; numerator and denominator use the same reference, so the result does not depend on it,
+// and O^T is never rescaled (no vector arithmetic touches the 256 accumulation registers inside the
+// loop).  If a row sum ends beyond 2^90 (or not finite) the workgroup finds every row's exact maximum in
+// a pass of S^T chains alone and runs the item again from those.
 #include "lca_internal.h"
 
 namespace lca {
@@ -39,7 +44,11 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+union Pb { bf16x8 v[2]; bf16x2 p[8]; };     // P^T of one tile: the B operands of the two k-steps of the second product
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef int int4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) const char *lds_cptr;
 
 #define LCA_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -59,7 +68,7 @@ constexpr int NDV = DV / 32;            // 16 value tiles
 constexpr int CHAIN_DEPTH = LCA_CHAIN_DEPTH;   // key fragments in flight ahead of the S^T chain
 constexpr int MLA_GRID = 256;            // workgroups of the persistent kernel = CUs of the chip
 constexpr float NEG_BIG = -1.0e30f;     // stands for -inf in running maxima (keeps exp2 arguments finite)
-constexpr float HEADROOM = 60.0f;       // base-2 exponent headroom above the reference before a pass is repeated
+constexpr float L_LIMIT = 0x1p90f;      // a row sum beyond this (or not finite) makes the workgroup repeat the item from exact maxima
 
 struct MlaParams {
     const uint16_t *Q, *POOL, *SEL, *pool_rep, *sel_rep;
@@ -72,16 +81,15 @@ struct MlaParams {
 // Accumulator register r of lane group G (lanes 32G..32G+31) of a 32x32 tile holds S^T row
 // m = 8*(r/4) + 4G + r%4.  S^T row m is computed from LDS row (= tile entry) pi(m): inside each half of 16,
 // pi(8h + 4G + j) = 4j + 2h + G.
-__device__ __forceinline__ int lds_row_of_m(int m) { return (m & 16) + 4 * (m & 3) + 2 * ((m >> 3) & 1) + ((m >> 2) & 1); }
-__device__ __forceinline__ int acc_entry(int r, int G) { return lds_row_of_m(8 * (r >> 2) + 4 * G + (r & 3)); }
+__device__ __forceinline__ constexpr int lds_row_of_m(int m) { return (m & 16) + 4 * (m & 3) + 2 * ((m >> 3) & 1) + ((m >> 2) & 1); }
+__device__ __forceinline__ constexpr int acc_entry(int r, int G) { return lds_row_of_m(8 * (r >> 2) + 4 * G + (r & 3)); }
 
-// per-lane softmax state (base-2 logits): reference, running sum over this lane's keys, largest seen
+// per-lane softmax state (base-2 logits): reference and running sum over this lane's keys
 struct RowState {
-    float m_ref, l_run, m_seen;
-    bool exceeded;
+    float m_ref, l_run;
 };
 
-// Fragments of the V^T operand: two groups of PV_GROUP steps (double-buffered bursts of transpose reads).
+// Fragments of the V^T operand: a ring of 2*PV_GROUP steps, requested PV_GROUP steps ahead of their use.
 // Step j of the O^T update = (value tile j/2, k-step j%2).
 #ifndef LCA_PV_GROUP
 #define LCA_PV_GROUP 4
@@ -90,185 +98,186 @@ constexpr int PV_GROUP = LCA_PV_GROUP;
 struct PvFrags {
     bf16x4 lo[2][PV_GROUP], hi[2][PV_GROUP];
 };
-__device__ __forceinline__ void pv_load_group(PvFrags &f, const char *vp0, int grp, int buf)
+// Requests the V^T fragment of step j into its ring slot (steps j and j + 2*PV_GROUP share one).
+__device__ __forceinline__ void pv_load_step(PvFrags &f, lds_cptr vp0, int j)
 {
     typedef __attribute__((address_space(3))) bf16x4 *lds_b64_ptr;
-#pragma unroll
-    for (int i = 0; i < PV_GROUP; ++i) {
-        const int j = grp * PV_GROUP + i;
-        if (j < 2 * NDV) {
-            // k-slots i = 4h + j of this step hold keys pi(16kk + 8h + 4G + j) = 16kk + 4j + 2h + G: the lanes of a
-            // 16-lane block address rows 4j + G (j = lane bits 2..3, part of vp0); h = 0 / 1 adds two rows
-            const char *vp = vp0 + (j & 1) * 16 * RSB + (j >> 1) * 64;
-            f.lo[buf][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp));
-            f.hi[buf][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp + 2 * RSB));
-        }
-    }
+    const int buf = (j / PV_GROUP) & 1, i = j % PV_GROUP;
+    // k-slots i = 4h + j of this step hold keys pi(16kk + 8h + 4G + j) = 16kk + 4j + 2h + G: the lanes of a
+    // 16-lane block address rows 4j + G (j = lane bits 2..3, part of vp0); h = 0 / 1 adds two rows
+    lds_cptr vp = vp0 + (j & 1) * 16 * RSB + (j >> 1) * 64;
+    f.lo[buf][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp));
+    f.hi[buf][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp + 2 * RSB));
 }
 
-// What one wavefront needs to copy its share of a key tile.
-struct CopyDesc {
-    int e0, last;                 // first entry of the tile, last valid entry of the segment
+// Tile copies go through raw buffer descriptors (base, size in bytes) so that rows past the end of a segment
+// need no clamping: the hardware range check turns them into zeros (such entries are masked anyway).
+struct Seg {
+    unsigned lo, hi, bytes;       // descriptor words 0..2: address bits 0..31, bits 32..47 (stride 0), size
 };
-// The same for one wavefront, in the form the copies use: its first row and how far its rows may go.
-struct WaveCopy {
-    const uint16_t *pool0, *sel0;     // the wavefront's first row of the latent / RoPE part: entry min(e0 + 8*wave, last)
-    int dmax;                         // rows 0..dmax after that one exist (>= 0); later ones are clamped to row dmax
-};
-
-// One direct-to-LDS load of 64 x 16 bytes: lane l fetches global bytes [base + voff, +16) into LDS bytes
-// [lds_addr + 16 l, +16).  Written as inline assembly on purpose: the compiler makes every LDS read that
-// follows a direct-to-LDS load it knows about wait for that load, and here the copy must stay in flight
-// for two more tiles.  Ordering is kept by hand instead: s_waitcnt vmcnt + workgroup barrier in the tile
-// loop before a stage is read, 9 loads per tile and wavefront.
-__device__ __forceinline__ void dma_1k(unsigned voff, const void *base, unsigned lds_addr)
+__device__ __forceinline__ Seg make_seg(const void *p, long bytes)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds_addr));   // writes M0, which no compiler-generated instruction of this kernel uses
+    const unsigned long long a = (unsigned long long)p;
+    return Seg{(unsigned)a, (unsigned)(a >> 32) & 0xFFFFu, (unsigned)bytes};
+}
+constexpr int RSRC_WORD3 = 0x00020000;   // raw buffer of dwords, gfx9 layout
+
+// What one wavefront needs to copy its 8 rows of one key tile into one stage (all wavefront-uniform).
+struct CopyCtl {
+    int4v pool_rs, sel_rs;               // descriptors of the latent / RoPE part of the tile's segment
+    unsigned soff_lo, soff_hi, soff_sel; // byte offsets of the wavefront's rows 0 and 4 (latent) and row 0 (RoPE) in the segment
+    unsigned m0_pool, m0_sel;            // LDS addresses of the wavefront's first row in the stage
+};
+
+// One direct-to-LDS load of 64 x 16 bytes: lane l fetches segment bytes [soff + IMM + voff, +16) into LDS bytes
+// [m0 + IMM + 16 l, +16) (the instruction offset moves both sides).  Inline assembly on purpose: the compiler
+// makes every LDS read that follows a direct-to-LDS load it knows about wait for that load, and here the
+// copy must stay in flight for two more tiles.  Ordering is kept by hand instead: s_waitcnt vmcnt + workgroup
+// barrier in the tile loop before a stage is read, 9 loads per tile and wavefront.
+template <int M0_ADD, int IMM>
+__device__ __forceinline__ void dma_1k(unsigned voff, const int4v &rs, unsigned soff, unsigned m0_base)
+{
+    asm volatile("s_add_u32 m0, %2, %4\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %3 offen offset:%5 lds"
+                 : : "v"(voff), "s"(rs), "s"(m0_base), "s"(soff), "n"(M0_ADD), "n"(IMM) : "scc", "memory");   // writes M0, which no compiler-generated instruction of this kernel uses
 }
 
-__device__ __forceinline__ unsigned lds_address(const char *p)
+__device__ __forceinline__ unsigned lds_address(const void *p)
 {
     return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char *)p;
 }
 
-// `pool` / `sel` = first row of the segment (representatives or raw tokens).
-// One of the 9 copies a wavefront makes per tile: j < 8 moves latent row 8*wave + j (1 KB), j == 8 moves the
-// RoPE parts of rows 8*wave .. 8*wave+7 (1 KB; lane l fills slot l&7 of local row l>>3 with the chunk
-// sel_chunk that the swizzle assigns to that slot).  Rows past the end of the segment are clamped here and
-// masked later.
-__device__ __forceinline__ WaveCopy wave_copy(const uint16_t *pool, const uint16_t *sel, const CopyDesc &cd, int wave)
+// One of the 9 copies a wavefront makes per tile: J < 8 moves latent row 8*wave + J (1 KB; LDS rows are RSB
+// apart, the instruction offset (J%4) KB already moves the LDS side by as much), J == 8 moves the RoPE parts
+// of rows 8*wave .. 8*wave+7 (1 KB; lane l fills slot l&7 of local row l>>3 with the chunk the swizzle assigns
+// to that slot: voff_sel = (l>>3)*128 + chunk*16).
+template <int J>
+__device__ __forceinline__ void issue_copy_part(const CopyCtl &c, unsigned voff_pool, unsigned voff_sel)
 {
-    WaveCopy wc;
-    const int first = cd.e0 + 8 * wave, r0 = min(first, cd.last);     // 0 <= r0 <= last: the base row always exists
-    wc.pool0 = pool + (long)r0 * DP;
-    wc.sel0 = sel + (long)r0 * DS;
-    wc.dmax = max(cd.last - first, 0);                                // all eight rows past the segment: every one reads row `last`
-    return wc;
+    if constexpr (J < 4) dma_1k<J * RSB - J * 1024, J * 1024>(voff_pool, c.pool_rs, c.soff_lo, c.m0_pool);
+    else if constexpr (J < 8) dma_1k<J * RSB - (J - 4) * 1024, (J - 4) * 1024>(voff_pool, c.pool_rs, c.soff_hi, c.m0_pool);
+    else dma_1k<0, 0>(voff_sel, c.sel_rs, c.soff_sel, c.m0_sel);
 }
-
-// The row offset (0 .. 7 KB; the hardware takes the per-lane offset as unsigned, so it must never be negative)
-// travels in the per-lane address offset, so that a row costs a scalar min and shift and one vector add
-// instead of 64-bit scalar address arithmetic.
-__device__ __forceinline__ void issue_copy_part(int j, const char *stage, const WaveCopy &wc, int wave, int lane, int sel_chunk)
+template <int J>
+__device__ __forceinline__ void issue_copy_from(const CopyCtl &c, unsigned voff_pool, unsigned voff_sel)
 {
-    if (j < 8) {
-        const int d = min(j, wc.dmax);
-        dma_1k(lane * 16 + d * (DP * 2), wc.pool0, lds_address(stage) + (8 * wave + j) * RSB);
-    } else {
-        const int d = min(lane >> 3, wc.dmax);
-        dma_1k(d * (DS * 2) + sel_chunk * 16, wc.sel0, lds_address(stage) + SEL_OFF + 8 * wave * (DS * 2));
+    if constexpr (J < COPIES_PER_TILE) {
+        issue_copy_part<J>(c, voff_pool, voff_sel);
+        issue_copy_from<J + 1>(c, voff_pool, voff_sel);
     }
 }
 
-__device__ __forceinline__ void issue_copy(const char *stage, const uint16_t *pool, const uint16_t *sel, const CopyDesc &cd, int wave, int lane,
-                                           int sel_chunk)
+__device__ __forceinline__ void issue_copy_part_dyn(int j, const CopyCtl &c, unsigned voff_pool, unsigned voff_sel)
 {
-    const WaveCopy wc = wave_copy(pool, sel, cd, wave);
-#pragma unroll
-    for (int j = 0; j < COPIES_PER_TILE; ++j) issue_copy_part(j, stage, wc, wave, lane, sel_chunk);
+    switch (j) {      // j is a constant after unrolling
+    case 0: issue_copy_part<0>(c, voff_pool, voff_sel); break;
+    case 1: issue_copy_part<1>(c, voff_pool, voff_sel); break;
+    case 2: issue_copy_part<2>(c, voff_pool, voff_sel); break;
+    case 3: issue_copy_part<3>(c, voff_pool, voff_sel); break;
+    case 4: issue_copy_part<4>(c, voff_pool, voff_sel); break;
+    case 5: issue_copy_part<5>(c, voff_pool, voff_sel); break;
+    case 6: issue_copy_part<6>(c, voff_pool, voff_sel); break;
+    case 7: issue_copy_part<7>(c, voff_pool, voff_sel); break;
+    default: issue_copy_part<8>(c, voff_pool, voff_sel); break;
+    }
 }
 
 // S^T chain of one tile (36 MFMAs into `snext`, key fragments prefetched CHAIN_DEPTH deep) and, when SOFTMAX,
 // the vector work that turns the previous tile's S^T (`scur`) into P^T fragments, spread over the
-// chain's issue slots.  `kb` = LDS address of this lane's first key fragment of the chain's tile.
+// chain's issue slots.  `kb` / `kb_sel` = LDS addresses of this lane's first key fragment of the chain's tile.
 // The MFMAs are inline assembly so that their accumulator is an ordinary vector register tuple (all 256
 // accumulation registers belong to O^T); the wait states an MFMA result needs before vector
 // instructions read it are spent explicitly at the end of the chain.
-// When PV_PREFETCH, the copy of a later tile and the first burst of V^T reads of the O^T update that follows are
-// issued in the last slots of the chain, and the explicit wait states are left out: the caller keeps every reader of the chain's
-// result behind the whole O^T update (see tile_step).
-template <bool CHAIN, bool SOFTMAX, bool PV_PREFETCH>
-__device__ __forceinline__ void chain_and_softmax(const char *kb, const char *kb_sel, int x6, const bf16x8 (&qf)[NKS], floatx16 &snext,
-                                                  const floatx16 &scur, bf16x8 (&pb)[2], RowState &st, float c, float bias, PvFrags &pvf,
-                                                  const char *vp0, const char *dma_stage, const WaveCopy &wc, int wave, int lane, int sel_chunk)
+// When PIPELINED, the first key fragments were requested by the caller (chain_prefetch), the copy of a later tile
+// and the first burst of V^T reads of the O^T update that follows are issued in the last slots of the chain, and
+// the explicit wait states are left out: the caller keeps every reader of the chain's result behind MFMAs of
+// the O^T update.
+struct ChainFrags { bf16x8 fr[CHAIN_DEPTH]; };
+__device__ __forceinline__ bf16x8 chain_frag(lds_cptr kb, lds_cptr kb_sel, int x6, int ks)
 {
     // key fragment of k-step ks: latent columns from the row-strided part, RoPE columns (ks >= 32) from the swizzled part
-    auto frag = [&](int ks) {
-        const char *p = ks < DP / 16 ? kb + ks * 32 : kb_sel + ((x6 ^ (2 * (ks - DP / 16))) << 4);
-        return *reinterpret_cast<const bf16x8 *>(p);
-    };
-    bf16x8 fr[CHAIN_DEPTH];
-    if (CHAIN) {
+    lds_cptr p = ks < DP / 16 ? kb + ks * 32 : kb_sel + ((x6 ^ (2 * (ks - DP / 16))) << 4);
+    return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8 *>(p);
+}
+__device__ __forceinline__ void chain_prefetch(ChainFrags &cf, lds_cptr kb, lds_cptr kb_sel, int x6)
+{
 #pragma unroll
-        for (int i = 0; i < CHAIN_DEPTH; ++i) fr[i] = frag(i);
-    }
-    float mx[6], nb = 0.f, p[16];
+    for (int i = 0; i < CHAIN_DEPTH; ++i) cf.fr[i] = chain_frag(kb, kb_sel, x6, i);
+}
+template <bool SOFTMAX, bool PIPELINED>
+__device__ __forceinline__ void chain_and_softmax(ChainFrags &cf, lds_cptr kb, lds_cptr kb_sel, int x6, const bf16x8 (&qf)[NKS], floatx16 &snext,
+                                                  const floatx16 &scur, Pb &pb, RowState &st, float c, float bias, PvFrags &pvf,
+                                                  lds_cptr vp0, const CopyCtl &cc, unsigned voff_pool, unsigned voff_sel)
+{
+    float nb = 0.f, pf[2];
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
         LCA_FENCE();
-        if (CHAIN) {
-            if (ks == 0)
-                asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(snext) : "v"(fr[0]), "v"(qf[0]));
-            else
-                asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(snext) : "v"(fr[ks % CHAIN_DEPTH]), "v"(qf[ks]));
-            if (ks + CHAIN_DEPTH < NKS) fr[ks % CHAIN_DEPTH] = frag(ks + CHAIN_DEPTH);
-        }
+        if (ks == 0)
+            asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(snext) : "v"(cf.fr[0]), "v"(qf[0]));
+        else
+            asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(snext) : "v"(cf.fr[ks % CHAIN_DEPTH]), "v"(qf[ks]));
+        if (ks + CHAIN_DEPTH < NKS) cf.fr[ks % CHAIN_DEPTH] = chain_frag(kb, kb_sel, x6, ks + CHAIN_DEPTH);
         if (SOFTMAX) {
-            // slots 0..4: maxima of triples; 5..7: reduce and scale; 8: partner lane; 9: reference; 10..25: exponentials
-            if (ks < 5) mx[ks] = fmaxf(fmaxf(scur[3 * ks], scur[3 * ks + 1]), scur[3 * ks + 2]);
-            if (ks == 5) mx[5] = fmaxf(fmaxf(mx[0], mx[1]), mx[2]);
-            if (ks == 6) mx[0] = fmaxf(fmaxf(mx[3], mx[4]), scur[15]);
-            if (ks == 7) mx[0] = fmaxf(fmaf(fmaxf(mx[5], mx[0]), c, bias), NEG_BIG);
-            if (ks == 8) mx[0] = fmaxf(mx[0], __shfl_xor(mx[0], 32, 64));
-            if (ks == 9) {
-                st.m_ref = (st.m_ref == NEG_BIG) ? mx[0] : st.m_ref;     // first visible keys of this row fix its reference
-                st.m_seen = fmaxf(st.m_seen, mx[0]);
-                st.exceeded |= mx[0] > st.m_ref + HEADROOM;
-                nb = bias - st.m_ref;
-            }
-            if (ks >= 10 && ks < 26) {
-                const int r = ks - 10;
-                p[r] = __builtin_amdgcn_exp2f(fmaf(scur[r], c, nb));
-                st.l_run += p[r];
-                if (r & 1) {
-                    pb[r >> 3][(r & 7) - 1] = (__bf16)p[r - 1];
-                    pb[r >> 3][r & 7] = (__bf16)p[r];
+            // P^T = exp2(S^T * c + bias - reference), two S^T registers per three slots: an exponential in each of two
+            // slots, then the pair is added to the row sum and rounded to bf16.  No maxima here: the reference was
+            // fixed when the row saw its first entries.  A row that has seen nothing yet has reference -1e30 and
+            // only -inf logits: exact zeros.
+            if (ks == 0) nb = bias - st.m_ref;
+            if (ks < 24) {
+                const int k = ks / 3, sub = ks % 3;
+                if (sub < 2) pf[sub] = __builtin_amdgcn_exp2f(fmaf(scur[2 * k + sub], c, nb));
+                else {
+                    const bf16x2 pr = {(__bf16)pf[0], (__bf16)pf[1]};
+                    pb.p[k] = pr;
+                    st.l_run += pf[0];       // (two plain additions: v_dot2c_f32_bf16 stalls next to MFMAs, about 25 cycles each)
+                    st.l_run += pf[1];
                 }
             }
         }
         // the copy of the tile three steps ahead rides in the chain's last slots, after the softmax work
-        if (PV_PREFETCH && ks >= 26 && ks - 26 < COPIES_PER_TILE) issue_copy_part(ks - 26, dma_stage, wc, wave, lane, sel_chunk);
-        if (PV_PREFETCH && ks == 35) pv_load_group(pvf, vp0, 0, 0);
+        if (PIPELINED && ks >= 24 && ks - 24 < COPIES_PER_TILE) issue_copy_part_dyn(ks - 24, cc, voff_pool, voff_sel);
+        // the V^T fragments of the first steps of the O^T update that follows
+        if (PIPELINED && ks >= NKS - PV_GROUP) pv_load_step(pvf, vp0, ks - (NKS - PV_GROUP));
     }
     LCA_FENCE();
-    if (CHAIN && !PV_PREFETCH) asm("s_nop 15\n\ts_nop 7" : "+v"(snext));
+    if (!PIPELINED) asm("s_nop 15\n\ts_nop 7" : "+v"(snext));
 }
 
-// O^T += V^T P^T for one tile; vp0 = this lane's transpose-read address in the tile's stage; group 0 of the
-// V^T fragments is already on its way.  The compiler only ever waits for ALL outstanding transpose reads, so
-// the reads of the next group go out in one burst right after the first MFMA of the current group and have
-// the rest of the group's MFMAs to land.
-__device__ __forceinline__ void pv_update(PvFrags &f, const char *vp0, const bf16x8 (&pb)[2], floatx16 (&acc)[NDV])
+constexpr int PV_STEPS = 2 * NDV;                 // 32 MFMAs of the O^T update of one tile
+constexpr int PV_TAIL = PV_GROUP;                 // the last group is held back: it runs after the next barrier
+constexpr int PV_NGROUPS = PV_STEPS / PV_GROUP;
+static_assert((PV_NGROUPS & 1) == 0, "the held-back group must sit in buffer 1");
+
+// O^T += V^T P^T for one tile, all but the last group of steps; vp0 = this lane's transpose-read address in the
+// tile's stage; the V^T fragments of the first PV_GROUP steps are already on their way, every step requests the
+// fragment of the step PV_GROUP later.  `shadow(j)` is work for the issue slots that the MFMAs leave free.  The
+// last group's fragments are left in buffer 1 for pv_tail.
+template <class Shadow>
+__device__ __forceinline__ void pv_update(PvFrags &f, lds_cptr vp0, const Pb &pb, floatx16 (&acc)[NDV], Shadow shadow)
 {
-    constexpr int NSTEP = 2 * NDV;
 #pragma unroll
-    for (int j = 0; j < NSTEP; ++j) {
+    for (int j = 0; j < PV_STEPS - PV_TAIL; ++j) {
         const int grp = j / PV_GROUP, i = j % PV_GROUP, buf = grp & 1;
         LCA_FENCE();
         const bf16x8 a = __builtin_shufflevector(f.lo[buf][i], f.hi[buf][i], 0, 1, 2, 3, 4, 5, 6, 7);
-        acc[j >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[j & 1], acc[j >> 1], 0, 0, 0);
-        if (i == 0 && (grp + 1) * PV_GROUP < NSTEP) {
-            LCA_FENCE();
-            pv_load_group(f, vp0, grp + 1, buf ^ 1);
-        }
+        acc[j >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb.v[j & 1], acc[j >> 1], 0, 0, 0);
+        pv_load_step(f, vp0, j + PV_GROUP);
+        LCA_FENCE();
+        shadow(j);
     }
     LCA_FENCE();
 }
-
-// One pipeline step: copy of tile t+3 (into dma_stage), S^T chain of tile t+1 with the softmax of tile t in
-// its shadow, O^T update of tile t.
-__device__ __forceinline__ void tile_step(const char *dma_stage, const char *chain_stage, const char *pv_stage, const WaveCopy &wc, int wave,
-                                          int lane, int sel_chunk, int k_off, int ksel_off,
-                                          int x6, int v_off, const bf16x8 (&qf)[NKS], floatx16 &snext, const floatx16 &scur, bf16x8 (&pb)[2],
-                                          RowState &st, float c, float bias, floatx16 (&acc)[NDV])
+// The held-back steps of the previous tile's O^T update: their fragments are in registers, so they run while
+// the first key fragments of the next S^T chain travel from LDS.
+__device__ __forceinline__ void pv_tail(const PvFrags &f, const Pb &pb, floatx16 (&acc)[NDV])
 {
-    PvFrags pvf;
-    chain_and_softmax<true, true, true>(chain_stage + k_off, chain_stage + ksel_off, x6, qf, snext, scur, pb, st, c, bias, pvf, pv_stage + v_off,
-                                        dma_stage, wc, wave, lane, sel_chunk);
-    pv_update(pvf, pv_stage + v_off, pb, acc);
-    // Anchor: nothing may read the chain's result before this point (the compiler takes an inline-assembly
-    // result as ready at once; the 32 MFMAs of the O^T update are the wait states it actually needs).
-    asm("" : "+v"(snext));
+#pragma unroll
+    for (int j = PV_STEPS - PV_TAIL; j < PV_STEPS; ++j) {
+        const int i = j % PV_GROUP;
+        LCA_FENCE();
+        const bf16x8 a = __builtin_shufflevector(f.lo[1][i], f.hi[1][i], 0, 1, 2, 3, 4, 5, 6, 7);
+        acc[j >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb.v[j & 1], acc[j >> 1], 0, 0, 0);
+    }
     LCA_FENCE();
 }
 
@@ -279,7 +288,7 @@ struct Blk {
     int raw_lo_blk, mt_blk_hi;               // first raw token / representatives any row of the block sees
     int n_rep_tiles, n_tiles;
     int rep_full_end, raw_full_lo, raw_full_hi;   // tiles this wavefront sees completely (no masking)
-    const uint16_t *rep_pool, *rep_sel, *raw_pool, *raw_sel;
+    Seg rep_pool, rep_sel, raw_pool, raw_sel;     // the two segments: visible representatives, raw tokens 0 .. t_last of the sequence
 };
 
 __device__ __forceinline__ Blk make_blk(const MlaParams &kp, int b, int h, int qb, int wave, int n)
@@ -303,45 +312,197 @@ __device__ __forceinline__ Blk make_blk(const MlaParams &kp, int b, int h, int q
     k.raw_full_lo = k.n_rep_tiles + (mt_w_hi * g - k.raw_lo_blk + BN - 1) / BN;
     k.raw_full_hi = k.n_rep_tiles + max(0, (t_wfirst + 1 - k.raw_lo_blk) / BN);
     const int s = h / (kp.H / kp.S);
-    k.rep_pool = kp.pool_rep + ((size_t)b * kp.S + s) * kp.m * DP;
-    k.rep_sel = kp.sel_rep + ((size_t)b * kp.S + s) * kp.m * DS;
-    k.raw_pool = kp.POOL + (size_t)b * L * DP;
-    k.raw_sel = kp.SEL + (size_t)b * L * DS;
+    k.rep_pool = make_seg(kp.pool_rep + ((size_t)b * kp.S + s) * kp.m * DP, (long)k.mt_blk_hi * (DP * 2));
+    k.rep_sel = make_seg(kp.sel_rep + ((size_t)b * kp.S + s) * kp.m * DS, (long)k.mt_blk_hi * (DS * 2));
+    k.raw_pool = make_seg(kp.POOL + (size_t)b * L * DP, (long)(k.t_last + 1) * (DP * 2));
+    k.raw_sel = make_seg(kp.SEL + (size_t)b * L * DS, (long)(k.t_last + 1) * (DS * 2));
     return k;
 }
 
-__device__ __forceinline__ CopyDesc copy_desc(const Blk &k, int tl)
+// Copy of tile tc into stage `sd` (LDS address of stage 0 = lds0).  A tile past the item's last one lies past the
+// end of the raw segment: its copy moves zeros.
+__device__ __forceinline__ CopyCtl make_copy(const Blk &k, int tc, int sd, int wave, unsigned lds0)
 {
-    const bool is_rep = tl < k.n_rep_tiles;
-    CopyDesc cd;
-    cd.e0 = is_rep ? tl * BN : k.raw_lo_blk + (tl - k.n_rep_tiles) * BN;
-    cd.last = (is_rep ? k.mt_blk_hi : k.t_last + 1) - 1;
-    return cd;
+    CopyCtl c;
+    const bool is_rep = tc < k.n_rep_tiles;
+    const Seg &ps = is_rep ? k.rep_pool : k.raw_pool, &ss = is_rep ? k.rep_sel : k.raw_sel;
+    c.pool_rs = int4v{(int)ps.lo, (int)ps.hi, (int)ps.bytes, RSRC_WORD3};
+    c.sel_rs = int4v{(int)ss.lo, (int)ss.hi, (int)ss.bytes, RSRC_WORD3};
+    const unsigned row0 = (is_rep ? tc * BN : k.raw_lo_blk + (tc - k.n_rep_tiles) * BN) + 8 * wave;   // first entry of this wavefront's share
+    c.soff_lo = row0 * (DP * 2);
+    c.soff_hi = c.soff_lo + 4 * (DP * 2);
+    c.soff_sel = row0 * (DS * 2);
+    c.m0_pool = lds0 + sd * STAGE_BYTES + 8 * wave * RSB;
+    c.m0_sel = lds0 + sd * STAGE_BYTES + SEL_OFF + 8 * wave * (DS * 2);
+    return c;
 }
 
-// copies of tiles 0..2 of a work item into stages 0..2 (past the last tile: that tile again, nobody reads it)
-__device__ __forceinline__ void issue_first_copies(const Blk &k, char (*stages)[STAGE_BYTES], int wave, int lane, int sel_chunk)
+// What iteration tl of the tile loop needs besides the data: the copy of tile tl+3, this lane's read addresses in
+// the stages of the S^T chain (tile tl+1) and of the O^T update (tile tl), and how tile tl is treated.
+struct Ctl {
+    CopyCtl cc;
+    lds_cptr kb, kb_sel, vp0;
+    float bias;             // base-2 logit bias of tile tl (representatives may carry one)
+    int is_rep, full;       // tile tl, as masks (-1 / 0): a tile of representatives; every entry visible to every row of this wavefront
+};
+// The same, computed in small steps (STEP 0..8) so that the work can be dealt out over the free issue slots of
+// the O^T update; `t` carries intermediate values from step to step.  The empty assembly statements pin each
+// step's results to its place (the compiler would otherwise gather the steps where their last result is needed).
+struct CtlTmp { int tc, rep_c; unsigned row0, chain_lds, pv_lds; unsigned p0, p1, p2, q0, q1, q2; };
+#define LCA_PIN_S(x) asm volatile("" : "+s"(x))
+#define LCA_PIN_V(x) asm volatile("" : "+v"(x))
+// -1 if a < b, else 0 (|a - b| < 2^31), by scalar arithmetic: a comparison result turned into an integer would travel
+// through a vector register.  Unsigned subtraction so that the compiler cannot turn it back into a comparison.
+__device__ __forceinline__ int lt_mask(int a, int b) { return (int)((unsigned)a - (unsigned)b) >> 31; }
+template <int STEP>
+__device__ __forceinline__ void ctl_step(Ctl &c, CtlTmp &t, const Blk &k, const MlaParams &kp, int tl, int wave, unsigned lds0, int k_off,
+                                         int ksel_off, int v_off)
+{
+    if constexpr (STEP == 0) {
+        t.tc = tl + 3;
+        t.rep_c = lt_mask(t.tc, k.n_rep_tiles);
+        c.is_rep = lt_mask(tl, k.n_rep_tiles);
+        LCA_PIN_S(t.rep_c); LCA_PIN_S(c.is_rep);
+    } else if constexpr (STEP == 1) {
+        t.p0 = t.rep_c ? k.rep_pool.lo : k.raw_pool.lo;
+        t.p1 = t.rep_c ? k.rep_pool.hi : k.raw_pool.hi;
+        t.p2 = t.rep_c ? k.rep_pool.bytes : k.raw_pool.bytes;
+        LCA_PIN_S(t.p0); LCA_PIN_S(t.p1); LCA_PIN_S(t.p2);
+    } else if constexpr (STEP == 2) {
+        t.q0 = t.rep_c ? k.rep_sel.lo : k.raw_sel.lo;
+        t.q1 = t.rep_c ? k.rep_sel.hi : k.raw_sel.hi;
+        t.q2 = t.rep_c ? k.rep_sel.bytes : k.raw_sel.bytes;
+        LCA_PIN_S(t.q0); LCA_PIN_S(t.q1); LCA_PIN_S(t.q2);
+    } else if constexpr (STEP == 3) {
+        t.row0 = (t.rep_c ? t.tc * BN : k.raw_lo_blk + (t.tc - k.n_rep_tiles) * BN) + 8 * wave;
+        LCA_PIN_S(t.row0);
+    } else if constexpr (STEP == 4) {
+        c.cc.soff_lo = t.row0 * (DP * 2);
+        c.cc.soff_hi = c.cc.soff_lo + 4 * (DP * 2);
+        c.cc.soff_sel = t.row0 * (DS * 2);
+        LCA_PIN_S(c.cc.soff_lo); LCA_PIN_S(c.cc.soff_hi); LCA_PIN_S(c.cc.soff_sel);
+    } else if constexpr (STEP == 5) {
+        const unsigned sbase = lds0 + ((tl + 3) & (NSTAGE - 1)) * STAGE_BYTES;
+        c.cc.m0_pool = sbase + 8 * wave * RSB;
+        c.cc.m0_sel = sbase + SEL_OFF + 8 * wave * (DS * 2);
+        LCA_PIN_S(c.cc.m0_pool); LCA_PIN_S(c.cc.m0_sel);
+    } else if constexpr (STEP == 6) {
+        // past the last tile the chain runs over a stage that holds zeros or an old tile: S^T that nobody reads
+        t.chain_lds = lds0 + ((tl + 1) & (NSTAGE - 1)) * STAGE_BYTES;
+        t.pv_lds = lds0 + (tl & (NSTAGE - 1)) * STAGE_BYTES;
+        LCA_PIN_S(t.chain_lds); LCA_PIN_S(t.pv_lds);
+    } else if constexpr (STEP == 7) {
+        c.full = lt_mask(tl, k.rep_full_end) | (~lt_mask(tl, k.raw_full_lo) & lt_mask(tl, k.raw_full_hi));
+        LCA_PIN_S(c.full);
+        c.cc.pool_rs = int4v{(int)t.p0, (int)t.p1, (int)t.p2, RSRC_WORD3};
+        c.cc.sel_rs = int4v{(int)t.q0, (int)t.q1, (int)t.q2, RSRC_WORD3};
+    } else {
+        unsigned kb = t.chain_lds + k_off, kb_sel = t.chain_lds + ksel_off, vp0 = t.pv_lds + v_off;
+        c.bias = c.is_rep ? kp.bias_log2 : 0.f;
+        LCA_PIN_V(kb); LCA_PIN_V(kb_sel); LCA_PIN_V(vp0); LCA_PIN_V(c.bias);
+        c.kb = (lds_cptr)(uintptr_t)kb; c.kb_sel = (lds_cptr)(uintptr_t)kb_sel; c.vp0 = (lds_cptr)(uintptr_t)vp0;
+    }
+}
+__device__ __forceinline__ Ctl make_ctl(const Blk &k, const MlaParams &kp, int tl, int wave, unsigned lds0, int k_off, int ksel_off, int v_off)
+{
+    Ctl c;
+    CtlTmp t;
+    ctl_step<0>(c, t, k, kp, tl, wave, lds0, k_off, ksel_off, v_off); ctl_step<1>(c, t, k, kp, tl, wave, lds0, k_off, ksel_off, v_off);
+    ctl_step<2>(c, t, k, kp, tl, wave, lds0, k_off, ksel_off, v_off); ctl_step<3>(c, t, k, kp, tl, wave, lds0, k_off, ksel_off, v_off);
+    ctl_step<4>(c, t, k, kp, tl, wave, lds0, k_off, ksel_off, v_off); ctl_step<5>(c, t, k, kp, tl, wave, lds0, k_off, ksel_off, v_off);
+    ctl_step<6>(c, t, k, kp, tl, wave, lds0, k_off, ksel_off, v_off); ctl_step<7>(c, t, k, kp, tl, wave, lds0, k_off, ksel_off, v_off);
+    ctl_step<8>(c, t, k, kp, tl, wave, lds0, k_off, ksel_off, v_off);
+    return c;
+}
+
+// copies of tiles 0..2 of a work item into stages 0..2
+__device__ __forceinline__ void issue_first_copies(const Blk &k, int wave, unsigned lds0, unsigned voff_pool, unsigned voff_sel)
 {
     for (int tl = 0; tl < 3; ++tl) {
-        const int tc = min(tl, k.n_tiles - 1);
-        issue_copy(stages[tl], tc < k.n_rep_tiles ? k.rep_pool : k.raw_pool, tc < k.n_rep_tiles ? k.rep_sel : k.raw_sel, copy_desc(k, tc), wave,
-                   lane, sel_chunk);
+        const CopyCtl c = make_copy(k, tl, tl, wave, lds0);
+        issue_copy_from<0>(c, voff_pool, voff_sel);
     }
 }
 
-// Q^T fragments of a work item: lane (n, G) holds Q[t_row, ks*16 + 8G .. +7]
-__device__ __forceinline__ void load_q(const MlaParams &kp, const Blk &k, int G, bf16x8 (&qf)[NKS])
+// Queries of a work item.  The second product wants lane (n, G) to hold Q[row n][16 ks + 8 G .. +7] for every
+// k-step ks, but loading them that way makes every load instruction touch 32 rows = 32 cache lines for 16 bytes
+// each.  So the loads are issued row-wise -- load i = 4c + q: lane l fetches the 16-byte piece l%8 of the 128-byte
+// column block c of row 8q + l/8, eight whole cache lines per instruction -- and q_to_fragments turns the
+// registers into fragments through a private 4 KB LDS buffer, one column block (four k-steps) at a time.
+__device__ __forceinline__ void load_q(const MlaParams &kp, const Blk &k, int wave, int lane, bf16x8 (&qf)[NKS])
 {
-    const uint16_t *qp = kp.Q + (((size_t)k.b * kp.L + min(k.t_row, kp.L - 1)) * kp.H + k.h) * DQK + G * 8;
+    const int t_wfirst = k.t0 + wave * 32;
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+    for (int q = 0; q < 4; ++q) {
+        const int t = min(t_wfirst + 8 * q + (lane >> 3), kp.L - 1);
+        const uint16_t *qp = kp.Q + (((size_t)k.b * kp.L + t) * kp.H + k.h) * DQK + (lane & 7) * 8;
+#pragma unroll
+        for (int c = 0; c < NKS / 4; ++c) qf[4 * c + q] = *reinterpret_cast<const bf16x8 *>(qp + c * 64);
+    }
 }
+// `buf`: 4 KB of LDS private to this wavefront.  Piece p of row r sits at r*128 + ((p ^ (r>>1)) & 7)*16, which makes
+// the row-wise writes and the fragment reads (16 lanes = 16 rows, one piece each) free of bank conflicts.  LDS
+// operations of one wavefront run in order, so the reads of one block need no wait before the next block's writes.
+__device__ __forceinline__ void q_to_fragments(char *buf, int lane, bf16x8 (&qf)[NKS])
+{
+    const int n = lane & 31, G = lane >> 5, wrow = lane >> 3, wp = lane & 7;
+#pragma unroll
+    for (int c = 0; c < NKS / 4; ++c) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int r = 8 * q + wrow;
+            *reinterpret_cast<bf16x8 *>(buf + r * 128 + ((wp ^ (r >> 1)) & 7) * 16) = qf[4 * c + q];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) qf[4 * c + j] = *reinterpret_cast<const bf16x8 *>(buf + n * 128 + (((2 * j + G) ^ (n >> 1)) & 7) * 16);
+    }
+}
+
+// Hide the entries of a boundary tile that this lane's query row must not see (e0 = first entry of the tile).
+// Accumulator register r of lane group G holds entry e0 + acc_entry(r, 0) + G; a row sees the representatives
+// [0, mt_row) or the raw tokens [raw_lo_row, t_row]: one unsigned comparison per register, no branches.
+__device__ __forceinline__ void mask_tile(floatx16 &sv, const Blk &k, bool is_rep, int e0, int G)
+{
+    const int lo = is_rep ? -(1 << 30) : k.raw_lo_row, end = is_rep ? k.mt_row : k.t_row + 1;
+    const unsigned count = (unsigned)(end - lo);         // may be 0: a row whose last token closes a group sees no raw token when w = 0
+    const int d = e0 + G - lo;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        static_assert(acc_entry(5, 1) == acc_entry(5, 0) + 1, "lane group adds one to the entry");
+        const bool vis = (unsigned)(d + acc_entry(r, 0)) < count;
+        sv[r] = vis ? sv[r] : -INFINITY;
+    }
+}
+// Largest base-2 logit of this lane's query row in one tile (both lanes of the row get it); -1e30 if it sees nothing.
+// (inline assembly: the compiler would first canonicalise every input of a maximum it cannot see the origin of)
+__device__ __forceinline__ float row_max(const floatx16 &sv, float c, float bias)
+{
+    float mx[6];
+#pragma unroll
+    for (int i = 0; i < 5; ++i) asm("v_max3_f32 %0, %1, %2, %3" : "=v"(mx[i]) : "v"(sv[3 * i]), "v"(sv[3 * i + 1]), "v"(sv[3 * i + 2]));
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(mx[5]) : "v"(mx[0]), "v"(mx[1]), "v"(mx[2]));
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(mx[0]) : "v"(mx[3]), "v"(mx[4]), "v"(sv[15]));
+    asm("v_max_f32 %0, %1, %2" : "=v"(mx[1]) : "v"(mx[5]), "v"(mx[0]));
+    const float t = fmaxf(fmaf(mx[1], c, bias), NEG_BIG);
+    // the partner lane holds the other 16 keys of this query: swap halves between two copies, no LDS traffic
+    typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
+    const uintx2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(t), __float_as_uint(t), false, false);
+    float m;
+    asm("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(sw[0]), "v"(sw[1]));
+    return m;
+}
+
 
 // Persistent kernel: one workgroup per CU walks a list of work items.  Workgroup w lives on XCD w%8 (round-
 // robin placement) and is slot w/8 of that XCD; the XCD's item list is (query-block order x, x+8, ... of
 // the heaviest-first order) x (all heads), so that at any time the slots of an XCD work on the heads of
 // one or two query blocks and share their K/V tiles in that XCD's L2.  The next item's queries and first
 // tiles are requested before the current item's output is written, so the transition costs no round trip.
+//
+// Iteration tl of the tile loop, after its barrier: the held-back last MFMAs of the O^T update of tile tl-1
+// (while the first key fragments of tile tl+1 arrive), the S^T chain of tile tl+1 with the softmax of tile tl
+// in its shadow and the copy of tile tl+3 in its last slots, then the O^T update of tile tl with the loop's
+// bookkeeping for iteration tl+1 in its shadow.
 __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
 {
     __shared__ __attribute__((aligned(1024))) char stages[NSTAGE][STAGE_BYTES];
@@ -349,6 +510,7 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, G = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int L = kp.L, H = kp.H;
+    const unsigned lds0 = lds_address(&stages[0][0]);
 
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, n_slots = gridDim.x >> 3;
     const int n_units = kp.n_qb * kp.B;                       // (query block, sequence) pairs, heaviest first
@@ -368,8 +530,10 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
     const int ksel_off = SEL_OFF + krow * (DS * 2) + ((G ^ (xs & 1)) << 4);          // S^T, RoPE part: chunk (2j+G) sits at slot (2j+G)^xs
     const int x6 = xs & 6;
     const int v_off = (4 * ((lane & 15) >> 2) + G) * RSB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;   // V^T transpose read
-    // copy side of the swizzle: lane l of the RoPE copy fills slot l&7 of local row l>>3 (row 8*wave + (l>>3) of the tile)
-    const int sel_chunk = (lane & 7) ^ ((4 * wave + (lane >> 4)) & 7);
+    // copy side: lane l of a latent-row copy moves chunk l; lane l of the RoPE copy fills slot l&7 of local row l>>3
+    // (row 8*wave + (l>>3) of the tile) with the chunk the swizzle assigns to that slot
+    const unsigned voff_pool = lane * 16;
+    const unsigned voff_sel = (lane >> 3) * (DS * 2) + (((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) << 4);
     const float c = kp.scale_log2;
 
     int kidx = slot, ib, ih, iqb;
@@ -380,63 +544,121 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
     bf16x8 qf[NKS];
     floatx16 acc[NDV];
     RowState st;
-    issue_first_copies(cur, stages, wave, lane, sel_chunk);
-    load_q(kp, cur, G, qf);
+    issue_first_copies(cur, wave, lds0, voff_pool, voff_sel);
+    load_q(kp, cur, wave, lane, qf);
+    char *const qbuf = &stages[3][0] + wave * 32 * (128 * 2 + 16);      // this wavefront's part of the output staging area
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    q_to_fragments(qbuf, lane, qf);
 
     while (true) {
-        float m_init = NEG_BIG;
-    restart:
+        // Pass 0 is the normal one: every row fixes its reference at the first entries it sees and never looks at
+        // maxima again.  Only if a row sum ends beyond L_LIMIT (or not finite) the workgroup finds every row's true
+        // maximum (S^T chains alone) and runs the item again from those (pass 2).
+        int pass = 0;
+        float m_exact = NEG_BIG;
+        while (true) {       // passes over this item
+        // O^T = 0: sixteen MFMAs with zero operands instead of 256 register writes (the matrix core is idle here anyway)
+        {
+            bf16x8 zf = {0, 0, 0, 0, 0, 0, 0, 0};
+            asm volatile("" : "+v"(zf));
 #pragma unroll
-        for (int i = 0; i < NDV; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-        st.m_ref = m_init; st.l_run = 0.f; st.m_seen = NEG_BIG; st.exceeded = false;
+            for (int i = 0; i < NDV; ++i) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc[i]) : "v"(zf));
+        }
+        st.m_ref = m_exact; st.l_run = 0.f;
+        bool need_ref = pass == 0;          // wave-uniform: some row of this wavefront has no reference yet
 
         // the first tiles and the queries of this item are on their way; then the S^T chain of tile 0
         floatx16 snext, scur;
-        bf16x8 pb[2];
+        Pb pb;
+        PvFrags pvf;
+        ChainFrags cf;
+        // there is no tile -1: its held-back MFMAs add V^T = 0 times P^T = 0
+#pragma unroll
+        for (int i = 0; i < PV_GROUP; ++i) { pvf.lo[1][i] = bf16x4{0, 0, 0, 0}; pvf.hi[1][i] = bf16x4{0, 0, 0, 0}; }
+        pb.v[0] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0}; pb.v[1] = pb.v[0];
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         {
-            PvFrags unused;
-            chain_and_softmax<true, false, false>(stages[0] + k_off, stages[0] + ksel_off, x6, qf, snext, snext, pb, st, c, 0.f, unused, nullptr,
-                                                  nullptr, WaveCopy(), wave, lane, sel_chunk);
+            lds_cptr s0 = (lds_cptr)(uintptr_t)lds0;
+            chain_prefetch(cf, s0 + k_off, s0 + ksel_off, x6);
+            chain_and_softmax<false, false>(cf, s0 + k_off, s0 + ksel_off, x6, qf, snext, snext, pb, st, c, 0.f, pvf, s0, CopyCtl(), 0, 0);
         }
+        scur = snext;
+        int tl0 = 0;
+        asm volatile("" : "+s"(tl0));        // (opaque: with a known zero the compiler turns the flag arithmetic of make_ctl back into comparisons)
+        Ctl ctl = make_ctl(cur, kp, tl0, wave, lds0, k_off, ksel_off, v_off);
 
         for (int tl = 0; tl < cur.n_tiles; ++tl) {
-            // everything that does not need the barrier comes before it, so that the chain starts right after it
-            const bool is_rep = tl < cur.n_rep_tiles;
-            const float bias = is_rep ? kp.bias_log2 : 0.f;
-            scur = snext;
-            const bool full = tl < cur.rep_full_end || (tl >= cur.raw_full_lo && tl < cur.raw_full_hi);
-            if (!full) {   // boundary tiles: hide the entries this row must not see
-                const int e0 = is_rep ? tl * BN : cur.raw_lo_blk + (tl - cur.n_rep_tiles) * BN;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int e = e0 + acc_entry(r, G);
-                    const bool vis = is_rep ? (e < cur.mt_row) : (e >= cur.raw_lo_row && e <= cur.t_row);
-                    scur[r] = vis ? scur[r] : -INFINITY;
+            if (__builtin_expect((ctl.full == 0) | need_ref, 0)) {      // rare: boundary tiles, and the first tiles of an item
+                if (ctl.full == 0) mask_tile(scur, cur, ctl.is_rep != 0, ctl.is_rep ? tl * BN : cur.raw_lo_blk + (tl - cur.n_rep_tiles) * BN, G);
+                if (need_ref) {              // the first visible entries of a row fix its reference
+                    const float mx = row_max(scur, c, ctl.bias);
+                    st.m_ref = (st.m_ref == NEG_BIG) ? mx : st.m_ref;
+                    need_ref = __builtin_amdgcn_ballot_w64(st.m_ref == NEG_BIG) != 0;
                 }
             }
-            // The chain and the copy always run: past the last tile they redo that tile (S^T that nobody reads, a
-            // copy into a stage that nobody reads again), which keeps the loop body branch-free.
-            const char *dma_stage = stages[(tl + 3) & (NSTAGE - 1)];
-            const char *chain_stage = stages[min(tl + 1, cur.n_tiles - 1) & (NSTAGE - 1)], *pv_stage = stages[tl & (NSTAGE - 1)];
-            const int tc = min(tl + 3, cur.n_tiles - 1);
-            const WaveCopy wc = wave_copy(tc < cur.n_rep_tiles ? cur.rep_pool : cur.raw_pool, tc < cur.n_rep_tiles ? cur.rep_sel : cur.raw_sel,
-                                          copy_desc(cur, tc), wave);
             // tile tl+1 has landed: its copy was issued two iterations ago, only tile tl+2's 9 loads may be pending ...
-            asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-            __syncthreads();      // ... for every wavefront, and every wavefront is done with tile tl-1
-            tile_step(dma_stage, chain_stage, pv_stage, wc, wave, lane, sel_chunk, k_off, ksel_off, x6, v_off, qf, snext, scur, pb, st, c, bias,
-                      acc);
+            // and this wavefront's transpose reads of tile tl-1 (the held-back group) are in registers
+            asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)" ::: "memory");
+            __syncthreads();      // ... for every wavefront, and every wavefront is done with tile tl-1 (all of its V^T fragments are in registers)
+            LCA_FENCE();
+            chain_prefetch(cf, ctl.kb, ctl.kb_sel, x6);
+            pv_tail(pvf, pb, acc);
+            chain_and_softmax<true, true>(cf,
+                                          ctl.kb, ctl.kb_sel, x6, qf, snext, scur, pb, st, c, ctl.bias, pvf, ctl.vp0, ctl.cc, voff_pool, voff_sel);
+            Ctl nx;
+            CtlTmp tmp;
+            pv_update(pvf, ctl.vp0, pb, acc, [&](int j) {
+                // Nothing may read the chain's result before MFMAs of the O^T update have run (the compiler takes an
+                // inline-assembly result as ready at once; these MFMAs are the wait states it actually needs).
+                if (j >= 4 && j < 20) asm volatile("v_mov_b32 %0, %1" : "=v"(scur[j - 4]) : "v"(snext[j - 4]));
+                // the bookkeeping of iteration tl+1, a few instructions per MFMA
+                switch (j) {
+                case 1: ctl_step<0>(nx, tmp, cur, kp, tl + 1, wave, lds0, k_off, ksel_off, v_off); break;
+                case 3: ctl_step<1>(nx, tmp, cur, kp, tl + 1, wave, lds0, k_off, ksel_off, v_off); break;
+                case 5: ctl_step<2>(nx, tmp, cur, kp, tl + 1, wave, lds0, k_off, ksel_off, v_off); break;
+                case 7: ctl_step<3>(nx, tmp, cur, kp, tl + 1, wave, lds0, k_off, ksel_off, v_off); break;
+                case 9: ctl_step<4>(nx, tmp, cur, kp, tl + 1, wave, lds0, k_off, ksel_off, v_off); break;
+                case 11: ctl_step<5>(nx, tmp, cur, kp, tl + 1, wave, lds0, k_off, ksel_off, v_off); break;
+                case 13: ctl_step<6>(nx, tmp, cur, kp, tl + 1, wave, lds0, k_off, ksel_off, v_off); break;
+                case 15: ctl_step<7>(nx, tmp, cur, kp, tl + 1, wave, lds0, k_off, ksel_off, v_off); break;
+                case 21: ctl_step<8>(nx, tmp, cur, kp, tl + 1, wave, lds0, k_off, ksel_off, v_off); break;
+                default: break;
+                }
+            });
+            ctl = nx;
         }
+        pv_tail(pvf, pb, acc);                             // the last tile's held-back MFMAs
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the trailing copies have landed before the stages are reused
-        // every wavefront is done with the tile stages; repeat the pass if any row ran out of exponent headroom
-        if (__syncthreads_or(st.exceeded)) {
-            m_init = st.m_seen;
-            issue_first_copies(cur, stages, wave, lane, sel_chunk);
-            goto restart;
+        // every wavefront is done with the tile stages; repeat the item if a row sum ran out of range
+        {
+            const float l_chk = st.l_run + __shfl_xor(st.l_run, 32, 64);
+            const bool redo = pass == 0 && !(l_chk <= L_LIMIT);
+            if (!__syncthreads_or(redo)) break;
+            {
+                // exact row maxima, one tile at a time (no overlap: this path is rare): tile tl goes into stage tl%2
+                // after the barrier of tile tl-1, which every wavefront reaches after its chain over tile tl-2
+                m_exact = NEG_BIG;
+                for (int tl = 0; tl < cur.n_tiles; ++tl) {
+                    const CopyCtl cc = make_copy(cur, tl, tl & 1, wave, lds0);
+                    issue_copy_from<0>(cc, voff_pool, voff_sel);
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    __syncthreads();
+                    lds_cptr sp = (lds_cptr)(uintptr_t)(lds0 + (tl & 1) * STAGE_BYTES);
+                    floatx16 sv;
+                    ChainFrags cf;
+                    PvFrags unused;
+                    chain_prefetch(cf, sp + k_off, sp + ksel_off, x6);
+                    chain_and_softmax<false, false>(cf, sp + k_off, sp + ksel_off, x6, qf, sv, sv, pb, st, c, 0.f, unused, sp, CopyCtl(), 0, 0);
+                    const bool is_rep = tl < cur.n_rep_tiles;
+                    mask_tile(sv, cur, is_rep, is_rep ? tl * BN : cur.raw_lo_blk + (tl - cur.n_rep_tiles) * BN, G);
+                    m_exact = fmaxf(m_exact, row_max(sv, c, is_rep ? kp.bias_log2 : 0.f));
+                }
+                __syncthreads();
+                pass = 2;
+                issue_first_copies(cur, wave, lds0, voff_pool, voff_sel);
+            }
+        }
         }
 
         // request the next item's first tiles (stages 0..2) and queries before writing this item's output
@@ -446,8 +668,8 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         const int out_b = cur.b, out_h = cur.h, out_t0 = cur.t0, out_t_row = cur.t_row;
         if (has_next) {
             cur = make_blk(kp, nb, nh, nqb, wave, n);
-            issue_first_copies(cur, stages, wave, lane, sel_chunk);
-            load_q(kp, cur, G, qf);
+            issue_first_copies(cur, wave, lds0, voff_pool, voff_sel);
+            load_q(kp, cur, wave, lane, qf);
         }
 
         // ---- epilogue: normalise, transpose through LDS stage 3 (four passes of 128 value columns), store coalesced ----
@@ -480,6 +702,9 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         if (kp.lse != nullptr && G == 0 && out_t_row < L)
             kp.lse[((size_t)out_b * L + out_t_row) * H + out_h] = (st.m_ref + log2f(l_tot)) * 0.6931471805599453f;
         if (!has_next) break;
+        // the next item's queries have been on their way since before the output was written
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        q_to_fragments(qbuf, lane, qf);
     }
 }
 
@@ -487,7 +712,8 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
 
 bool attn_mla_supported(const Dims &d)
 {
-    return d.dtype == LCA_BF16 && d.mode == LCA_MODE_MLA && d.d_pool == DP && d.d_sel == DS && d.scale > 0.f;
+    // segment sizes and row offsets travel as 32-bit byte counts
+    return d.dtype == LCA_BF16 && d.mode == LCA_MODE_MLA && d.d_pool == DP && d.d_sel == DS && d.scale > 0.f && d.L <= (1 << 21);
 }
 
 hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st)
