@@ -183,7 +183,7 @@ __device__ __forceinline__ void issue_copy_part_dyn(int j, const CopyCtl &c, uns
 
 // S^T chain of one tile (36 MFMAs into `snext`, key fragments prefetched CHAIN_DEPTH deep) and, when SOFTMAX,
 // the vector work that turns the previous tile's S^T (`scur`) into P^T fragments, spread over the
-// chain's issue slots.  `kb` / `kb_sel` = LDS addresses of this lane's first key fragment of the chain's tile.
+// chain's issue slots.  `kb` / `ksel` = LDS addresses of this lane's key fragments in the chain's tile (latent part: first one; RoPE part: all four).
 // The MFMAs are inline assembly so that their accumulator is an ordinary vector register tuple (all 256
 // accumulation registers belong to O^T); the wait states an MFMA result needs before vector
 // instructions read it are spent explicitly at the end of the chain.
@@ -192,19 +192,27 @@ __device__ __forceinline__ void issue_copy_part_dyn(int j, const CopyCtl &c, uns
 // the explicit wait states are left out: the caller keeps every reader of the chain's result behind MFMAs of
 // the O^T update.
 struct ChainFrags { bf16x8 fr[CHAIN_DEPTH]; };
-__device__ __forceinline__ bf16x8 chain_frag(lds_cptr kb, lds_cptr kb_sel, int x6, int ks)
+// LDS addresses of this lane's four key fragments of the RoPE part (k-steps 32..35) of a stage: chunk 2j + G of the
+// lane's row sits at slot (2j + G) ^ xs.  `first` = address of the slot of j = 0 (x6 = xs & 6 already applied);
+// slot bits 1..2 are address bits 5..6, which are zero in the row's base address, so j enters as an exclusive or.
+struct KSel { unsigned a[4]; };
+__device__ __forceinline__ KSel make_ksel(unsigned first)
+{
+    return KSel{{first, first ^ (1u << 5), first ^ (2u << 5), first ^ (3u << 5)}};
+}
+__device__ __forceinline__ bf16x8 chain_frag(lds_cptr kb, const KSel &ksel, int ks)
 {
     // key fragment of k-step ks: latent columns from the row-strided part, RoPE columns (ks >= 32) from the swizzled part
-    lds_cptr p = ks < DP / 16 ? kb + ks * 32 : kb_sel + ((x6 ^ (2 * (ks - DP / 16))) << 4);
+    lds_cptr p = ks < DP / 16 ? kb + ks * 32 : (lds_cptr)(uintptr_t)ksel.a[ks - DP / 16];
     return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8 *>(p);
 }
-__device__ __forceinline__ void chain_prefetch(ChainFrags &cf, lds_cptr kb, lds_cptr kb_sel, int x6)
+__device__ __forceinline__ void chain_prefetch(ChainFrags &cf, lds_cptr kb, const KSel &ksel)
 {
 #pragma unroll
-    for (int i = 0; i < CHAIN_DEPTH; ++i) cf.fr[i] = chain_frag(kb, kb_sel, x6, i);
+    for (int i = 0; i < CHAIN_DEPTH; ++i) cf.fr[i] = chain_frag(kb, ksel, i);
 }
 template <bool SOFTMAX, bool PIPELINED>
-__device__ __forceinline__ void chain_and_softmax(ChainFrags &cf, lds_cptr kb, lds_cptr kb_sel, int x6, const bf16x8 (&qf)[NKS], floatx16 &snext,
+__device__ __forceinline__ void chain_and_softmax(ChainFrags &cf, lds_cptr kb, const KSel &ksel, const bf16x8 (&qf)[NKS], floatx16 &snext,
                                                   const floatx16 &scur, Pb &pb, RowState &st, float c, float bias, PvFrags &pvf,
                                                   lds_cptr vp0, const CopyCtl &cc, unsigned voff_pool, unsigned voff_sel)
 {
@@ -216,7 +224,7 @@ __device__ __forceinline__ void chain_and_softmax(ChainFrags &cf, lds_cptr kb, l
             asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(snext) : "v"(cf.fr[0]), "v"(qf[0]));
         else
             asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(snext) : "v"(cf.fr[ks % CHAIN_DEPTH]), "v"(qf[ks]));
-        if (ks + CHAIN_DEPTH < NKS) cf.fr[ks % CHAIN_DEPTH] = chain_frag(kb, kb_sel, x6, ks + CHAIN_DEPTH);
+        if (ks + CHAIN_DEPTH < NKS) cf.fr[ks % CHAIN_DEPTH] = chain_frag(kb, ksel, ks + CHAIN_DEPTH);
         if (SOFTMAX) {
             // P^T = exp2(S^T * c + bias - reference), two S^T registers per three slots: an exponential in each of two
             // slots, then the pair is added to the row sum and rounded to bf16.  No maxima here: the reference was
@@ -227,7 +235,10 @@ __device__ __forceinline__ void chain_and_softmax(ChainFrags &cf, lds_cptr kb, l
                 const int k = ks / 3, sub = ks % 3;
                 if (sub < 2) pf[sub] = __builtin_amdgcn_exp2f(fmaf(scur[2 * k + sub], c, nb));
                 else {
-                    const bf16x2 pr = {(__bf16)pf[0], (__bf16)pf[1]};
+                    bf16x2 pr = {(__bf16)pf[0], (__bf16)pf[1]};
+                    unsigned bits = __builtin_bit_cast(unsigned, pr);
+                    asm volatile("" : "+v"(bits));      // (pins the conversion to this slot: the compiler would gather four of them where the fragment is complete)
+                    pr = __builtin_bit_cast(bf16x2, bits);
                     pb.p[k] = pr;
                     st.l_run += pf[0];       // (two plain additions: v_dot2c_f32_bf16 stalls next to MFMAs, about 25 cycles each)
                     st.l_run += pf[1];
@@ -341,7 +352,8 @@ __device__ __forceinline__ CopyCtl make_copy(const Blk &k, int tc, int sd, int w
 // the stages of the S^T chain (tile tl+1) and of the O^T update (tile tl), and how tile tl is treated.
 struct Ctl {
     CopyCtl cc;
-    lds_cptr kb, kb_sel, vp0;
+    lds_cptr kb, vp0;
+    KSel ksel;
     float bias;             // base-2 logit bias of tile tl (representatives may carry one)
     int is_rep, full;       // tile tl, as masks (-1 / 0): a tile of representatives; every entry visible to every row of this wavefront
 };
@@ -397,10 +409,12 @@ __device__ __forceinline__ void ctl_step(Ctl &c, CtlTmp &t, const Blk &k, const 
         c.cc.pool_rs = int4v{(int)t.p0, (int)t.p1, (int)t.p2, RSRC_WORD3};
         c.cc.sel_rs = int4v{(int)t.q0, (int)t.q1, (int)t.q2, RSRC_WORD3};
     } else {
-        unsigned kb = t.chain_lds + k_off, kb_sel = t.chain_lds + ksel_off, vp0 = t.pv_lds + v_off;
+        unsigned kb = t.chain_lds + k_off, vp0 = t.pv_lds + v_off;
+        c.ksel = make_ksel(t.chain_lds + ksel_off);
         c.bias = c.is_rep ? kp.bias_log2 : 0.f;
-        LCA_PIN_V(kb); LCA_PIN_V(kb_sel); LCA_PIN_V(vp0); LCA_PIN_V(c.bias);
-        c.kb = (lds_cptr)(uintptr_t)kb; c.kb_sel = (lds_cptr)(uintptr_t)kb_sel; c.vp0 = (lds_cptr)(uintptr_t)vp0;
+        LCA_PIN_V(kb); LCA_PIN_V(vp0); LCA_PIN_V(c.bias);
+        LCA_PIN_V(c.ksel.a[0]); LCA_PIN_V(c.ksel.a[1]); LCA_PIN_V(c.ksel.a[2]); LCA_PIN_V(c.ksel.a[3]);
+        c.kb = (lds_cptr)(uintptr_t)kb; c.vp0 = (lds_cptr)(uintptr_t)vp0;
     }
 }
 __device__ __forceinline__ Ctl make_ctl(const Blk &k, const MlaParams &kp, int tl, int wave, unsigned lds0, int k_off, int ksel_off, int v_off)
@@ -527,8 +541,7 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
     const int krow = lds_row_of_m(n);                                                // LDS row behind S^T row n
     const int k_off = krow * RSB + G * 16;                                           // S^T, latent part: 16-byte chunk G of that row
     const int xs = (krow >> 1) & 7;                                                  // swizzle of that row in the RoPE part
-    const int ksel_off = SEL_OFF + krow * (DS * 2) + ((G ^ (xs & 1)) << 4);          // S^T, RoPE part: chunk (2j+G) sits at slot (2j+G)^xs
-    const int x6 = xs & 6;
+    const int ksel_off = SEL_OFF + krow * (DS * 2) + (((G ^ xs) & 7) << 4);          // S^T, RoPE part: chunk (2j+G) sits at slot (2j+G)^xs; this is j = 0
     const int v_off = (4 * ((lane & 15) >> 2) + G) * RSB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;   // V^T transpose read
     // copy side: lane l of a latent-row copy moves chunk l; lane l of the RoPE copy fills slot l&7 of local row l>>3
     // (row 8*wave + (l>>3) of the tile) with the chunk the swizzle assigns to that slot
@@ -580,8 +593,9 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         __syncthreads();
         {
             lds_cptr s0 = (lds_cptr)(uintptr_t)lds0;
-            chain_prefetch(cf, s0 + k_off, s0 + ksel_off, x6);
-            chain_and_softmax<false, false>(cf, s0 + k_off, s0 + ksel_off, x6, qf, snext, snext, pb, st, c, 0.f, pvf, s0, CopyCtl(), 0, 0);
+            const KSel ks0 = make_ksel(lds0 + ksel_off);
+            chain_prefetch(cf, s0 + k_off, ks0);
+            chain_and_softmax<false, false>(cf, s0 + k_off, ks0, qf, snext, snext, pb, st, c, 0.f, pvf, s0, CopyCtl(), 0, 0);
         }
         scur = snext;
         int tl0 = 0;
@@ -602,10 +616,10 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
             asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)" ::: "memory");
             __syncthreads();      // ... for every wavefront, and every wavefront is done with tile tl-1 (all of its V^T fragments are in registers)
             LCA_FENCE();
-            chain_prefetch(cf, ctl.kb, ctl.kb_sel, x6);
+            chain_prefetch(cf, ctl.kb, ctl.ksel);
             pv_tail(pvf, pb, acc);
             chain_and_softmax<true, true>(cf,
-                                          ctl.kb, ctl.kb_sel, x6, qf, snext, scur, pb, st, c, ctl.bias, pvf, ctl.vp0, ctl.cc, voff_pool, voff_sel);
+                                          ctl.kb, ctl.ksel, qf, snext, scur, pb, st, c, ctl.bias, pvf, ctl.vp0, ctl.cc, voff_pool, voff_sel);
             Ctl nx;
             CtlTmp tmp;
             pv_update(pvf, ctl.vp0, pb, acc, [&](int j) {
@@ -648,8 +662,9 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
                     floatx16 sv;
                     ChainFrags cf;
                     PvFrags unused;
-                    chain_prefetch(cf, sp + k_off, sp + ksel_off, x6);
-                    chain_and_softmax<false, false>(cf, sp + k_off, sp + ksel_off, x6, qf, sv, sv, pb, st, c, 0.f, unused, sp, CopyCtl(), 0, 0);
+                    const KSel ksp = make_ksel(lds0 + (tl & 1) * STAGE_BYTES + ksel_off);
+                    chain_prefetch(cf, sp + k_off, ksp);
+                    chain_and_softmax<false, false>(cf, sp + k_off, ksp, qf, sv, sv, pb, st, c, 0.f, unused, sp, CopyCtl(), 0, 0);
                     const bool is_rep = tl < cur.n_rep_tiles;
                     mask_tile(sv, cur, is_rep, is_rep ? tl * BN : cur.raw_lo_blk + (tl - cur.n_rep_tiles) * BN, G);
                     m_exact = fmaxf(m_exact, row_max(sv, c, is_rep ? kp.bias_log2 : 0.f));
