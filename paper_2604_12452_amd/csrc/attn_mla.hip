@@ -508,9 +508,9 @@ __device__ __forceinline__ float row_max(const floatx16 &sv, float c, float bias
 
 
 // Persistent kernel: one workgroup per CU walks a list of work items.  Workgroup w lives on XCD w%8 (round-
-// robin placement) and is slot w/8 of that XCD; the XCD's item list is (query-block order x, x+8, ... of
-// the heaviest-first order) x (all heads), so that at any time the slots of an XCD work on the heads of
-// one or two query blocks and share their K/V tiles in that XCD's L2.  The next item's queries and first
+// robin placement) and is slot w/8 of that XCD; the XCD's item list is (query blocks 2x, 2x+1, 2x+16, 2x+17, ...
+// of the heaviest-first order) x (all heads), so that at any time the slots of an XCD work on the heads of two
+// neighbouring query blocks, which see nearly the same keys, and share their K/V tiles in that XCD's L2.  The next item's queries and first
 // tiles are requested before the current item's output is written, so the transition costs no round trip.
 //
 // Iteration tl of the tile loop, after its barrier: the held-back last MFMAs of the O^T update of tile tl-1
@@ -528,10 +528,10 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
 
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, n_slots = gridDim.x >> 3;
     const int n_units = kp.n_qb * kp.B;                       // (query block, sequence) pairs, heaviest first
-    const int items_per_xcd = ((n_units + 7) / 8) * H;        // some may fall past n_units
+    const int items_per_xcd = ((n_units + 15) / 16) * 2 * H;  // some may fall past n_units
     auto item = [&](int kidx, int &b, int &h, int &qb) {      // false when the item does not exist
         h = kidx % H;
-        const int ord = (kidx / H) * 8 + xcd;
+        const int j = kidx / H, ord = (j >> 1) * 16 + 2 * xcd + (j & 1);     // an XCD works on two neighbouring query blocks at a time
         b = ord % kp.B;
         qb = kp.n_qb - 1 - ord / kp.B;
         return kidx < items_per_xcd && ord < n_units;
@@ -694,6 +694,14 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         static_assert(4 * 32 * ORS <= STAGE_BYTES, "output staging must fit in one tile stage");
         char *obuf = &stages[3][0] + wave * 32 * ORS;
         const int t_wfirst = out_t0 + wave * 32;
+        // The stores go through a buffer descriptor of this wavefront's rows of this head (row r at r*H*1 KB): scalar
+        // offsets instead of 64-bit address arithmetic per store, and rows past the end of the sequence fall outside
+        // the descriptor's range and are dropped.
+        const int rows_valid = min(max(L - t_wfirst, 0), 32);
+        const __amdgpu_buffer_rsrc_t o_rs = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(kp.O + (((size_t)out_b * L + t_wfirst) * H + out_h) * DV), (short)0,
+            rows_valid > 0 ? ((rows_valid - 1) * H * DV + DV) * 2 : 0, RSRC_WORD3);
+        const int o_voff = ((lane >> 4) * H * DV + (lane & 15) * 8) * 2;
 #pragma unroll
         for (int pass = 0; pass < 4; ++pass) {
 #pragma unroll
@@ -708,9 +716,10 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int r4 = 0; r4 < 8; ++r4) {                 // one wave-wide store covers four rows of 256 B
-                const int r = r4 * 4 + (lane >> 4), t = t_wfirst + r;
-                const uint4 v = *reinterpret_cast<const uint4 *>(obuf + r * ORS + (lane & 15) * 16);
-                if (t < L) *reinterpret_cast<uint4 *>(kp.O + (((size_t)out_b * L + t) * H + out_h) * DV + pass * 128 + (lane & 15) * 8) = v;
+                typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+                const int r = r4 * 4 + (lane >> 4);
+                const uintx4 v = *reinterpret_cast<const uintx4 *>(obuf + r * ORS + (lane & 15) * 16);
+                __builtin_amdgcn_raw_buffer_store_b128(v, o_rs, o_voff, (r4 * 4 * H * DV + pass * 128) * 2, 0);
             }
             __builtin_amdgcn_wave_barrier();
         }
@@ -743,7 +752,7 @@ hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st)
     kp.scale_log2 = d.scale * 1.4426950408889634f;
     kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
     // persistent grid: one workgroup per CU (a workgroup takes all of a CU's LDS and registers)
-    const long items = (((long)kp.n_qb * d.B + 7) / 8) * 8 * d.H;
+    const long items = (((long)kp.n_qb * d.B + 15) / 16) * 16 * d.H;
     long grid = items < MLA_GRID ? items : MLA_GRID;
     grid = (grid + 7) / 8 * 8;
     attn_mla_kernel<<<(unsigned)grid, 256, 0, st>>>(kp);
