@@ -61,6 +61,8 @@ hipError_t launch_summary_query(const Dims &d, const void *Q, int L, float *qbar
 hipError_t launch_attn_simple(const AttnArgs &a, hipStream_t st);
 bool attn_mla_supported(const Dims &d);
 hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st);
+bool attn_gqa64_supported(const Dims &d);
+hipError_t launch_attn_gqa64(const AttnArgs &a, hipStream_t st);
 bool attn_gqa_supported(const Dims &d);
 hipError_t launch_attn_gqa(const AttnArgs &a, hipStream_t st);
 bool attn_mfma_supported(const Dims &d);
