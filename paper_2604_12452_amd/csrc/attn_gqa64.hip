@@ -87,18 +87,20 @@ __device__ __forceinline__ int lt_mask(int a, int b) { return (int)((unsigned)a 
 
 // A segment of keys or values as the first three words of a raw buffer descriptor: rows past its end read as zeros.
 struct Seg { unsigned lo, hi, bytes; };
-__device__ __forceinline__ Seg make_seg(const void *p, long bytes)
+__device__ __forceinline__ Seg make_seg(const void *p, unsigned bytes)
 {
     const unsigned long long a = (unsigned long long)p;
-    return Seg{(unsigned)a, (unsigned)(a >> 32) & 0xFFFFu, (unsigned)max(bytes, 0l)};
+    return Seg{(unsigned)a, (unsigned)(a >> 32) & 0xFFFFu, bytes};
 }
 
 // One direct-to-LDS load of 64 x 16 bytes: lane l fetches segment bytes [soff + voff, +16) into LDS bytes
-// [m0 + 16 l, +16).  Inline assembly: the compiler would make every later LDS read wait for a direct-to-LDS load it
-// knows about; ordering is by hand (s_waitcnt vmcnt + workgroup barrier before a stage is read).
-__device__ __forceinline__ void dma_1k(unsigned voff, const int4v &rs, unsigned soff, unsigned m0)
+// [m0_base + M0_ADD + 16 l, +16).  Inline assembly: the compiler would make every later LDS read wait for a
+// direct-to-LDS load it knows about; ordering is by hand (s_waitcnt vmcnt + workgroup barrier before a stage is read).
+template <int M0_ADD>
+__device__ __forceinline__ void dma_1k(unsigned voff, const int4v &rs, unsigned soff, unsigned m0_base)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %3 offen lds" : : "v"(voff), "s"(rs), "s"(m0), "s"(soff) : "memory");
+    asm volatile("s_add_u32 m0, %2, %4\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, %3 offen lds"
+                 : : "v"(voff), "s"(rs), "s"(m0_base), "s"(soff), "n"(M0_ADD) : "scc", "memory");
 }
 
 // Everything one workgroup needs to know about one work item = 64 query rows of the four heads of one head group.
@@ -140,42 +142,100 @@ __device__ __forceinline__ Blk make_blk(const G64Params &kp, int unit, int qb, i
     k.rep_stride = RB;
     k.raw_stride = kp.S * RB;
     const size_t rep_off = ((size_t)k.b * kp.S + s) * kp.m * D, raw_off = ((size_t)k.b * L * kp.S + s) * D;
-    k.rep_k = make_seg(kp.k_rep + rep_off, (long)k.mt_blk_hi * RB);
-    k.rep_v = make_seg(kp.v_rep + rep_off, (long)k.mt_blk_hi * RB);
-    k.raw_k = make_seg(kp.K + raw_off, (long)k.t_last * k.raw_stride + RB);
-    k.raw_v = make_seg(kp.V + raw_off, (long)k.t_last * k.raw_stride + RB);
+    k.rep_k = make_seg(kp.k_rep + rep_off, (unsigned)k.mt_blk_hi * RB);
+    k.rep_v = make_seg(kp.v_rep + rep_off, (unsigned)k.mt_blk_hi * RB);
+    k.raw_k = make_seg(kp.K + raw_off, (unsigned)k.t_last * k.raw_stride + RB);
+    k.raw_v = make_seg(kp.V + raw_off, (unsigned)k.t_last * k.raw_stride + RB);
     return k;
 }
 
-// What a wavefront needs to copy its 16 rows of K and of V of one tile into one stage (all wavefront-uniform).
+// What a wavefront needs to copy its 16 rows of K and of V of one tile into one stage (all wavefront-uniform).  The
+// wavefront's rows are 4*wave + 16q + (0..3), q = 0..3: one load per q and operand.
 struct CopyCtl {
     int4v k_rs, v_rs;
-    unsigned soff, stride4;     // byte offset of the wavefront's first row in the segment; four rows further
+    unsigned soff[4];           // byte offsets of the wavefront's rows 0, 16, 32, 48 (+ 4*wave) in the segment
     unsigned m0;                // LDS address of the wavefront's first K row in the stage
-    int is_rep;                 // mask
+    unsigned stride;            // bytes between rows of the segment
 };
 __device__ __forceinline__ CopyCtl make_copy(const Blk &k, int tc, int sd, int wave, unsigned lds0)
 {
     CopyCtl c;
-    c.is_rep = lt_mask(tc, k.n_rep_tiles);
-    const Seg &ks = c.is_rep ? k.rep_k : k.raw_k, &vs = c.is_rep ? k.rep_v : k.raw_v;
+    const int is_rep = lt_mask(tc, k.n_rep_tiles);
+    const Seg &ks = is_rep ? k.rep_k : k.raw_k, &vs = is_rep ? k.rep_v : k.raw_v;
     c.k_rs = int4v{(int)ks.lo, (int)ks.hi, (int)ks.bytes, RSRC_WORD3};
     c.v_rs = int4v{(int)vs.lo, (int)vs.hi, (int)vs.bytes, RSRC_WORD3};
-    const unsigned stride = c.is_rep ? k.rep_stride : k.raw_stride;
-    const unsigned row0 = (c.is_rep ? tc * BN : k.raw_lo_blk + (tc - k.n_rep_tiles) * BN) + 16 * wave;
-    c.soff = row0 * stride;
-    c.stride4 = 4 * stride;
-    c.m0 = lds0 + sd * STAGE_BYTES + 16 * wave * RB;
+    c.stride = is_rep ? k.rep_stride : k.raw_stride;
+    const unsigned row0 = (is_rep ? tc * BN : k.raw_lo_blk + (tc - k.n_rep_tiles) * BN) + 4 * wave;
+    c.soff[0] = row0 * c.stride;
+    c.soff[1] = c.soff[0] + 16 * c.stride;
+    c.soff[2] = c.soff[1] + 16 * c.stride;
+    c.soff[3] = c.soff[2] + 16 * c.stride;
+    c.m0 = lds0 + sd * STAGE_BYTES + 4 * wave * RB;
     return c;
 }
-// Copy q (0..3: K rows 4q..4q+3 of the wavefront's share; 4..7: the V rows).  Lane l fills slot l&15 of local row
-// l>>4 with the chunk the swizzle assigns to that slot: K chunk ^ (row & 15), V chunk ^ (row & 12), where
-// row & 15 = 4q + (l>>4) -- the 4q enters the lane's byte offset as an exclusive or of bits 6..7.
-__device__ __forceinline__ void issue_copy_part(int q, const CopyCtl &c, unsigned voff_k, unsigned voff_v)
+// make_copy in four steps (STEP 0..3) of a few scalar instructions each, so that the tile loop can deal them out over
+// steps that have issue slots to spare; `sel` carries the descriptor words from step to step.  The empty assembly
+// statements pin each step's results to its place.
+struct CopySel { int is_rep; unsigned k0, k1, k2, v0, v1, v2; };
+template <int STEP>
+__device__ __forceinline__ void copy_step(CopyCtl &c, CopySel &t, const Blk &k, int tc, int wave, unsigned lds0)
 {
-    const int qq = q & 3;
-    if (q < 4) dma_1k(voff_k ^ (qq << 6), c.k_rs, c.soff + qq * c.stride4, c.m0 + qq * 4 * RB);
-    else dma_1k(voff_v ^ (qq << 6), c.v_rs, c.soff + qq * c.stride4, c.m0 + V_OFF + qq * 4 * RB);
+    if constexpr (STEP == 0) {
+        t.is_rep = lt_mask(tc, k.n_rep_tiles);
+        t.k0 = t.is_rep ? k.rep_k.lo : k.raw_k.lo;
+        t.k1 = t.is_rep ? k.rep_k.hi : k.raw_k.hi;
+        t.k2 = t.is_rep ? k.rep_k.bytes : k.raw_k.bytes;
+        LCA_PIN_S(t.is_rep); LCA_PIN_S(t.k0); LCA_PIN_S(t.k1); LCA_PIN_S(t.k2);
+    } else if constexpr (STEP == 1) {
+        t.v0 = t.is_rep ? k.rep_v.lo : k.raw_v.lo;
+        t.v1 = t.is_rep ? k.rep_v.hi : k.raw_v.hi;
+        t.v2 = t.is_rep ? k.rep_v.bytes : k.raw_v.bytes;
+        c.stride = t.is_rep ? k.rep_stride : k.raw_stride;
+        LCA_PIN_S(t.v0); LCA_PIN_S(t.v1); LCA_PIN_S(t.v2); LCA_PIN_S(c.stride);
+    } else if constexpr (STEP == 2) {
+        const unsigned row0 = (t.is_rep ? tc * BN : k.raw_lo_blk + (tc - k.n_rep_tiles) * BN) + 4 * wave;
+        c.soff[0] = row0 * c.stride;
+        c.m0 = lds0 + (tc & (NSTAGE - 1)) * STAGE_BYTES + 4 * wave * RB;
+        LCA_PIN_S(c.soff[0]); LCA_PIN_S(c.m0);
+    } else {
+        const unsigned s16 = 16 * c.stride;
+        c.soff[1] = c.soff[0] + s16;
+        c.soff[2] = c.soff[1] + s16;
+        c.soff[3] = c.soff[2] + s16;
+        LCA_PIN_S(c.soff[1]); LCA_PIN_S(c.soff[2]); LCA_PIN_S(c.soff[3]);
+        c.k_rs = int4v{(int)t.k0, (int)t.k1, (int)t.k2, RSRC_WORD3};
+        c.v_rs = int4v{(int)t.v0, (int)t.v1, (int)t.v2, RSRC_WORD3};
+    }
+}
+// Copy Q (0..3: K rows 16Q + 4*wave + 0..3; 4..7: the V rows).  Lane l fills slot l&15 of row l>>4 of those four with the
+// chunk the swizzle assigns to that slot: K chunk ^ (row & 15), V chunk ^ (row & 12), and row & 15 = 4*wave + (l>>4)
+// whatever Q is, so the lane's byte offset voff_k / voff_v = (l>>4)*stride + 16*chunk is the same for every copy of a tile.
+template <int Q>
+__device__ __forceinline__ void issue_copy_part(const CopyCtl &c, unsigned voff_k, unsigned voff_v)
+{
+    if constexpr (Q < 4) dma_1k<Q * 16 * RB>(voff_k, c.k_rs, c.soff[Q], c.m0);
+    else dma_1k<V_OFF + (Q - 4) * 16 * RB>(voff_v, c.v_rs, c.soff[Q - 4], c.m0);
+}
+template <int Q = 0>
+__device__ __forceinline__ void issue_copy_all(const CopyCtl &c, unsigned voff_k, unsigned voff_v)
+{
+    if constexpr (Q < COPIES) {
+        issue_copy_part<Q>(c, voff_k, voff_v);
+        issue_copy_all<Q + 1>(c, voff_k, voff_v);
+    }
+}
+__device__ __forceinline__ void issue_copy_dyn(int q, const CopyCtl &c, unsigned voff_k, unsigned voff_v)
+{
+    switch (q) {      // q is a constant after unrolling
+    case 0: issue_copy_part<0>(c, voff_k, voff_v); break;
+    case 1: issue_copy_part<1>(c, voff_k, voff_v); break;
+    case 2: issue_copy_part<2>(c, voff_k, voff_v); break;
+    case 3: issue_copy_part<3>(c, voff_k, voff_v); break;
+    case 4: issue_copy_part<4>(c, voff_k, voff_v); break;
+    case 5: issue_copy_part<5>(c, voff_k, voff_v); break;
+    case 6: issue_copy_part<6>(c, voff_k, voff_v); break;
+    default: issue_copy_part<7>(c, voff_k, voff_v); break;
+    }
 }
 
 // Hide the entries of a boundary half-tile that this lane's query row must not see (e0 = first entry of the half).
@@ -297,7 +357,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
         }
     }
     // copy side: lane l moves piece l&15 of local row l>>4 (rows of the representatives are 256 B apart, raw rows S*256)
-    const unsigned chunk_k = (((lane & 15) ^ (lane >> 4)) << 4), chunk_v = (lane & 15) << 4;
+    const unsigned chunk_k = (((lane & 15) ^ (4 * wave + (lane >> 4))) << 4), chunk_v = (((lane & 15) ^ (4 * wave)) << 4);
 
     int kidx = slot, iu, iqb;
     if (!item(kidx, iu, iqb)) return;
@@ -310,10 +370,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
     auto issue_first_copies = [&](const Blk &k) {
         for (int tl = 0; tl < 3; ++tl) {
             const CopyCtl cc = make_copy(k, tl, tl, wave, lds0);
-            const unsigned stride = cc.is_rep ? k.rep_stride : k.raw_stride;
-            const unsigned vk = (lane >> 4) * stride + chunk_k, vv = (lane >> 4) * stride + chunk_v;
-#pragma unroll
-            for (int q = 0; q < COPIES; ++q) issue_copy_part(q, cc, vk, vv);
+            issue_copy_all(cc, (lane >> 4) * cc.stride + chunk_k, (lane >> 4) * cc.stride + chunk_v);
         }
     };
     issue_first_copies(cur);
@@ -344,26 +401,38 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
             Addr a = adr;                // a.k: the stage of the tile whose keys the next chain reads; a.v: one tile behind from mid-iteration on
             auto next_stage = [&](int t) { return (t & (NSTAGE - 1)) == NSTAGE - 1 ? -(NSTAGE - 1) * STAGE_BYTES : STAGE_BYTES; };
 
-            // Softmax of element e = 0..31 of half `par` (row block e&1, accumulator register e>>1): its exponential, its
-            // share of the row sum, and with every second register the rounding of the pair.
-            float keep[2];
-            auto softmax_elem = [&](int par, int e) {
-                const int rb = e & 1, r = e >> 1;
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[par][rb][r], c, nb[rb]));
-                st.l_run[rb] += p;
-                if (r & 1) {
-                    bf16x2 pr = {(__bf16)keep[rb], (__bf16)p};
+            // Softmax of half `par`, element by element: element e = 0..31 is accumulator register 2*(e/4) + e%2 of row
+            // block (e/2)%2, so that two consecutive elements are one bf16 pair of the second product's operand.  Step e
+            // issues the exponential of element e and finishes element e-1 (its share of the row sum and, with every
+            // second element, the rounding of the pair): an instruction that reads an exponential right behind it costs
+            // a wait state, one step later it costs none.  The empty assembly statements pin the work to its place.
+            float p_prev = 0.f, p_prev2 = 0.f;
+            auto softmax_finish = [&](int par, int e) {        // element e, whose exponential is p_prev (and p_prev2 that of e-1)
+                const int rb = (e >> 1) & 1;
+                st.l_run[rb] += p_prev;
+                LCA_PIN_V(st.l_run[rb]);
+                if (e & 1) {
+                    bf16x2 pr = {(__bf16)p_prev2, (__bf16)p_prev};
                     unsigned bits = __builtin_bit_cast(unsigned, pr);
-                    asm volatile("" : "+v"(bits));      // (pins the conversion to this place)
-                    pb[par][rb].p[r >> 1] = __builtin_bit_cast(bf16x2, bits);
-                } else keep[rb] = p;
+                    LCA_PIN_V(bits);
+                    pb[par][rb].p[(e >> 2)] = __builtin_bit_cast(bf16x2, bits);
+                }
+            };
+            auto softmax_step = [&](int par, int e) {
+                const int rb = (e >> 1) & 1, r = 2 * (e >> 2) + (e & 1);
+                float p = __builtin_amdgcn_exp2f(fmaf(s[par][rb][r], c, nb[rb]));
+                if (e > 0) softmax_finish(par, e - 1);
+                LCA_PIN_V(p);           // the exponential belongs to this step too (pinned behind the other work: right behind the
+                                        // exponential the statement would cost a wait state)
+                p_prev2 = p_prev;
+                p_prev = p;
             };
             // The softmax work that follows MFMA m = 0..31 of a slot: none after the first two (the chain that ended just
             // before the slot may still be writing the S^T registers), then one element per MFMA, two after the last two.
             auto softmax_after = [&](int par, int m) {
-                if (m >= 2 && m < 30) softmax_elem(par, m - 2);
-                if (m == 30) { softmax_elem(par, 28); softmax_elem(par, 29); }
-                if (m == 31) { softmax_elem(par, 30); softmax_elem(par, 31); }
+                if (m >= 2 && m < 30) softmax_step(par, m - 2);
+                if (m == 30) { softmax_step(par, 28); softmax_step(par, 29); }
+                if (m == 31) { softmax_step(par, 30); softmax_step(par, 31); softmax_finish(par, 31); }
             };
             // S^T chain step (k-step ks, row block rb) into s[par][rb]; assembly so that the accumulator is a vector
             // register tuple that the vector ALU can read as it is
@@ -407,8 +476,8 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
             // tile a.v points to), softmax of half H (S^T in s[par]), S^T chain of half H+1 into s[1-par] (its keys are half
             // `1-par` of the tile a.k points to).  PV / SM switch parts off at the ends of an item.  In the even slot of an
             // iteration the value addresses move on to the iteration's tile once the update has requested its last
-            // fragment; `cc`: the copy of a later tile rides in the chain part.
-            auto slot_fn = [&](auto par_c, auto pv_c, auto sm_c, auto ch_c, int tile, const CopyCtl *cc, unsigned vk, unsigned vv) {
+            // fragment; `extra(m)` is further work for the step of MFMA m = 0..31.
+            auto slot_fn = [&](auto par_c, auto pv_c, auto sm_c, auto ch_c, int tile, auto extra) {
                 constexpr int par = decltype(par_c)::value;
                 constexpr bool PV = decltype(pv_c)::value, SM = decltype(sm_c)::value, CH = decltype(ch_c)::value;
                 // first part: 16 MFMAs of the O^T update, value fragment i = (kk, dvt) feeds both row blocks
@@ -419,6 +488,8 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
                         LCA_FENCE();
                         // (assembly: keeps O^T in the accumulation registers in every block of the loop)
                         if (PV) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[rb][i % NDV]) : "v"(vf[i % RING]), "v"(pb[1 - par][rb].v[i / NDV]));
+                        LCA_FENCE();        // the MFMA first, then this step's other work (left alone, the scheduler puts every second MFMA
+                                            // behind its step's work, and the matrix core idles between the pairs)
                         if (rb == 1) {
                             if (PV && i + RING < 2 * NDV) vf[i % RING] = load_v(a, 1 - par, i + RING);
                             if (PV && par == 0 && i == 2 * NDV - RING) {       // the last value fragment of tile `tile`-1 is requested
@@ -430,6 +501,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
                             if (CH && i >= 2 * NDV - RING) kf[i % RING] = load_k(a, 1 - par, i - (2 * NDV - RING));
                         }
                         if (SM) softmax_after(par, 2 * i + rb);
+                        extra(2 * i + rb);
                     }
                 }
                 // second part: 16 MFMAs of the S^T chain, key fragment ks feeds both row blocks
@@ -439,13 +511,14 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
                     for (int rb = 0; rb < 2; ++rb) {
                         LCA_FENCE();
                         if (CH) chain_mfma(1 - par, rb, ks, kf[ks % RING]);
+                        LCA_FENCE();
                         if (rb == 1) {
                             if (CH && ks + RING < NKS) kf[ks % RING] = load_k(a, 1 - par, ks + RING);
                             // the next slot's first value fragments: half `par` of the tile the value addresses now point to
                             if (ks >= NKS - RING) vf[ks % RING] = load_v(a, par, ks - (NKS - RING));
                         }
                         if (SM) softmax_after(par, 16 + 2 * ks + rb);
-                        if (cc != nullptr && rb == 0) issue_copy_part(ks, *cc, vk, vv);
+                        extra(16 + 2 * ks + rb);
                     }
                 }
                 LCA_FENCE();
@@ -471,27 +544,45 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
                 constexpr bool FIRST = decltype(first_c)::value;
                 const TileInfo ti = tile_info(T);
                 prepare_half(0, 0, ti);
-                slot_fn(P0(), std::integral_constant<bool, !FIRST>(), Y(), Y(), T, nullptr, 0, 0);     // no half before the first one
-                // the key addresses move on to tile T+1
-                {
-                    const int d = next_stage(T);
-#pragma unroll
-                    for (int ks = 0; ks < NKS; ++ks) a.k[ks] += d;
-                }
-                // the copy of tile T+3 (past the item's last tile: zeros) goes where tile T-1 was
-                const CopyCtl cc = make_copy(cur, T + 3, (T + 3) & (NSTAGE - 1), wave, lds0);
-                const unsigned stride = cc.is_rep ? cur.rep_stride : cur.raw_stride;
-                const unsigned vk = (lane >> 4) * stride + chunk_k, vv = (lane >> 4) * stride + chunk_v;
+                // The even slot also prepares the copy of tile T+3 (past the item's last tile: zeros), which goes where tile T-1
+                // was, in its first steps (they carry no softmax work), and moves the key addresses on to tile T+1 once the
+                // chain has requested its last fragment.
+                CopyCtl cc;
+                CopySel sel;
+                unsigned vk = 0, vv = 0;
+                slot_fn(P0(), std::integral_constant<bool, !FIRST>(), Y(), Y(), T, [&](int m) {      // no half before the first one
+                    switch (m) {
+                    case 0: copy_step<0>(cc, sel, cur, T + 3, wave, lds0); break;
+                    case 1: copy_step<1>(cc, sel, cur, T + 3, wave, lds0); break;
+                    case 2: copy_step<2>(cc, sel, cur, T + 3, wave, lds0); break;
+                    case 3:
+                        copy_step<3>(cc, sel, cur, T + 3, wave, lds0);
+                        vk = (lane >> 4) * cc.stride + chunk_k; vv = (lane >> 4) * cc.stride + chunk_v;
+                        LCA_PIN_V(vk); LCA_PIN_V(vv);
+                        break;
+                    default: break;
+                    }
+                    if (m >= 24 && (m & 1) == 0) {       // steps of k-steps 4..7, row block 0: two key addresses each
+                        const int d = next_stage(T), j = (m - 24);
+                        a.k[j] += d; a.k[j + 1] += d;
+                        LCA_PIN_V(a.k[j]); LCA_PIN_V(a.k[j + 1]);
+                    }
+                });
                 // tile T+1 has landed (tile T+2 may be on its way) and this wavefront's reads of tile T-1 are in registers ...
                 asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"(COPIES) : "memory");
                 __syncthreads();      // ... for every wavefront
                 prepare_half(1, 1, ti);
-                slot_fn(P1(), Y(), Y(), Y(), T, &cc, vk, vv);     // past the last tile its chain runs over stale keys: S^T nobody reads
+                // the odd slot issues the copy in its first steps; past the last tile its chain runs over stale keys: S^T nobody reads
+                slot_fn(P1(), Y(), Y(), Y(), T, [&](int m) {
+                    if (m < COPIES) issue_copy_dyn(m, cc, vk, vv);
+                });
             };
-            iteration(Y(), 0);
+            int t_first = 0;
+            asm volatile("" : "+s"(t_first));    // (opaque: with a known zero the compiler turns the flag arithmetic back into comparisons)
+            iteration(Y(), t_first);
             for (int T = 1; T < cur.n_tiles; ++T) iteration(N(), T);
             // ---- O^T update of the last half ----
-            slot_fn(P0(), Y(), N(), N(), cur.n_tiles, nullptr, 0, 0);
+            slot_fn(P0(), Y(), N(), N(), cur.n_tiles, [](int) {});
 
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the trailing copies have landed before the stages are reused
             float l_tot[2];
@@ -509,10 +600,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
                 m_exact[0] = NEG_BIG; m_exact[1] = NEG_BIG;
                 for (int tl = 0; tl < cur.n_tiles; ++tl) {
                     const CopyCtl cc = make_copy(cur, tl, tl & 1, wave, lds0);
-                    const unsigned stride = cc.is_rep ? cur.rep_stride : cur.raw_stride;
-                    const unsigned vk = (lane >> 4) * stride + chunk_k, vv = (lane >> 4) * stride + chunk_v;
-#pragma unroll
-                    for (int q = 0; q < COPIES; ++q) issue_copy_part(q, cc, vk, vv);
+                    issue_copy_all(cc, (lane >> 4) * cc.stride + chunk_k, (lane >> 4) * cc.stride + chunk_v);
                     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                     __syncthreads();
                     Addr ax = adr;
