@@ -271,9 +271,9 @@ def main():
                                (f"{wl.name}: GQA B={wl.B} L={wl.L} H={wl.H} KV heads={wl.S} d={wl.d_sel} g={wl.g} w={wl.w} bf16, "
                                 f"AR(1) keys/values, RoPE theta {wl.theta:g}; one attention layer"),
                    "step": "lca_condense + lca_prefill_attn"},
-        "roofline": {"bound": "mfma", "kernel": ("attn_mla_kernel" if mla else "attn_gqa_kernel") + " (lca_prefill_attn)", "achieved": tflops,
+        "roofline": {"bound": "mfma", "kernel": ("attn_mla_kernel" if mla else "attn_gqa64_kernel") + " (lca_prefill_attn)", "achieved": tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
-                     "traffic": profiled_traffic(args.config, "attn_mla_kernel" if mla else "attn_gqa_kernel")},
+                     "traffic": profiled_traffic(args.config, "attn_mla_kernel" if mla else "attn_gqa64_kernel")},
         "cpu_baseline": base,
         "extra": extra,
     }

@@ -75,8 +75,13 @@ struct G64Params {
     int B, L, H, S, g, w, m, dense;
     int hgs;            // groups of four query heads per KV head
     int n_qb, n_units;  // query blocks (of 64 rows) per sequence; KV-sharing units = B * S * hgs
+    unsigned g_magic, units_magic, hgs_magic, s_magic;     // for divisions by g, n_units, hgs and S (udiv_small)
     float scale_log2, bias_log2;
 };
+
+// x / d for d >= 1 and x * d < 2^32, with magic = 2^32 / d + 1 (rounded down) from the host: one multiplication instead
+// of the thirty-odd instructions of a 32-bit division (a work item is short enough for a dozen of those to show).
+__device__ __forceinline__ unsigned udiv_small(unsigned x, unsigned d, unsigned magic) { return d == 1 ? x : __umulhi(x, magic); }
 
 __device__ __forceinline__ constexpr int lds_row_of_m(int m) { return (m & 16) + 4 * (m & 3) + 2 * ((m >> 3) & 1) + ((m >> 2) & 1); }
 __device__ __forceinline__ constexpr int acc_entry(int r, int G) { return lds_row_of_m(8 * (r >> 2) + 4 * G + (r & 3)); }
@@ -118,9 +123,10 @@ __device__ __forceinline__ Blk make_blk(const G64Params &kp, int unit, int qb, i
 {
     Blk k;
     const int L = kp.L, g = kp.g, w = kp.w, hps = kp.H / kp.S;
-    auto groups_visible = [&](int t) { return (kp.dense || t + 1 <= w) ? 0 : (t + 1 - w) / g; };
-    const int hg = unit % kp.hgs, s = (unit / kp.hgs) % kp.S;
-    k.b = unit / (kp.hgs * kp.S);
+    auto groups_visible = [&](int t) { return (kp.dense || t + 1 <= w) ? 0 : (int)udiv_small(t + 1 - w, g, kp.g_magic); };
+    const int uq = udiv_small(unit, kp.hgs, kp.hgs_magic), hg = unit - uq * kp.hgs;
+    k.b = udiv_small(uq, kp.S, kp.s_magic);
+    const int s = uq - k.b * kp.S;
     k.h = s * hps + hg * NW + wave;
     k.t0 = qb * BMW;
     k.t_last = min(k.t0 + BMW, L) - 1;
@@ -296,12 +302,18 @@ struct RowState { float m_ref[2], l_run[2]; };
 // first product (lane (n, G) holds Q[row n][16 ks + 8 G .. +7] of each row block) through 8 KB of LDS private to
 // the wavefront, one row block at a time.  Piece p of row r sits at r*256 + ((p ^ r) & 15)*16: no bank conflicts
 // either way.  LDS operations of one wavefront run in order, so nothing has to wait in between.
+// (through a buffer descriptor of the item's rows of this head: one scalar offset per load instead of 64-bit address
+// arithmetic, rows past the end of the sequence read as zeros)
 __device__ __forceinline__ void load_q(const G64Params &kp, const Blk &k, int lane, bf16x8 (&qf)[2][NKS])
 {
+    const int rows_valid = min(max(kp.L - k.t0, 0), BMW);
+    const __amdgpu_buffer_rsrc_t q_rs = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(kp.Q + (((size_t)k.b * kp.L + k.t0) * kp.H + k.h) * D), (short)0, rows_valid > 0 ? ((rows_valid - 1) * kp.H * D + D) * 2 : 0, RSRC_WORD3);
+    const int voff = ((lane >> 4) * kp.H * D + (lane & 15) * 8) * 2;
 #pragma unroll
     for (int i = 0; i < 2 * NKS; ++i) {
-        const int t = min(k.t0 + 4 * i + (lane >> 4), kp.L - 1);
-        qf[i / NKS][i % NKS] = *reinterpret_cast<const bf16x8 *>(kp.Q + (((size_t)k.b * kp.L + t) * kp.H + k.h) * D + (lane & 15) * 8);
+        const uintx4 v = __builtin_amdgcn_raw_buffer_load_b128(q_rs, voff, 4 * i * kp.H * D * 2, 0);
+        qf[i / NKS][i % NKS] = __builtin_bit_cast(bf16x8, v);
     }
 }
 __device__ __forceinline__ void q_to_fragments(char *buf, int lane, bf16x8 (&qf)[2][NKS])
@@ -337,8 +349,9 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
     const int n_items = kp.n_qb * kp.n_units;
     auto item = [&](int kidx, int &unit, int &qb) {           // item kidx of this XCD; false past the end
         const int i = kidx * 8 + xcd;
-        unit = i % kp.n_units;
-        qb = kp.n_qb - 1 - i / kp.n_units;
+        const int iq = udiv_small(i, kp.n_units, kp.units_magic);
+        unit = i - iq * kp.n_units;
+        qb = kp.n_qb - 1 - iq;
         return i < n_items;
     };
 
@@ -690,8 +703,10 @@ bool attn_gqa64_supported(const Dims &d)
 {
     const int hps = d.H / d.S;
     // segment sizes and row offsets travel as 32-bit byte counts
+    // ... and item indices are divided with udiv_small
+    const long n_units = (long)d.B * d.S * (hps / NW), n_items = ((long)d.L + BMW - 1) / BMW * n_units;
     return d.dtype == LCA_BF16 && d.mode == LCA_MODE_GQA && d.d_pool == D && d.d_sel == D && d.scale > 0.f && hps % NW == 0 &&
-           (long)(d.L + 4 * BN) * d.S * RB < (1l << 32);
+           (long)(d.L + 4 * BN) * d.S * RB < (1l << 32) && (n_items + 8 * GRID) * n_units < (1l << 32) && (long)d.L * d.g < (1l << 31);
 }
 
 hipError_t launch_attn_gqa64(const AttnArgs &a, hipStream_t st)
@@ -705,6 +720,8 @@ hipError_t launch_attn_gqa64(const AttnArgs &a, hipStream_t st)
     kp.hgs = d.H / d.S / NW;
     kp.n_qb = (d.L + BMW - 1) / BMW;
     kp.n_units = d.B * d.S * kp.hgs;
+    auto magic = [](int dv) { return dv > 1 ? (unsigned)((1ull << 32) / (unsigned)dv + 1) : 0u; };
+    kp.g_magic = magic(d.g); kp.units_magic = magic(kp.n_units); kp.hgs_magic = magic(kp.hgs); kp.s_magic = magic(d.S);
     kp.scale_log2 = d.scale * 1.4426950408889634f;
     kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
     // persistent grid: one workgroup per CU (a workgroup takes 128 KB of LDS and most of the registers)
