@@ -111,7 +111,9 @@ def decode_bench(wl, lca, hp, torch):
     pool_tail, sel_tail = mk(B, wd.kv_heads, k, wd.d_pool), mk(B, wd.kv_heads, k, wd.d_sel)
     q = mk(B, wd.H, wd.d_qk) * 0.1
     O = torch.empty((B, wd.H, wd.d_pool), dtype=torch.bfloat16, device="cuda")
-    ws = lca.alloc_workspace(desc)
+    wu = wl.with_(B=B, L=wd.w + (m + 1) * wd.g)                     # the next length at which an update is due
+    du = hp.lca_desc(wu)
+    ws = torch.empty(max(lca.workspace_size(desc), lca.workspace_size(du), 256), dtype=torch.uint8, device="cuda")
     ms = time_kernel(lambda: lca.decode_attn(desc, q, pool_rep, sel_rep, pool_tail, sel_tail, O, ws), 20, 3)
     nbytes = B * wd.S * (m + k) * (wd.d_pool + wd.d_sel) * 2
     out = {"B": B, "L": wd.L, "m": m, "k": k, "ms_decode_step": ms, "algorithmic_bytes": nbytes,
@@ -123,8 +125,6 @@ def decode_bench(wl, lca, hp, torch):
     pool_ring, sel_ring = mk(B, wd.kv_heads, k_cap, wd.d_pool), mk(B, wd.kv_heads, k_cap, wd.d_sel)
     out["ms_decode_step_cached"] = time_kernel(
         lambda: lca.decode_attn_cached(desc, lay, q, pool_rep2, sel_rep2, pool_ring, sel_ring, O, ws), 20, 3)
-    wu = wl.with_(B=B, L=wd.w + (m + 1) * wd.g)                     # the next length at which an update is due
-    du = hp.lca_desc(wu)
     q_recent = mk(B, wd.g, wd.H, wd.d_qk) * 0.1
     anchor = torch.zeros((B, wd.S, m_cap), dtype=torch.int32, device="cuda")
     out["ms_cache_update"] = time_kernel(
