@@ -1,4 +1,4 @@
-// bf16 MFMA attention kernel for the GQA widths (d_k = d_v = 128) with four query heads (or a multiple) per KV
+// bf16 MFMA attention kernel for the GQA widths (d_k = d_v = 128) with 1, 2 or a multiple of 4 query heads per KV
 // head, on gfx950: prefill over the condensed context with hard-selected keys and pooled values per KV head
 // (section 5.4 of the paper; attention as in section 4.3, Eq. 10 with the per-query partition of appendix
 // A.2) and, with dense = 1, plain causal attention (section 3, Eq. 5).
@@ -11,7 +11,8 @@
 // every value fragment it reads from LDS feeds two MFMAs.
 //
 // Workgroup = 4 wavefronts = the four query heads of one KV head (of one group of four) x the same 64 query rows:
-// they see exactly the same keys and share every key/value tile.  Tiles of 64 entries (K and V rows of 256 B)
+// they see exactly the same keys and share every key/value tile.  (With 2 or 1 heads per KV head the wavefronts
+// are 2 heads x 2 groups of 64 rows, or 4 groups of 64 rows of one head.)  Tiles of 64 entries (K and V rows of 256 B)
 // are copied by direct-to-LDS loads into four 32 KB stages, three tiles ahead.  Rows sit at a 256-byte stride
 // with their 16-byte chunks XOR-swizzled by row (at the source address of the copy), which keeps both read
 // patterns bank-conflict-free:
@@ -57,8 +58,8 @@ constexpr int RB = D * 2;               // row bytes
 constexpr int V_OFF = BN * RB;          // the value rows of a stage start here
 constexpr int STAGE_BYTES = 2 * BN * RB;   // 32 768
 constexpr int NSTAGE = 4;
-constexpr int NW = 4;                   // wavefronts per workgroup = query heads per work item
-constexpr int BMW = 64;                 // query rows per wavefront and per work item
+constexpr int NW = 4;                   // wavefronts per workgroup
+constexpr int BMW = 64;                 // query rows per wavefront
 constexpr int NKS = D / 16;             // 8 k-steps of S^T
 constexpr int NDV = D / 32;             // 4 value tiles
 constexpr int COPIES = 2 * BN / NW / 4; // direct-to-LDS loads per wavefront and tile: 16 rows of K and of V, 4 rows each
@@ -73,8 +74,8 @@ struct G64Params {
     uint16_t *O;
     float *lse;
     int B, L, H, S, g, w, m, dense;
-    int hgs;            // groups of four query heads per KV head
-    int n_qb, n_units;  // query blocks (of 64 rows) per sequence; KV-sharing units = B * S * hgs
+    int hw, hgs;        // query heads per work item (min(H/S, 4): the wavefronts are hw heads x 4/hw groups of 64 rows); head groups per KV head
+    int n_qb, n_units;  // query blocks (of 256/hw rows) per sequence; KV-sharing units = B * S * hgs
     unsigned g_magic, units_magic, hgs_magic, s_magic;     // for divisions by g, n_units, hgs and S (udiv_small)
     float scale_log2, bias_log2;
 };
@@ -108,13 +109,13 @@ __device__ __forceinline__ void dma_1k(unsigned voff, const int4v &rs, unsigned 
                  : : "v"(voff), "s"(rs), "s"(m0_base), "s"(soff), "n"(M0_ADD) : "scc", "memory");
 }
 
-// Everything one workgroup needs to know about one work item = 64 query rows of the four heads of one head group.
+// Everything one wavefront needs to know about one work item = 256/hw query rows of the hw heads of one head group.
 struct Blk {
-    int b, h, t0, t_last;                    // sequence, this wavefront's query head, first / last query row
+    int b, h, t0, t_last, t_w0;              // sequence, this wavefront's query head, first / last query row of the item, first of the wavefront
     int t_row[2], mt_row[2], raw_lo_row[2];  // per lane and row block: query row, representatives it sees, first raw token it sees
     int raw_lo_blk, mt_blk_hi;               // first raw token / representatives any row of the block sees
     int n_rep_tiles, n_tiles;
-    int rep_full_end, raw_full_lo, raw_full_hi;   // tiles every row sees completely (no masking)
+    int rep_full_end, raw_full_lo, raw_full_hi;   // tiles every row of this wavefront sees completely (no masking)
     Seg rep_k, rep_v, raw_k, raw_v;
     unsigned rep_stride, raw_stride;         // bytes between rows of a segment
 };
@@ -127,23 +128,25 @@ __device__ __forceinline__ Blk make_blk(const G64Params &kp, int unit, int qb, i
     const int uq = udiv_small(unit, kp.hgs, kp.hgs_magic), hg = unit - uq * kp.hgs;
     k.b = udiv_small(uq, kp.S, kp.s_magic);
     const int s = uq - k.b * kp.S;
-    k.h = s * hps + hg * NW + wave;
-    k.t0 = qb * BMW;
-    k.t_last = min(k.t0 + BMW, L) - 1;
+    const int hi = wave & (kp.hw - 1), rg = wave / kp.hw, rows = BMW * (NW / kp.hw);     // hw is 1, 2 or 4
+    k.h = s * hps + hg * kp.hw + hi;
+    k.t0 = qb * rows;
+    k.t_last = min(k.t0 + rows, L) - 1;
+    k.t_w0 = k.t0 + rg * BMW;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-        k.t_row[rb] = k.t0 + 32 * rb + n;
+        k.t_row[rb] = k.t_w0 + 32 * rb + n;
         k.mt_row[rb] = groups_visible(k.t_row[rb]);
         k.raw_lo_row[rb] = k.mt_row[rb] * g;
     }
-    const int mt_lo = groups_visible(k.t0), mt_hi = groups_visible(k.t0 + BMW - 1);
+    const int mt_w_lo = groups_visible(k.t_w0), mt_w_hi = groups_visible(k.t_w0 + BMW - 1);
     k.mt_blk_hi = groups_visible(k.t_last);
-    k.raw_lo_blk = mt_lo * g;
+    k.raw_lo_blk = groups_visible(k.t0) * g;
     k.n_rep_tiles = (k.mt_blk_hi + BN - 1) / BN;
     k.n_tiles = k.n_rep_tiles + (k.t_last + 1 - k.raw_lo_blk + BN - 1) / BN;
-    k.rep_full_end = mt_lo / BN;
-    k.raw_full_lo = k.n_rep_tiles + (mt_hi * g - k.raw_lo_blk + BN - 1) / BN;
-    k.raw_full_hi = k.n_rep_tiles + max(0, (k.t0 + 1 - k.raw_lo_blk) / BN);
+    k.rep_full_end = mt_w_lo / BN;
+    k.raw_full_lo = k.n_rep_tiles + (mt_w_hi * g - k.raw_lo_blk + BN - 1) / BN;
+    k.raw_full_hi = k.n_rep_tiles + max(0, (k.t_w0 + 1 - k.raw_lo_blk) / BN);
     // segments: representatives [B,S,m,128] (row stride 256 B), raw tokens [B,L,S,128] (row stride S*256 B)
     k.rep_stride = RB;
     k.raw_stride = kp.S * RB;
@@ -306,9 +309,9 @@ struct RowState { float m_ref[2], l_run[2]; };
 // arithmetic, rows past the end of the sequence read as zeros)
 __device__ __forceinline__ void load_q(const G64Params &kp, const Blk &k, int lane, bf16x8 (&qf)[2][NKS])
 {
-    const int rows_valid = min(max(kp.L - k.t0, 0), BMW);
+    const int rows_valid = min(max(kp.L - k.t_w0, 0), BMW);
     const __amdgpu_buffer_rsrc_t q_rs = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(kp.Q + (((size_t)k.b * kp.L + k.t0) * kp.H + k.h) * D), (short)0, rows_valid > 0 ? ((rows_valid - 1) * kp.H * D + D) * 2 : 0, RSRC_WORD3);
+        (void *)(kp.Q + (((size_t)k.b * kp.L + k.t_w0) * kp.H + k.h) * D), (short)0, rows_valid > 0 ? ((rows_valid - 1) * kp.H * D + D) * 2 : 0, RSRC_WORD3);
     const int voff = ((lane >> 4) * kp.H * D + (lane & 15) * 8) * 2;
 #pragma unroll
     for (int i = 0; i < 2 * NKS; ++i) {
@@ -643,7 +646,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
         int nu, nqb;
         kidx += n_slots;
         const bool has_next = item(kidx, nu, nqb);
-        const int out_b = cur.b, out_h = cur.h, out_t0 = cur.t0;
+        const int out_b = cur.b, out_h = cur.h, out_t0 = cur.t_w0;
         const int out_t_row[2] = {cur.t_row[0], cur.t_row[1]};
         const float out_m_ref[2] = {st.m_ref[0], st.m_ref[1]};
         float l_tot[2];
@@ -704,8 +707,9 @@ bool attn_gqa64_supported(const Dims &d)
     const int hps = d.H / d.S;
     // segment sizes and row offsets travel as 32-bit byte counts
     // ... and item indices are divided with udiv_small
-    const long n_units = (long)d.B * d.S * (hps / NW), n_items = ((long)d.L + BMW - 1) / BMW * n_units;
-    return d.dtype == LCA_BF16 && d.mode == LCA_MODE_GQA && d.d_pool == D && d.d_sel == D && d.scale > 0.f && hps % NW == 0 &&
+    const int hw = hps < NW ? hps : NW, rows = BMW * (NW / (hw > 0 ? hw : 1));
+    const long n_units = (long)d.B * d.S * (hps / hw), n_items = ((long)d.L + rows - 1) / rows * n_units;
+    return d.dtype == LCA_BF16 && d.mode == LCA_MODE_GQA && d.d_pool == D && d.d_sel == D && d.scale > 0.f && (hps == 1 || hps == 2 || hps % NW == 0) &&
            (long)(d.L + 4 * BN) * d.S * RB < (1l << 32) && (n_items + 8 * GRID) * n_units < (1l << 32) && (long)d.L * d.g < (1l << 31);
 }
 
@@ -717,8 +721,11 @@ hipError_t launch_attn_gqa64(const AttnArgs &a, hipStream_t st)
     kp.k_rep = (const uint16_t *)a.sel_rep; kp.v_rep = (const uint16_t *)a.pool_rep;
     kp.O = (uint16_t *)a.O; kp.lse = a.lse;
     kp.B = d.B; kp.L = d.L; kp.H = d.H; kp.S = d.S; kp.g = d.g; kp.w = d.w; kp.m = d.m; kp.dense = a.dense;
-    kp.hgs = d.H / d.S / NW;
-    kp.n_qb = (d.L + BMW - 1) / BMW;
+    const int hps = d.H / d.S;
+    kp.hw = hps < NW ? hps : NW;
+    kp.hgs = hps / kp.hw;
+    const int rows = BMW * (NW / kp.hw);
+    kp.n_qb = (d.L + rows - 1) / rows;
     kp.n_units = d.B * d.S * kp.hgs;
     auto magic = [](int dv) { return dv > 1 ? (unsigned)((1ull << 32) / (unsigned)dv + 1) : 0u; };
     kp.g_magic = magic(d.g); kp.units_magic = magic(kp.n_units); kp.hgs_magic = magic(kp.hgs); kp.s_magic = magic(d.S);

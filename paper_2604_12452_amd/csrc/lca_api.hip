@@ -98,7 +98,6 @@ lca_status run_attn(const lca::AttnArgs &a, hipStream_t st, const char *what)
 {
     if (lca::attn_mla_supported(a.d)) return hip_status(lca::launch_attn_mla(a, st), what);
     if (lca::attn_gqa64_supported(a.d)) return hip_status(lca::launch_attn_gqa64(a, st), what);
-    if (lca::attn_gqa_supported(a.d)) return hip_status(lca::launch_attn_gqa(a, st), what);
     if (lca::attn_mfma_supported(a.d)) return hip_status(lca::launch_attn_mfma(a, st), what);
     return hip_status(lca::launch_attn_simple(a, st), what);
 }

@@ -63,8 +63,6 @@ bool attn_mla_supported(const Dims &d);
 hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st);
 bool attn_gqa64_supported(const Dims &d);
 hipError_t launch_attn_gqa64(const AttnArgs &a, hipStream_t st);
-bool attn_gqa_supported(const Dims &d);
-hipError_t launch_attn_gqa(const AttnArgs &a, hipStream_t st);
 bool attn_mfma_supported(const Dims &d);
 hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t st);
 bool decode_supported(const Dims &d);

@@ -91,7 +91,7 @@ def test_mla_topic_shift_inputs(oracle):
 @pytest.mark.parametrize("B,L,g,w,H,S", [(1, 700, 16, 100, 8, 2), (1, 300, 8, 0, 4, 4), (1, 129, 16, 64, 4, 1), (2, 515, 16, 32, 4, 2),
                                            (2, 260, 4, 7, 16, 2), (1, 31, 4, 2, 8, 2), (1, 1100, 32, 256, 8, 1), (1, 333, 8, 40, 6, 2)])
 def test_gqa_mfma_small_all_rows(oracle, B, L, g, w, H, S):
-    """Heads per KV head of 1, 2, 4 and 8 run the 128-wide kernel (8 wavefronts = heads x 32-row blocks); 3 heads per
+    """Heads per KV head of 1, 2, 4 and 8 run the 128-wide kernel (4 wavefronts = heads x groups of 64 rows); 3 heads per
     KV head (the last case) is served by the older general MFMA kernel."""
     wl = inputs.Workload("gqa_small", B=B, L=L, H=H, S=S, d_pool=128, d_sel=128, g=g, w=w, dtype="bf16", mode=inputs.MODE_GQA,
                          theta=500000.0, seed=11 + L)
