@@ -71,6 +71,9 @@ def test_cfg1_tiny_fp32_all_rows(oracle, S):
     (128, 16, 16, 1, 1, 1),       # exactly one query block
     (100, 16, 200, 2, 1, 1),      # L < w: no groups
     (33, 2, 3, 1, 1, 1),
+    (1, 1, 0, 1, 1, 1),           # a single token
+    (7, 2, 1, 3, 3, 2),           # fewer rows than a tile, two sequences: segments of a few rows behind one another
+    (40, 4, 4, 4, 2, 3),          # three sequences back to back: nothing may leak across a sequence's end
 ])
 def test_mla_mfma_small_all_rows(oracle, L, g, w, H, S, B):
     wl = inputs.Workload("mla_small", B=B, L=L, H=H, S=S, d_pool=512, d_sel=64, g=g, w=w, dtype="bf16", seed=7 + L)
@@ -89,7 +92,8 @@ def test_mla_topic_shift_inputs(oracle):
 
 # ---- MFMA kernel at the GQA widths (128 / 128) --------------------------------------------------------
 @pytest.mark.parametrize("B,L,g,w,H,S", [(1, 700, 16, 100, 8, 2), (1, 300, 8, 0, 4, 4), (1, 129, 16, 64, 4, 1), (2, 515, 16, 32, 4, 2),
-                                           (2, 260, 4, 7, 16, 2), (1, 31, 4, 2, 8, 2), (1, 1100, 32, 256, 8, 1), (1, 333, 8, 40, 6, 2)])
+                                           (2, 260, 4, 7, 16, 2), (1, 31, 4, 2, 8, 2), (1, 1100, 32, 256, 8, 1), (1, 333, 8, 40, 6, 2),
+                                           (2, 777, 16, 128, 2, 2), (1, 513, 32, 0, 4, 2), (3, 70, 4, 5, 4, 1), (1, 1, 1, 0, 4, 1)])
 def test_gqa_mfma_small_all_rows(oracle, B, L, g, w, H, S):
     """Heads per KV head of 1, 2, 4 and 8 run the 128-wide kernel (4 wavefronts = heads x groups of 64 rows); 3 heads per
     KV head (the last case) is served by the older general MFMA kernel."""
