@@ -555,6 +555,9 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
                 for (int rb = 0; rb < 2; ++rb) chain_mfma(0, rb, ks, kf[ks % RING]);
                 if (ks + RING < NKS) kf[ks % RING] = load_k(a, 0, ks + RING);
             }
+            // the wait states an MFMA result needs before vector instructions may read it (the chains are assembly: the
+            // compiler does not know; inside the loop two MFMAs of the next slot stand between a chain and its readers)
+            asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s[0][0]), "+v"(s[0][1]));
             // ---- iterations: slot 2T, barrier, slot 2T+1 ----
             auto iteration = [&](auto first_c, int T) {
                 constexpr bool FIRST = decltype(first_c)::value;
