@@ -224,6 +224,7 @@ __device__ __forceinline__ void chain_and_softmax(ChainFrags &cf, lds_cptr kb, c
             asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(snext) : "v"(cf.fr[0]), "v"(qf[0]));
         else
             asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(snext) : "v"(cf.fr[ks % CHAIN_DEPTH]), "v"(qf[ks]));
+        LCA_FENCE();        // the MFMA first, then this slot's other work (left alone, the scheduler sometimes puts the MFMA last)
         if (ks + CHAIN_DEPTH < NKS) cf.fr[ks % CHAIN_DEPTH] = chain_frag(kb, ksel, ks + CHAIN_DEPTH);
         if (SOFTMAX) {
             // P^T = exp2(S^T * c + bias - reference), two S^T registers per three slots: an exponential in each of two
@@ -272,6 +273,7 @@ __device__ __forceinline__ void pv_update(PvFrags &f, lds_cptr vp0, const Pb &pb
         LCA_FENCE();
         const bf16x8 a = __builtin_shufflevector(f.lo[buf][i], f.hi[buf][i], 0, 1, 2, 3, 4, 5, 6, 7);
         acc[j >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb.v[j & 1], acc[j >> 1], 0, 0, 0);
+        LCA_FENCE();
         pv_load_step(f, vp0, j + PV_GROUP);
         LCA_FENCE();
         shadow(j);
