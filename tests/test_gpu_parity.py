@@ -80,6 +80,36 @@ def test_mla_mfma_small_all_rows(oracle, L, g, w, H, S, B):
     _full_parity(oracle, wl)
 
 
+def _random_shapes(mode, n, seed):
+    """Seeded draws of valid shapes for the bf16 MFMA kernels: lengths around the tile and block sizes, every group size,
+    windows from none to longer than the sequence, several head ratios."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        L = int(rng.choice([rng.integers(1, 70), rng.integers(60, 140), rng.integers(120, 300), rng.integers(250, 650)]))
+        g = int(rng.choice([1, 2, 3, 4, 8, 16, 32, 64]))
+        w = int(rng.choice([0, 1, rng.integers(0, 40), rng.integers(30, 200), L + 5]))
+        if mode == inputs.MODE_MLA:
+            H, S = [(1, 1), (2, 1), (4, 2), (4, 4), (3, 1)][int(rng.integers(0, 5))]
+        else:
+            H, S = [(4, 1), (8, 2), (2, 2), (4, 2), (8, 1), (2, 1)][int(rng.integers(0, 6))]
+        out.append((L, g, w, H, S, int(rng.integers(1, 3))))
+    return out
+
+
+@pytest.mark.parametrize("L,g,w,H,S,B", _random_shapes(inputs.MODE_MLA, 16, 2024))
+def test_mla_mfma_random_shapes(oracle, L, g, w, H, S, B):
+    wl = inputs.Workload("mla_rand", B=B, L=L, H=H, S=S, d_pool=512, d_sel=64, g=g, w=w, dtype="bf16", seed=1000 + L + 7 * g + w, n_q=min(g, L))
+    _full_parity(oracle, wl)
+
+
+@pytest.mark.parametrize("L,g,w,H,S,B", _random_shapes(inputs.MODE_GQA, 16, 2025))
+def test_gqa_mfma_random_shapes(oracle, L, g, w, H, S, B):
+    wl = inputs.Workload("gqa_rand", B=B, L=L, H=H, S=S, d_pool=128, d_sel=128, g=g, w=w, dtype="bf16", mode=inputs.MODE_GQA,
+                         theta=500000.0, seed=2000 + L + 7 * g + w, n_q=min(g, L))
+    _full_parity(oracle, wl)
+
+
 def test_mla_mfma_multiplicity_bias(oracle):
     wl = inputs.Workload("mla_bias", B=1, L=400, H=2, S=1, d_pool=512, d_sel=64, g=16, w=32, dtype="bf16", seed=5)
     _full_parity(oracle, wl, bias=math.log(16.0), dense=False)
