@@ -233,6 +233,13 @@ def main():
     extra["parity_max_rel_err_sampled_rows"] = float((num / np.maximum(np.abs(O_ref).max(axis=-1), 1e-6)).max())
 
     if not args.no_extra:
+        # context for the MFMA roofline fraction: what the vendor library's plain bf16 GEMM reaches on this chip right now
+        # (the chip clocks down under matrix-core load; no part of the product path)
+        ga = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+        gb = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+        ms_gemm = time_kernel(lambda: torch.matmul(ga, gb), 10, 2)
+        extra["context_library_gemm_bf16_8192_TFLOPs"] = 2.0 * 8192 ** 3 / (ms_gemm * 1e-3) / 1e12
+        del ga, gb
         # in-run dense MLA baseline (same kernel engine, plain causal mask)
         O2 = torch.empty_like(O)
         n_dense = 2 if wl.L > 65536 else 5
