@@ -481,7 +481,8 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st)
     if (decode_mla_supported(a.d)) {     // matrix-core kernel at the MLA widths, then the common merge
         const hipError_t e = launch_decode_mla(a, st);
         if (e != hipSuccess) return e;
-        decode_merge_kernel<uint16_t><<<a.d.B * a.d.H, MERGE_THREADS, a.splits * sizeof(float), st>>>(a.part, (uint16_t *)a.O, a.d.H / a.d.S, a.d.d_pool, a.splits);
+        const int wgs = a.splits / 4;    // one partial result per workgroup of four wavefronts
+        decode_merge_kernel<uint16_t><<<a.d.B * a.d.H, MERGE_THREADS, wgs * sizeof(float), st>>>(a.part, (uint16_t *)a.O, a.d.H / a.d.S, a.d.d_pool, wgs);
         return hipGetLastError();
     }
     switch (shape_id(a.d)) {

@@ -14,8 +14,9 @@
 // the S^T accumulators already are the B fragments of the second product when the transpose reads of a 16-lane
 // block take rows 4 apart (conflict-free on the 1040-byte stride).  Softmax keeps one fixed reference per head
 // (taken at the first tile), so the 128 accumulation registers are never rescaled; if a row sum ends beyond
-// 2^100 the wavefront collects the exact maximum of its range and runs it again.  The wavefronts' partial
-// results (reference, sum, unnormalised output per head) are merged by decode_merge_kernel.
+// 2^100 the wavefront collects the exact maximum of its range and runs it again.  The four wavefronts' results
+// (reference, sum, unnormalised output per head) are merged in LDS into one partial result per workgroup; the
+// workgroups' partial results are merged by decode_merge_kernel.
 #include "lca_internal.h"
 
 namespace lca {
@@ -33,6 +34,8 @@ constexpr int BUF_BYTES = SEL_OFF + BN * DS * 2;   // 37 376 per wavefront
 constexpr int NKS = DQK / 32;                   // 18 k-steps of S^T
 constexpr int NDT = DP / 16;                    // 32 value tiles
 constexpr int PV_GROUP = 8;                     // value tiles whose V^T fragments are requested together
+constexpr int MROW = DP + 4;                    // floats per head of a wavefront's rescaled output in LDS (merge at the end)
+static_assert(16 * MROW * 4 <= BUF_BYTES, "the rescaled output of 16 heads fits a wavefront's tile buffer");
 constexpr float NEG_BIG = -1.0e30f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -59,6 +62,7 @@ __device__ __forceinline__ void dma_lanes(const void *addr, unsigned lds_addr)  
 __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
 {
     __shared__ __attribute__((aligned(1024))) char bufs[4][BUF_BYTES];
+    __shared__ float wave_ml[4][16][2];                                     // (reference, sum) per wavefront and head
 
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 15, q4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -230,18 +234,54 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
         again = true;
     }
 
-    // partial result of this wavefront: (reference, sum, unnormalised output) per head, natural-log units
-    if (col < kp.hps) {
-        float *dst = kp.part + (((size_t)bs * kp.n_parts + part) * kp.hps + col) * (DP + 2);
-        const bool any = t_lo < t_hi;
-        if (q4 == 0) {
-            dst[0] = any ? m_ref * LN2 : -INFINITY;
-            dst[1] = any ? l_tot : 0.f;
+    // The four wavefronts' results (reference, sum, unnormalised output per head) are merged here, through LDS, so that
+    // one partial result per workgroup goes to memory: each wavefront publishes its references and sums, rescales its
+    // accumulators to the common reference into its own (now idle) tile buffer, and then adds up a quarter of the
+    // value columns over the four buffers.
+    const bool any = t_lo < t_hi;
+    if (q4 == 0) {
+        wave_ml[wave][col][0] = any ? m_ref : -INFINITY;
+        wave_ml[wave][col][1] = any ? l_tot : 0.f;
+    }
+    __syncthreads();
+    float m_all = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) m_all = fmaxf(m_all, wave_ml[w][col][0]);
+    float l_all = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const float mw = wave_ml[w][col][0];
+        l_all += mw == -INFINITY ? 0.f : wave_ml[w][col][1] * __builtin_amdgcn_exp2f(mw - m_all);
+    }
+    {
+        const float f = any ? __builtin_amdgcn_exp2f(m_ref - m_all) : 0.f;
+        float *mine = reinterpret_cast<float *>(buf) + col * MROW + 4 * q4;   // [head][MROW] floats, 33 KB of the 36.5 KB buffer
+#pragma unroll
+        for (int t = 0; t < NDT; ++t) {
+            floatx4 v = acc[t];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] = any ? v[r] * f : 0.f;
+            *reinterpret_cast<floatx4 *>(mine + 16 * t) = v;
         }
+    }
+    __syncthreads();
+    // partial result of this workgroup, natural-log units: wavefront w writes value columns [128 w, 128 w + 128) of every head
+    float *dst0 = kp.part + ((size_t)bs * wg_per_bs + blockIdx.x % wg_per_bs) * kp.hps * (DP + 2);
+    for (int h = 0; h < kp.hps; ++h) {
+        const int x = 128 * wave + 2 * lane;
+        float2 sum = float2{0.f, 0.f};
 #pragma unroll
-        for (int t = 0; t < NDT; ++t)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) dst[2 + 16 * t + 4 * q4 + r] = acc[t][r];
+        for (int w = 0; w < 4; ++w) {
+            const float2 v = *reinterpret_cast<const float2 *>(reinterpret_cast<const float *>(bufs[w]) + h * MROW + x);
+            sum.x += v.x;
+            sum.y += v.y;
+        }
+        *reinterpret_cast<float2 *>(dst0 + (size_t)h * (DP + 2) + 2 + x) = sum;
+    }
+    if (wave == 0 && q4 == 0 && col < kp.hps) {
+        float *dst = dst0 + (size_t)col * (DP + 2);
+        dst[0] = m_all == -INFINITY ? -INFINITY : m_all * LN2;
+        dst[1] = l_all;
     }
 }
 
