@@ -113,18 +113,18 @@ def profiled_traffic(config, kernel):
     return None
 
 
-def decode_bench(wl, lca, hp, torch):
+def decode_bench(wl, lca, hp, torch, tdt):
     """One decode step of 32 sequences over their condensed caches (HBM-bound). Cache contents are random
     (torch.randn on the device): only the time matters here, parity is covered by the GPU tests."""
     B = 32
     wd = wl.with_(B=B, L=wl.L + 1)
     desc = hp.lca_desc(wd)
     m, k = wd.m, wd.k
-    mk = lambda *shape: torch.randn(shape, dtype=torch.bfloat16, device="cuda")
+    mk = lambda *shape: torch.randn(shape, dtype=tdt, device="cuda")
     pool_rep, sel_rep = mk(B, wd.S, m, wd.d_pool), mk(B, wd.S, m, wd.d_sel)
     pool_tail, sel_tail = mk(B, wd.kv_heads, k, wd.d_pool), mk(B, wd.kv_heads, k, wd.d_sel)
     q = mk(B, wd.H, wd.d_qk) * 0.1
-    O = torch.empty((B, wd.H, wd.d_pool), dtype=torch.bfloat16, device="cuda")
+    O = torch.empty((B, wd.H, wd.d_pool), dtype=tdt, device="cuda")
     wu = wl.with_(B=B, L=wd.w + (m + 1) * wd.g)                     # the next length at which an update is due
     du = hp.lca_desc(wu)
     ws = torch.empty(max(lca.workspace_size(desc), lca.workspace_size(du), 256), dtype=torch.uint8, device="cuda")
@@ -147,14 +147,14 @@ def decode_bench(wl, lca, hp, torch):
     return out
 
 
-def sweep_bench(wl, args, lca, hp, torch, inputs):
+def sweep_bench(wl, args, lca, hp, torch, inputs, tdt):
     """Speed and cache size over the method's knobs at the workload's shapes (the paper's ablations of the
     pooling strategy, Table 5; of the group size, the window and the number of summary queries, Table 8 and
     the sensitivity figures): one line per setting with condensation and attention time, tokens/s, the
     attention kernel's rate and the bytes of the emitted cache."""
     Q, POOL, SEL = inputs.gen_all(wl)
     run = hp.GpuRun(wl, Q, POOL, SEL)
-    O = torch.empty((wl.B, wl.L, wl.H, wl.d_v), dtype=torch.bfloat16, device="cuda")
+    O = torch.empty((wl.B, wl.L, wl.H, wl.d_v), dtype=tdt, device="cuda")
     names = {lca.REDUCE_WEIGHTED: "weighted", lca.REDUCE_MEAN: "mean", lca.REDUCE_MAXSEL: "maxsel", lca.REDUCE_MAXPOOL: "maxpool"}
     settings = [dict(g=g) for g in (4, 8, 16, 32)] + [dict(w=w) for w in (512, 2048, 4096)] + [dict(n_q=n) for n in (8, 32)]
     settings += [dict(pool_reduce=pr, sel_reduce=sr) for pr, sr in ((lca.REDUCE_MEAN, lca.REDUCE_MEAN), (lca.REDUCE_MAXPOOL, lca.REDUCE_MAXPOOL),
@@ -186,6 +186,8 @@ def main():
     ap.add_argument("--oracle-rows", type=int, default=4096)
     ap.add_argument("--no-extra", action="store_true", help="skip dense baseline and variants (profiling runs)")
     ap.add_argument("--decode-only", action="store_true", help="time only the decode step of 32 sequences over their condensed caches")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
+                    help="16-bit element type of the inputs, the cache and the output (the metric is quoted on bf16)")
     ap.add_argument("--sweep", action="store_true",
                     help="time the prefill over group sizes, windows, numbers of summary queries and pooling strategies instead")
     ap.add_argument("--pmc-calib", action="store_true",
@@ -201,7 +203,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     lca.load()   # fails loudly when liblca.so is missing
-    wl = inputs.configs()[args.config]
+    wl = inputs.configs()[args.config].with_(dtype=args.dtype)
+    tdt = torch.bfloat16 if args.dtype == "bf16" else torch.float16
     if args.pmc_calib:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -209,15 +212,15 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if args.decode_only:
-        dec = decode_bench(wl, lca, hp, torch)
+        dec = decode_bench(wl, lca, hp, torch, tdt)
         print(json.dumps({"metric": f"LCA decode step over the condensed cache ({wl.name})", "value": dec["ms_decode_step"], "unit": "ms",
-                          "n_gpus": 1, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+                          "n_gpus": 1, "higher_is_better": False, "dtype": args.dtype, "data": "synthetic",
                           "roofline": {"bound": "hbm", "kernel": ("decode_mla_kernel" if wl.mode == inputs.MODE_MLA else "decode_gqa_kernel") + " (lca_decode_attn)", "achieved": dec["GBps"], "peak": PEAK_HBM_GBS,
                                        "unit": "GB/s", "frac": dec["frac_of_hbm_peak"], "traffic": None}, "extra": dec}))
         return
     if args.sweep:
         print(json.dumps({"metric": f"LCA prefill over the method's settings ({wl.name} shapes)", "unit": "tokens/s", "n_gpus": 1,
-                          "steps": args.steps, "dtype": "bf16", "data": "synthetic", "sweep": sweep_bench(wl, args, lca, hp, torch, inputs)}))
+                          "steps": args.steps, "dtype": args.dtype, "data": "synthetic", "sweep": sweep_bench(wl, args, lca, hp, torch, inputs, tdt)}))
         return
     t_gen = time.perf_counter()
     Q, POOL, SEL = inputs.gen_all(wl)
@@ -227,7 +230,7 @@ def main():
     d = run.desc
     mla = wl.mode == inputs.MODE_MLA
     run.pool_rep, run.sel_rep, run.anchor, _ = lca.alloc_condensed(d)
-    O = torch.empty((d.B, d.L, d.H, d.d_pool), dtype=torch.bfloat16, device="cuda")
+    O = torch.empty((d.B, d.L, d.H, d.d_pool), dtype=tdt, device="cuda")
 
     def f_cond():
         lca.condense(d, run.Q, run.POOL, run.SEL, run.pool_rep, run.sel_rep, run.anchor, None, run.ws)
@@ -317,17 +320,17 @@ def main():
             del pr, sr, an
 
     if not mla and not args.no_extra:
-        extra["decode"] = decode_bench(wl, lca, hp, torch)
+        extra["decode"] = decode_bench(wl, lca, hp, torch, tdt)
 
     out = {
         "metric": "LCA prefill tokens/s at 128K (MLA, 16 heads) + speedup vs dense MLA" if args.config == "cfg4"
         else f"LCA prefill tokens/s ({wl.name})",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": (f"{wl.name}: B={wl.B} L={wl.L} H={wl.H} d_c={wl.d_pool} d_R={wl.d_sel} g={wl.g} w={wl.w} "
-                                f"S={wl.S} bf16, AR(1) rho=0.9 latents, RoPE keys, Gaussian queries; one attention layer") if mla else
-                               (f"{wl.name}: GQA B={wl.B} L={wl.L} H={wl.H} KV heads={wl.S} d={wl.d_sel} g={wl.g} w={wl.w} bf16, "
+                                f"S={wl.S} {args.dtype}, AR(1) rho=0.9 latents, RoPE keys, Gaussian queries; one attention layer") if mla else
+                               (f"{wl.name}: GQA B={wl.B} L={wl.L} H={wl.H} KV heads={wl.S} d={wl.d_sel} g={wl.g} w={wl.w} {args.dtype}, "
                                 f"AR(1) keys/values, RoPE theta {wl.theta:g}; one attention layer"),
                    "step": "lca_condense + lca_prefill_attn"},
         "roofline": {"bound": "mfma", "kernel": ("attn_mla_kernel" if mla else "attn_gqa64_kernel") + " (lca_prefill_attn)", "achieved": tflops,

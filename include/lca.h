@@ -28,7 +28,7 @@
  *     lca_last_error() gives a thread-local message for the last non-OK status.
  *   - Invalid: NULL required pointer; B, L, H, S, g <= 0; w < 0; H % S != 0; n_q < 0, and n_q > L in
  *     the calls that read the summary queries (lca_condense, lca_cache_update); a dtype or
- *     mode outside the enums; d_pool / d_sel not multiples of 8 (bf16) or 4 (f32) or above 1024;
+ *     mode outside the enums; d_pool / d_sel not multiples of 8 (bf16, f16) or 4 (f32) or above 1024;
  *     g > 64; a reduce strategy outside the enum; workspace too small (LCA_ERR_WORKSPACE).  m = 0 (L < w + g) is valid: lca_condense
  *     writes nothing and lca_prefill_attn equals dense attention (section 4.3, fallback remark).
  */
@@ -51,7 +51,9 @@ typedef enum {
 } lca_status;
 
 typedef enum { LCA_MODE_MLA = 0, LCA_MODE_GQA = 1 } lca_mode;
-typedef enum { LCA_BF16 = 0, LCA_F32 = 1 } lca_dtype;
+/* Element type of Q, POOL, SEL, the representatives and O.  The two 16-bit types are the ones the paper's
+ * implementation is written for (limitations section); products are accumulated in fp32 for all three. */
+typedef enum { LCA_BF16 = 0, LCA_F32 = 1, LCA_F16 = 2 } lca_dtype;
 
 /*
  * How the g vectors of a group become the representative's component (the ablation of section 5.4,

@@ -1,4 +1,4 @@
-// bf16 MFMA attention kernel for the GQA widths (d_k = d_v = 128) with 1, 2 or a multiple of 4 query heads per KV
+// bf16 / fp16 MFMA attention kernel for the GQA widths (d_k = d_v = 128) with 1, 2 or a multiple of 4 query heads per KV
 // head, on gfx950: prefill over the condensed context with hard-selected keys and pooled values per KV head
 // (section 5.4 of the paper; attention as in section 4.3, Eq. 10 with the per-query partition of appendix
 // A.2) and, with dense = 1, plain causal attention (section 3, Eq. 5).
@@ -46,6 +46,11 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef int int4v __attribute__((ext_vector_type(4)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+// fp16 runs through the same code (template parameter F16): fragments travel in the bf16 vector types as plain 16-bit
+// containers, and only the matrix instructions, the two conversions (P^T, output) and the softmax range differ.
 union Pb { bf16x8 v[2]; bf16x2 p[8]; };     // P^T of one half and row block: the B operands of the two k-steps of the second product
 
 #define LCA_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -67,6 +72,12 @@ constexpr int GRID = 256;               // workgroups of the persistent kernel =
 constexpr int RING = 4;                 // fragments in flight per operand
 constexpr float NEG_BIG = -1.0e30f;
 constexpr float L_LIMIT = 0x1p90f;      // a row sum beyond this (or not finite) makes the workgroup repeat the item from exact maxima
+// fp16 ends at 65504: the fp16 kernels keep the largest exponential of each row (one v_max3 per pair) and repeat the item
+// from exact maxima if it left the type's range.  The reference sits 4 binades above the first maximum a row sees
+// (first entries at 2^-4): later logits may be 2^19 times larger before that happens, at the price of 4 of fp16's 24
+// binades at the bottom.
+constexpr float P_LIMIT_F16 = 65000.f;
+constexpr float REF_SHIFT_F16 = 4.f;
 constexpr int RSRC_WORD3 = 0x00020000;  // raw buffer of dwords, gfx9 layout
 
 struct G64Params {
@@ -298,7 +309,7 @@ __device__ __forceinline__ bf16x8 load_v(const Addr &a, int half, int i)
 }
 
 // per-lane softmax state of the two query rows (base-2 logits)
-struct RowState { float m_ref[2], l_run[2]; };
+struct RowState { float m_ref[2], l_run[2], p_max[2]; };      // p_max, fp16 only: the largest exponential of the row so far
 
 // Queries of a work item: the loads are issued row-wise -- load i: lane l fetches the 16-byte piece l&15 of row
 // 4i + (l>>4), four whole rows per instruction -- and q_to_fragments turns the registers into the fragments of the
@@ -338,6 +349,7 @@ __device__ __forceinline__ void q_to_fragments(char *buf, int lane, bf16x8 (&qf)
 // placement) and is slot w/8 of that XCD.  Items are numbered (query block, heaviest first) x (unit = sequence x KV
 // head x head group) and item i belongs to XCD i%8: with a multiple of eight units every unit keeps to one XCD, whose
 // L2 then holds that KV head's representatives and the sliding raw window.
+template <bool F16>
 __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params kp)
 {
     __shared__ __attribute__((aligned(1024))) char stages[NSTAGE][STAGE_BYTES];
@@ -407,7 +419,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
 #pragma unroll
                     for (int i = 0; i < NDV; ++i) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc[rb][i]) : "v"(zf));
             }
-            st.m_ref[0] = m_exact[0]; st.m_ref[1] = m_exact[1]; st.l_run[0] = 0.f; st.l_run[1] = 0.f;
+            st.m_ref[0] = m_exact[0]; st.m_ref[1] = m_exact[1]; st.l_run[0] = 0.f; st.l_run[1] = 0.f; st.p_max[0] = 0.f; st.p_max[1] = 0.f;
             bool need_ref = pass == 0;
 
             floatx16 s[2][2];            // S^T of half H and row block rb lives in s[H % 2][rb]
@@ -428,8 +440,10 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
                 st.l_run[rb] += p_prev;
                 LCA_PIN_V(st.l_run[rb]);
                 if (e & 1) {
-                    bf16x2 pr = {(__bf16)p_prev2, (__bf16)p_prev};
-                    unsigned bits = __builtin_bit_cast(unsigned, pr);
+                    if (F16) asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(st.p_max[rb]) : "v"(p_prev2), "v"(p_prev));
+                    unsigned bits;
+                    if (F16) bits = __builtin_bit_cast(unsigned, f16x2{(_Float16)p_prev2, (_Float16)p_prev});
+                    else bits = __builtin_bit_cast(unsigned, bf16x2{(__bf16)p_prev2, (__bf16)p_prev});
                     LCA_PIN_V(bits);
                     pb[par][rb].p[(e >> 2)] = __builtin_bit_cast(bf16x2, bits);
                 }
@@ -453,8 +467,13 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
             // S^T chain step (k-step ks, row block rb) into s[par][rb]; assembly so that the accumulator is a vector
             // register tuple that the vector ALU can read as it is
             auto chain_mfma = [&](int par, int rb, int ks, const bf16x8 &kfrag) {
-                if (ks == 0) asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s[par][rb]) : "v"(kfrag), "v"(qf[rb][ks]));
-                else asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s[par][rb]) : "v"(kfrag), "v"(qf[rb][ks]));
+                if (F16) {
+                    if (ks == 0) asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(s[par][rb]) : "v"(kfrag), "v"(qf[rb][ks]));
+                    else asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(s[par][rb]) : "v"(kfrag), "v"(qf[rb][ks]));
+                } else {
+                    if (ks == 0) asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s[par][rb]) : "v"(kfrag), "v"(qf[rb][ks]));
+                    else asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s[par][rb]) : "v"(kfrag), "v"(qf[rb][ks]));
+                }
             };
 
             // How tile tl is treated (wavefront-uniform): segment, first entry, whether nothing has to be masked
@@ -479,7 +498,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
                         if (ti.full == 0) mask_half(s[par][rb], ti.is_rep != 0, cur.mt_row[rb], cur.raw_lo_row[rb], cur.t_row[rb], ti.e0 + 32 * half, G);
                         if (need_ref) {
                             const float mx = row_max(s[par][rb], c, ti.bias);
-                            st.m_ref[rb] = (st.m_ref[rb] == NEG_BIG) ? mx : st.m_ref[rb];
+                            st.m_ref[rb] = (st.m_ref[rb] == NEG_BIG) ? (F16 ? mx + REF_SHIFT_F16 : mx) : st.m_ref[rb];    // (-1e30 + 4 is -1e30)
                         }
                     }
                     if (need_ref) need_ref = __builtin_amdgcn_ballot_w64((st.m_ref[0] == NEG_BIG) | (st.m_ref[1] == NEG_BIG)) != 0;
@@ -503,7 +522,8 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
                     for (int rb = 0; rb < 2; ++rb) {
                         LCA_FENCE();
                         // (assembly: keeps O^T in the accumulation registers in every block of the loop)
-                        if (PV) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[rb][i % NDV]) : "v"(vf[i % RING]), "v"(pb[1 - par][rb].v[i / NDV]));
+                        if (PV && F16) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc[rb][i % NDV]) : "v"(vf[i % RING]), "v"(pb[1 - par][rb].v[i / NDV]));
+                        if (PV && !F16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[rb][i % NDV]) : "v"(vf[i % RING]), "v"(pb[1 - par][rb].v[i / NDV]));
                         LCA_FENCE();        // the MFMA first, then this step's other work (left alone, the scheduler puts every second MFMA
                                             // behind its step's work, and the matrix core idles between the pairs)
                         if (rb == 1) {
@@ -609,7 +629,7 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb) {
                 l_tot[rb] = st.l_run[rb] + __shfl_xor(st.l_run[rb], 32, 64);
-                redo |= !(l_tot[rb] <= L_LIMIT);
+                redo |= !(l_tot[rb] <= L_LIMIT) | (F16 && st.p_max[rb] > P_LIMIT_F16);
             }
             // every wavefront is done with the stages; repeat the item if a row sum ran out of range
             if (!__syncthreads_or(pass == 0 && redo)) break;
@@ -634,7 +654,10 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
 #pragma unroll
                             for (int r = 0; r < 16; ++r) sv[r] = 0.f;
 #pragma unroll
-                            for (int ks = 0; ks < NKS; ++ks) sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_k(ax, half, ks), qf[rb][ks], sv, 0, 0, 0);
+                            for (int ks = 0; ks < NKS; ++ks) {
+                                if (F16) sv = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, load_k(ax, half, ks)), __builtin_bit_cast(f16x8, qf[rb][ks]), sv, 0, 0, 0);
+                                else sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_k(ax, half, ks), qf[rb][ks], sv, 0, 0, 0);
+                            }
                             mask_half(sv, ti.is_rep != 0, cur.mt_row[rb], cur.raw_lo_row[rb], cur.t_row[rb], ti.e0 + 32 * half, G);
                             m_exact[rb] = fmaxf(m_exact[rb], row_max(sv, c, ti.bias));
                         }
@@ -679,9 +702,12 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
                 for (int d2 = 0; d2 < 2; ++d2)
 #pragma unroll
                     for (int r4 = 0; r4 < 4; ++r4) {
-                        union { bf16x4 h; uint2 u; } o;
+                        union { bf16x4 h; f16x4 hf; uint2 u; } o;
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) o.h[i] = (__bf16)(acc[rb][ch * 2 + d2][r4 * 4 + i] * inv);
+                        for (int i = 0; i < 4; ++i) {
+                            if (F16) o.hf[i] = (_Float16)(acc[rb][ch * 2 + d2][r4 * 4 + i] * inv);
+                            else o.h[i] = (__bf16)(acc[rb][ch * 2 + d2][r4 * 4 + i] * inv);
+                        }
                         *reinterpret_cast<uint2 *>(obuf + n * ORS + (d2 * 32 + 8 * r4 + 4 * G) * 2) = o.u;
                     }
                 __builtin_amdgcn_wave_barrier();
@@ -712,7 +738,7 @@ bool attn_gqa64_supported(const Dims &d)
     // ... and item indices are divided with udiv_small
     const int hw = hps < NW ? hps : NW, rows = BMW * (NW / (hw > 0 ? hw : 1));
     const long n_units = (long)d.B * d.S * (hps / hw), n_items = ((long)d.L + rows - 1) / rows * n_units;
-    return d.dtype == LCA_BF16 && d.mode == LCA_MODE_GQA && d.d_pool == D && d.d_sel == D && d.scale > 0.f && (hps == 1 || hps == 2 || hps % NW == 0) &&
+    return (d.dtype == LCA_BF16 || d.dtype == LCA_F16) && d.mode == LCA_MODE_GQA && d.d_pool == D && d.d_sel == D && d.scale > 0.f && (hps == 1 || hps == 2 || hps % NW == 0) &&
            (long)(d.L + 4 * BN) * d.S * RB < (1l << 32) && (n_items + 8 * GRID) * n_units < (1l << 32) && (long)d.L * d.g < (1l << 31);
 }
 
@@ -738,7 +764,10 @@ hipError_t launch_attn_gqa64(const AttnArgs &a, hipStream_t st)
     const long items = (long)kp.n_qb * kp.n_units;
     long grid = items < GRID ? items : GRID;
     grid = (grid + 7) / 8 * 8;
-    attn_gqa64_kernel<<<(unsigned)grid, 64 * NW, 0, st>>>(kp);
+    if (d.dtype == LCA_F16)
+        attn_gqa64_kernel<true><<<(unsigned)grid, 64 * NW, 0, st>>>(kp);
+    else
+        attn_gqa64_kernel<false><<<(unsigned)grid, 64 * NW, 0, st>>>(kp);
     return hipGetLastError();
 }
 

@@ -1,4 +1,4 @@
-// bf16 MFMA attention kernel for the MLA widths (d_c = 512, d_R = 64) on gfx950: prefill over the
+// bf16 / fp16 MFMA attention kernel for the MLA widths (d_c = 512, d_R = 64) on gfx950: prefill over the
 // condensed context (section 4.3, Eq. 10; per-query partition of appendix A.2) and, with dense = 1,
 // plain causal attention in absorbed form (section 3, Eq. 5).
 //
@@ -45,6 +45,11 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+// fp16 runs through the same code (template parameter F16): fragments travel in the bf16 vector types as plain 16-bit
+// containers, and only the matrix instructions, the two conversions (P^T, output) and the softmax range differ.
 union Pb { bf16x8 v[2]; bf16x2 p[8]; };     // P^T of one tile: the B operands of the two k-steps of the second product
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef int int4v __attribute__((ext_vector_type(4)));
@@ -69,6 +74,12 @@ constexpr int CHAIN_DEPTH = LCA_CHAIN_DEPTH;   // key fragments in flight ahead 
 constexpr int MLA_GRID = 256;            // workgroups of the persistent kernel = CUs of the chip
 constexpr float NEG_BIG = -1.0e30f;     // stands for -inf in running maxima (keeps exp2 arguments finite)
 constexpr float L_LIMIT = 0x1p90f;      // a row sum beyond this (or not finite) makes the workgroup repeat the item from exact maxima
+// fp16 ends at 65504: the fp16 kernels keep the largest exponential of each row (one v_max3 per pair) and repeat the item
+// from exact maxima if it left the type's range.  The reference sits 4 binades above the first maximum a row sees
+// (first entries at 2^-4): later logits may be 2^19 times larger before that happens, at the price of 4 of fp16's 24
+// binades at the bottom.
+constexpr float P_LIMIT_F16 = 65000.f;
+constexpr float REF_SHIFT_F16 = 4.f;
 
 struct MlaParams {
     const uint16_t *Q, *POOL, *SEL, *pool_rep, *sel_rep;
@@ -87,6 +98,7 @@ __device__ __forceinline__ constexpr int acc_entry(int r, int G) { return lds_ro
 // per-lane softmax state (base-2 logits): reference and running sum over this lane's keys
 struct RowState {
     float m_ref, l_run;
+    float p_max;        // fp16 only: the largest exponential of the row so far
 };
 
 // Fragments of the V^T operand: a ring of 2*PV_GROUP steps, requested PV_GROUP steps ahead of their use.
@@ -211,7 +223,7 @@ __device__ __forceinline__ void chain_prefetch(ChainFrags &cf, lds_cptr kb, cons
 #pragma unroll
     for (int i = 0; i < CHAIN_DEPTH; ++i) cf.fr[i] = chain_frag(kb, ksel, i);
 }
-template <bool SOFTMAX, bool PIPELINED>
+template <bool SOFTMAX, bool PIPELINED, bool F16>
 __device__ __forceinline__ void chain_and_softmax(ChainFrags &cf, lds_cptr kb, const KSel &ksel, const bf16x8 (&qf)[NKS], floatx16 &snext,
                                                   const floatx16 &scur, Pb &pb, RowState &st, float c, float bias, PvFrags &pvf,
                                                   lds_cptr vp0, const CopyCtl &cc, unsigned voff_pool, unsigned voff_sel)
@@ -220,10 +232,13 @@ __device__ __forceinline__ void chain_and_softmax(ChainFrags &cf, lds_cptr kb, c
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
         LCA_FENCE();
-        if (ks == 0)
-            asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(snext) : "v"(cf.fr[0]), "v"(qf[0]));
-        else
-            asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(snext) : "v"(cf.fr[ks % CHAIN_DEPTH]), "v"(qf[ks]));
+        if (ks == 0) {
+            if (F16) asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(snext) : "v"(cf.fr[0]), "v"(qf[0]));
+            else asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(snext) : "v"(cf.fr[0]), "v"(qf[0]));
+        } else {
+            if (F16) asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(snext) : "v"(cf.fr[ks % CHAIN_DEPTH]), "v"(qf[ks]));
+            else asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(snext) : "v"(cf.fr[ks % CHAIN_DEPTH]), "v"(qf[ks]));
+        }
         LCA_FENCE();        // the MFMA first, then this slot's other work (left alone, the scheduler sometimes puts the MFMA last)
         if (ks + CHAIN_DEPTH < NKS) cf.fr[ks % CHAIN_DEPTH] = chain_frag(kb, ksel, ks + CHAIN_DEPTH);
         if (SOFTMAX) {
@@ -236,11 +251,12 @@ __device__ __forceinline__ void chain_and_softmax(ChainFrags &cf, lds_cptr kb, c
                 const int k = ks / 3, sub = ks % 3;
                 if (sub < 2) pf[sub] = __builtin_amdgcn_exp2f(fmaf(scur[2 * k + sub], c, nb));
                 else {
-                    bf16x2 pr = {(__bf16)pf[0], (__bf16)pf[1]};
-                    unsigned bits = __builtin_bit_cast(unsigned, pr);
+                    unsigned bits;
+                    if (F16) bits = __builtin_bit_cast(unsigned, f16x2{(_Float16)pf[0], (_Float16)pf[1]});
+                    else bits = __builtin_bit_cast(unsigned, bf16x2{(__bf16)pf[0], (__bf16)pf[1]});
                     asm volatile("" : "+v"(bits));      // (pins the conversion to this slot: the compiler would gather four of them where the fragment is complete)
-                    pr = __builtin_bit_cast(bf16x2, bits);
-                    pb.p[k] = pr;
+                    pb.p[k] = __builtin_bit_cast(bf16x2, bits);
+                    if (F16) asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(st.p_max) : "v"(pf[0]), "v"(pf[1]));
                     st.l_run += pf[0];       // (two plain additions: v_dot2c_f32_bf16 stalls next to MFMAs, about 25 cycles each)
                     st.l_run += pf[1];
                 }
@@ -264,7 +280,13 @@ static_assert((PV_NGROUPS & 1) == 0, "the held-back group must sit in buffer 1")
 // tile's stage; the V^T fragments of the first PV_GROUP steps are already on their way, every step requests the
 // fragment of the step PV_GROUP later.  `shadow(j)` is work for the issue slots that the MFMAs leave free.  The
 // last group's fragments are left in buffer 1 for pv_tail.
-template <class Shadow>
+template <bool F16>
+__device__ __forceinline__ floatx16 pv_mfma(const bf16x8 &a, const bf16x8 &b, const floatx16 &c)
+{
+    if (F16) return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+template <bool F16, class Shadow>
 __device__ __forceinline__ void pv_update(PvFrags &f, lds_cptr vp0, const Pb &pb, floatx16 (&acc)[NDV], Shadow shadow)
 {
 #pragma unroll
@@ -272,7 +294,7 @@ __device__ __forceinline__ void pv_update(PvFrags &f, lds_cptr vp0, const Pb &pb
         const int grp = j / PV_GROUP, i = j % PV_GROUP, buf = grp & 1;
         LCA_FENCE();
         const bf16x8 a = __builtin_shufflevector(f.lo[buf][i], f.hi[buf][i], 0, 1, 2, 3, 4, 5, 6, 7);
-        acc[j >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb.v[j & 1], acc[j >> 1], 0, 0, 0);
+        acc[j >> 1] = pv_mfma<F16>(a, pb.v[j & 1], acc[j >> 1]);
         LCA_FENCE();
         pv_load_step(f, vp0, j + PV_GROUP);
         LCA_FENCE();
@@ -282,6 +304,7 @@ __device__ __forceinline__ void pv_update(PvFrags &f, lds_cptr vp0, const Pb &pb
 }
 // The held-back steps of the previous tile's O^T update: their fragments are in registers, so they run while
 // the first key fragments of the next S^T chain travel from LDS.
+template <bool F16>
 __device__ __forceinline__ void pv_tail(const PvFrags &f, const Pb &pb, floatx16 (&acc)[NDV])
 {
 #pragma unroll
@@ -289,7 +312,7 @@ __device__ __forceinline__ void pv_tail(const PvFrags &f, const Pb &pb, floatx16
         const int i = j % PV_GROUP;
         LCA_FENCE();
         const bf16x8 a = __builtin_shufflevector(f.lo[1][i], f.hi[1][i], 0, 1, 2, 3, 4, 5, 6, 7);
-        acc[j >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb.v[j & 1], acc[j >> 1], 0, 0, 0);
+        acc[j >> 1] = pv_mfma<F16>(a, pb.v[j & 1], acc[j >> 1]);
     }
     LCA_FENCE();
 }
@@ -519,6 +542,7 @@ __device__ __forceinline__ float row_max(const floatx16 &sv, float c, float bias
 // (while the first key fragments of tile tl+1 arrive), the S^T chain of tile tl+1 with the softmax of tile tl
 // in its shadow and the copy of tile tl+3 in its last slots, then the O^T update of tile tl with the loop's
 // bookkeeping for iteration tl+1 in its shadow.
+template <bool F16>
 __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
 {
     __shared__ __attribute__((aligned(1024))) char stages[NSTAGE][STAGE_BYTES];
@@ -577,9 +601,9 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
             bf16x8 zf = {0, 0, 0, 0, 0, 0, 0, 0};
             asm volatile("" : "+v"(zf));
 #pragma unroll
-            for (int i = 0; i < NDV; ++i) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc[i]) : "v"(zf));
+            for (int i = 0; i < NDV; ++i) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc[i]) : "v"(zf));   // (zeros in either type)
         }
-        st.m_ref = m_exact; st.l_run = 0.f;
+        st.m_ref = m_exact; st.l_run = 0.f; st.p_max = 0.f;
         bool need_ref = pass == 0;          // wave-uniform: some row of this wavefront has no reference yet
 
         // the first tiles and the queries of this item are on their way; then the S^T chain of tile 0
@@ -597,7 +621,7 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
             lds_cptr s0 = (lds_cptr)(uintptr_t)lds0;
             const KSel ks0 = make_ksel(lds0 + ksel_off);
             chain_prefetch(cf, s0 + k_off, ks0);
-            chain_and_softmax<false, false>(cf, s0 + k_off, ks0, qf, snext, snext, pb, st, c, 0.f, pvf, s0, CopyCtl(), 0, 0);
+            chain_and_softmax<false, false, F16>(cf, s0 + k_off, ks0, qf, snext, snext, pb, st, c, 0.f, pvf, s0, CopyCtl(), 0, 0);
         }
         scur = snext;
         int tl0 = 0;
@@ -609,7 +633,7 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
                 if (ctl.full == 0) mask_tile(scur, cur, ctl.is_rep != 0, ctl.is_rep ? tl * BN : cur.raw_lo_blk + (tl - cur.n_rep_tiles) * BN, G);
                 if (need_ref) {              // the first visible entries of a row fix its reference
                     const float mx = row_max(scur, c, ctl.bias);
-                    st.m_ref = (st.m_ref == NEG_BIG) ? mx : st.m_ref;
+                    st.m_ref = (st.m_ref == NEG_BIG) ? (F16 ? mx + REF_SHIFT_F16 : mx) : st.m_ref;    // (-1e30 + 4 is -1e30)
                     need_ref = __builtin_amdgcn_ballot_w64(st.m_ref == NEG_BIG) != 0;
                 }
             }
@@ -619,12 +643,12 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
             __syncthreads();      // ... for every wavefront, and every wavefront is done with tile tl-1 (all of its V^T fragments are in registers)
             LCA_FENCE();
             chain_prefetch(cf, ctl.kb, ctl.ksel);
-            pv_tail(pvf, pb, acc);
-            chain_and_softmax<true, true>(cf,
+            pv_tail<F16>(pvf, pb, acc);
+            chain_and_softmax<true, true, F16>(cf,
                                           ctl.kb, ctl.ksel, qf, snext, scur, pb, st, c, ctl.bias, pvf, ctl.vp0, ctl.cc, voff_pool, voff_sel);
             Ctl nx;
             CtlTmp tmp;
-            pv_update(pvf, ctl.vp0, pb, acc, [&](int j) {
+            pv_update<F16>(pvf, ctl.vp0, pb, acc, [&](int j) {
                 // Nothing may read the chain's result before MFMAs of the O^T update have run (the compiler takes an
                 // inline-assembly result as ready at once; these MFMAs are the wait states it actually needs).
                 if (j >= 4 && j < 20) asm volatile("v_mov_b32 %0, %1" : "=v"(scur[j - 4]) : "v"(snext[j - 4]));
@@ -644,12 +668,12 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
             });
             ctl = nx;
         }
-        pv_tail(pvf, pb, acc);                             // the last tile's held-back MFMAs
+        pv_tail<F16>(pvf, pb, acc);                        // the last tile's held-back MFMAs
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the trailing copies have landed before the stages are reused
         // every wavefront is done with the tile stages; repeat the item if a row sum ran out of range
         {
             const float l_chk = st.l_run + __shfl_xor(st.l_run, 32, 64);
-            const bool redo = pass == 0 && !(l_chk <= L_LIMIT);
+            const bool redo = pass == 0 && (!(l_chk <= L_LIMIT) | (F16 && st.p_max > P_LIMIT_F16));
             if (!__syncthreads_or(redo)) break;
             {
                 // exact row maxima, one tile at a time (no overlap: this path is rare): tile tl goes into stage tl%2
@@ -666,7 +690,7 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
                     PvFrags unused;
                     const KSel ksp = make_ksel(lds0 + (tl & 1) * STAGE_BYTES + ksel_off);
                     chain_prefetch(cf, sp + k_off, ksp);
-                    chain_and_softmax<false, false>(cf, sp + k_off, ksp, qf, sv, sv, pb, st, c, 0.f, unused, sp, CopyCtl(), 0, 0);
+                    chain_and_softmax<false, false, F16>(cf, sp + k_off, ksp, qf, sv, sv, pb, st, c, 0.f, unused, sp, CopyCtl(), 0, 0);
                     const bool is_rep = tl < cur.n_rep_tiles;
                     mask_tile(sv, cur, is_rep, is_rep ? tl * BN : cur.raw_lo_blk + (tl - cur.n_rep_tiles) * BN, G);
                     m_exact = fmaxf(m_exact, row_max(sv, c, is_rep ? kp.bias_log2 : 0.f));
@@ -710,9 +734,12 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
             for (int d4 = 0; d4 < 4; ++d4)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    union { bf16x4 h; uint2 u; } o;
+                    union { bf16x4 h; f16x4 hf; uint2 u; } o;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) o.h[i] = (__bf16)(acc[pass * 4 + d4][r4 * 4 + i] * inv);
+                    for (int i = 0; i < 4; ++i) {
+                        if (F16) o.hf[i] = (_Float16)(acc[pass * 4 + d4][r4 * 4 + i] * inv);
+                        else o.h[i] = (__bf16)(acc[pass * 4 + d4][r4 * 4 + i] * inv);
+                    }
                     *reinterpret_cast<uint2 *>(obuf + n * ORS + (d4 * 32 + 8 * r4 + 4 * G) * 2) = o.u;
                 }
             __builtin_amdgcn_wave_barrier();
@@ -739,7 +766,7 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
 bool attn_mla_supported(const Dims &d)
 {
     // segment sizes and row offsets travel as 32-bit byte counts
-    return d.dtype == LCA_BF16 && d.mode == LCA_MODE_MLA && d.d_pool == DP && d.d_sel == DS && d.scale > 0.f && d.L <= (1 << 21);
+    return (d.dtype == LCA_BF16 || d.dtype == LCA_F16) && d.mode == LCA_MODE_MLA && d.d_pool == DP && d.d_sel == DS && d.scale > 0.f && d.L <= (1 << 21);
 }
 
 hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st)
@@ -757,7 +784,10 @@ hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st)
     const long items = (((long)kp.n_qb * d.B + 15) / 16) * 16 * d.H;
     long grid = items < MLA_GRID ? items : MLA_GRID;
     grid = (grid + 7) / 8 * 8;
-    attn_mla_kernel<<<(unsigned)grid, 256, 0, st>>>(kp);
+    if (d.dtype == LCA_F16)
+        attn_mla_kernel<true><<<(unsigned)grid, 256, 0, st>>>(kp);
+    else
+        attn_mla_kernel<false><<<(unsigned)grid, 256, 0, st>>>(kp);
     return hipGetLastError();
 }
 

@@ -14,6 +14,7 @@ constexpr int MAXD = 1024;   // largest d_qk / d_v handled (validated by the API
 
 template <typename T> __device__ __forceinline__ float ldf(const T *p);
 template <> __device__ __forceinline__ float ldf<uint16_t>(const uint16_t *p) { return __uint_as_float(((uint32_t)*p) << 16); }
+template <> __device__ __forceinline__ float ldf<f16_t>(const f16_t *p) { return f16_bits_to_float(p->bits); }
 template <> __device__ __forceinline__ float ldf<float>(const float *p) { return *p; }
 
 template <typename T> __device__ __forceinline__ void stf(T *p, float v);
@@ -23,6 +24,7 @@ template <> __device__ __forceinline__ void stf<uint16_t>(uint16_t *p, float v)
     u += 0x7FFFu + ((u >> 16) & 1u);
     *p = (uint16_t)(u >> 16);
 }
+template <> __device__ __forceinline__ void stf<f16_t>(f16_t *p, float v) { p->bits = float_to_f16_bits(v); }
 template <> __device__ __forceinline__ void stf<float>(float *p, float v) { *p = v; }
 
 template <typename T>
@@ -125,6 +127,10 @@ hipError_t launch_attn_simple(const AttnArgs &a, hipStream_t st)
             (const uint16_t *)a.Q, (const uint16_t *)a.POOL, (const uint16_t *)a.SEL, (const uint16_t *)a.pool_rep,
             (const uint16_t *)a.sel_rep, (uint16_t *)a.O, a.lse, d.L, d.H, d.S, d.P, d.d_pool, d.d_sel, mla, d.g, d.w, d.m, a.dense,
             d.scale, d.rep_logit_bias);
+    else if (d.dtype == LCA_F16)
+        attn_simple_kernel<f16_t><<<(unsigned)rows, WAVE, 0, st>>>(
+            (const f16_t *)a.Q, (const f16_t *)a.POOL, (const f16_t *)a.SEL, (const f16_t *)a.pool_rep, (const f16_t *)a.sel_rep,
+            (f16_t *)a.O, a.lse, d.L, d.H, d.S, d.P, d.d_pool, d.d_sel, mla, d.g, d.w, d.m, a.dense, d.scale, d.rep_logit_bias);
     else
         attn_simple_kernel<float><<<(unsigned)rows, WAVE, 0, st>>>(
             (const float *)a.Q, (const float *)a.POOL, (const float *)a.SEL, (const float *)a.pool_rep, (const float *)a.sel_rep,

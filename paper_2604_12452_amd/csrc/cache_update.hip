@@ -24,6 +24,10 @@ template <> struct Elt<uint16_t> {
         *p = (uint16_t)(u >> 16);
     }
 };
+template <> struct Elt<f16_t> {
+    __device__ static float ld(const f16_t *p) { return f16_bits_to_float(p->bits); }
+    __device__ static void st(f16_t *p, float v) { p->bits = float_to_f16_bits(v); }
+};
 template <> struct Elt<float> {
     __device__ static float ld(const float *p) { return *p; }
     __device__ static void st(float *p, float v) { *p = v; }
@@ -109,7 +113,7 @@ hipError_t launch_cache_update(const UpdateArgs &a, hipStream_t st)
     // the n_q recent queries are, to the summary-query kernel, a sequence of n_q tokens of which it averages the last n_q
     const hipError_t e = launch_summary_query(a.d, a.q_recent, a.d.n_q, a.qbar, st);
     if (e != hipSuccess) return e;
-    return a.d.dtype == LCA_BF16 ? run<uint16_t>(a, st) : run<float>(a, st);
+    return a.d.dtype == LCA_BF16 ? run<uint16_t>(a, st) : a.d.dtype == LCA_F16 ? run<f16_t>(a, st) : run<float>(a, st);
 }
 
 }  // namespace lca

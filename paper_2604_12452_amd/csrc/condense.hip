@@ -45,6 +45,27 @@ template <> struct Elt<uint16_t> {      // bf16 bit patterns
         return make_uint4(w[0], w[1], w[2], w[3]);
     }
 };
+template <> struct Elt<f16_t> {         // fp16 bit patterns
+    static constexpr int EPC = 8;
+    __device__ static float ld(const f16_t *p) { return f16_bits_to_float(p->bits); }
+    __device__ static void st(f16_t *p, float v) { p->bits = float_to_f16_bits(v); }
+    __device__ static void unpack(const uint4 &c, float *f)
+    {
+        const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = f16_bits_to_float((uint16_t)w[i]);
+            f[2 * i + 1] = f16_bits_to_float((uint16_t)(w[i] >> 16));
+        }
+    }
+    __device__ static uint4 pack(const float *f)
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)float_to_f16_bits(f[2 * i]) | ((uint32_t)float_to_f16_bits(f[2 * i + 1]) << 16);
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
 template <> struct Elt<float> {
     static constexpr int EPC = 4;
     __device__ static float ld(const float *p) { return *p; }
@@ -436,6 +457,9 @@ hipError_t launch_summary_query(const Dims &d, const void *Q, int L, float *qbar
     if (d.dtype == LCA_BF16) {
         const int sq_blocks = d.B * d.S * ((d.d_qk / 8 + WAVE - 1) / WAVE);
         summary_query_kernel<uint16_t><<<sq_blocks, SQ_WAVES * WAVE, 0, st>>>((const uint16_t *)Q, qbar, L, d.H, d.S, d.d_qk, d.n_q);
+    } else if (d.dtype == LCA_F16) {
+        const int sq_blocks = d.B * d.S * ((d.d_qk / 8 + WAVE - 1) / WAVE);
+        summary_query_kernel<f16_t><<<sq_blocks, SQ_WAVES * WAVE, 0, st>>>((const f16_t *)Q, qbar, L, d.H, d.S, d.d_qk, d.n_q);
     } else {
         const int sq_blocks = d.B * d.S * ((d.d_qk / 4 + WAVE - 1) / WAVE);
         summary_query_kernel<float><<<sq_blocks, SQ_WAVES * WAVE, 0, st>>>((const float *)Q, qbar, L, d.H, d.S, d.d_qk, d.n_q);
@@ -452,12 +476,16 @@ hipError_t launch_condense(const CondenseArgs &a, hipStream_t st)
     // 2. groups
     const bool mla = d.mode == LCA_MODE_MLA;
     // the register kernels implement the method's own strategies (weighted pooling, max selection); the ablation's others run generic
-    if (d.pool_reduce != LCA_REDUCE_WEIGHTED || d.sel_reduce != LCA_REDUCE_MAXSEL)
-        return d.dtype == LCA_BF16 ? run_generic<uint16_t>(a, st) : run_generic<float>(a, st);
+    auto generic = [&]() {
+        return d.dtype == LCA_BF16 ? run_generic<uint16_t>(a, st) : d.dtype == LCA_F16 ? run_generic<f16_t>(a, st) : run_generic<float>(a, st);
+    };
+    if (d.pool_reduce != LCA_REDUCE_WEIGHTED || d.sel_reduce != LCA_REDUCE_MAXSEL) return generic();
+    if (d.dtype == LCA_F16 && mla && d.d_pool == 512 && d.d_sel == 64 && try_reg<f16_t, 512, 64, true>(a, st, err)) return err;
+    if (d.dtype == LCA_F16 && !mla && d.d_pool == 128 && d.d_sel == 128 && try_reg<f16_t, 128, 128, false>(a, st, err)) return err;
     if (d.dtype == LCA_BF16 && mla && d.d_pool == 512 && d.d_sel == 64 && try_reg<uint16_t, 512, 64, true>(a, st, err)) return err;
     if (d.dtype == LCA_BF16 && !mla && d.d_pool == 128 && d.d_sel == 128 && try_reg<uint16_t, 128, 128, false>(a, st, err)) return err;
     if (d.dtype == LCA_F32 && mla && d.d_pool == 128 && d.d_sel == 32 && try_reg<float, 128, 32, true>(a, st, err)) return err;
-    return d.dtype == LCA_BF16 ? run_generic<uint16_t>(a, st) : run_generic<float>(a, st);
+    return generic();
 }
 
 }  // namespace lca

@@ -35,6 +35,20 @@ template <> struct DElt<uint16_t> {
         *p = (uint16_t)(u >> 16);
     }
 };
+template <> struct DElt<f16_t> {
+    static constexpr int EPC = 8;
+    __device__ static float ld(const f16_t *p) { return f16_bits_to_float(p->bits); }
+    __device__ static void unpack(const uint4 &c, float *f)
+    {
+        const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = f16_bits_to_float((uint16_t)w[i]);
+            f[2 * i + 1] = f16_bits_to_float((uint16_t)(w[i] >> 16));
+        }
+    }
+    __device__ static void st(f16_t *p, float v) { p->bits = float_to_f16_bits(v); }
+};
 template <> struct DElt<float> {
     static constexpr int EPC = 4;
     __device__ static float ld(const float *p) { return *p; }
@@ -226,10 +240,10 @@ __device__ __forceinline__ float row16_allreduce_sum(float x)
 // 16-byte chunk of the key AND of the value of that row; 4 rows per wavefront step, GQ_UNROLL steps in flight
 // (all loads of an iteration are issued before any arithmetic), one softmax rescale per iteration.
 constexpr int GQ_UNROLL = 4;
-template <int HPS>
-__global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const uint16_t *__restrict__ q, const uint16_t *__restrict__ pool_rep,
-                                                                 const uint16_t *__restrict__ sel_rep, const uint16_t *__restrict__ pool_tail,
-                                                                 const uint16_t *__restrict__ sel_tail, float *__restrict__ part, int S, int m,
+template <typename T, int HPS>
+__global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const T *__restrict__ q, const T *__restrict__ pool_rep,
+                                                                 const T *__restrict__ sel_rep, const T *__restrict__ pool_tail,
+                                                                 const T *__restrict__ sel_tail, float *__restrict__ part, int S, int m,
                                                                  int k, int splits, float scale, float rep_bias, int m_cap, int k_cap,
                                                                  int k_start)
 {
@@ -246,12 +260,12 @@ __global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const uint16_t 
 #pragma unroll
     for (int h = 0; h < H; ++h) {
         float f[8];
-        DElt<uint16_t>::unpack(*reinterpret_cast<const uint4 *>(q + (((size_t)b * S + s) * H + h) * D + sub * 8), f);
+        DElt<T>::unpack(*reinterpret_cast<const uint4 *>(q + (((size_t)b * S + s) * H + h) * D + sub * 8), f);
 #pragma unroll
         for (int x = 0; x < 8; ++x) qv[h][x] = f[x] * scale;
     }
-    const uint16_t *krep = sel_rep + ((size_t)b * S + s) * m_cap * D, *vrep = pool_rep + ((size_t)b * S + s) * m_cap * D;
-    const uint16_t *ktail = sel_tail + ((size_t)b * S + s) * k_cap * D, *vtail = pool_tail + ((size_t)b * S + s) * k_cap * D;
+    const T *krep = sel_rep + ((size_t)b * S + s) * m_cap * D, *vrep = pool_rep + ((size_t)b * S + s) * m_cap * D;
+    const T *ktail = sel_tail + ((size_t)b * S + s) * k_cap * D, *vtail = pool_tail + ((size_t)b * S + s) * k_cap * D;
 
     float mr[H], lr[H], acc[H][8];
 #pragma unroll
@@ -273,8 +287,8 @@ __global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const uint16_t 
             rep[u] = ec < m;
             int r = k_start + (ec - m);                         // the tail is a ring of k_cap rows
             r = r >= k_cap ? r - k_cap : r;
-            const uint16_t *kp = rep[u] ? krep + (size_t)ec * D : ktail + (size_t)r * D;
-            const uint16_t *vp = rep[u] ? vrep + (size_t)ec * D : vtail + (size_t)r * D;
+            const T *kp = rep[u] ? krep + (size_t)ec * D : ktail + (size_t)r * D;
+            const T *vp = rep[u] ? vrep + (size_t)ec * D : vtail + (size_t)r * D;
             kd[u] = *reinterpret_cast<const uint4 *>(kp + sub * 8);
             vd[u] = *reinterpret_cast<const uint4 *>(vp + sub * 8);
         }
@@ -282,7 +296,7 @@ __global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const uint16_t 
 #pragma unroll
         for (int u = 0; u < GQ_UNROLL; ++u) {
             float f[8];
-            DElt<uint16_t>::unpack(kd[u], f);
+            DElt<T>::unpack(kd[u], f);
 #pragma unroll
             for (int h = 0; h < H; ++h) {
                 float a = 0.f;
@@ -308,7 +322,7 @@ __global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const uint16_t 
                 const float pe = __expf(logit[u][h] - m_eff);
                 lr[h] += pe;
                 float f[8];
-                DElt<uint16_t>::unpack(vd[u], f);
+                DElt<T>::unpack(vd[u], f);
 #pragma unroll
                 for (int x = 0; x < 8; ++x) acc[h][x] = fmaf(pe, f[x], acc[h][x]);
             }
@@ -418,16 +432,16 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(const float
     }
 }
 
-template <int HPS>
+template <typename T, int HPS>
 hipError_t run_gqa(const DecodeArgs &a, hipStream_t st)
 {
     const Dims &d = a.d;
-    decode_gqa_kernel<HPS><<<d.B * d.S * a.splits, WAVE * NWAVE, 0, st>>>(
-        (const uint16_t *)a.q, (const uint16_t *)a.pool_rep, (const uint16_t *)a.sel_rep, (const uint16_t *)a.pool_tail,
-        (const uint16_t *)a.sel_tail, a.part, d.S, d.m, d.k, a.splits, d.scale, d.rep_logit_bias, a.m_cap, a.k_cap, a.k_start);
+    decode_gqa_kernel<T, HPS><<<d.B * d.S * a.splits, WAVE * NWAVE, 0, st>>>(
+        (const T *)a.q, (const T *)a.pool_rep, (const T *)a.sel_rep, (const T *)a.pool_tail,
+        (const T *)a.sel_tail, a.part, d.S, d.m, d.k, a.splits, d.scale, d.rep_logit_bias, a.m_cap, a.k_cap, a.k_start);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    decode_merge_kernel<uint16_t><<<d.B * d.H, MERGE_THREADS, a.splits * sizeof(float), st>>>(a.part, (uint16_t *)a.O, HPS, 128, a.splits);
+    decode_merge_kernel<T><<<d.B * d.H, MERGE_THREADS, a.splits * sizeof(float), st>>>(a.part, (T *)a.O, HPS, 128, a.splits);
     return hipGetLastError();
 }
 
@@ -449,8 +463,9 @@ int shape_id(const Dims &d)
 {
     const int hps = d.H / d.S;
     const bool mla = d.mode == LCA_MODE_MLA;
-    if (d.dtype == LCA_BF16 && !mla && d.d_pool == 128 && d.d_sel == 128 && (hps == 1 || hps == 2 || hps == 4 || hps == 8)) return 100 + hps;
-    if (d.dtype == LCA_BF16 && mla && d.d_pool == 512 && d.d_sel == 64 && (hps == 1 || hps == 16)) return 200 + hps;
+    const bool b16 = d.dtype == LCA_BF16 || d.dtype == LCA_F16;    // the 16-bit types share the shapes; the launcher picks the type
+    if (b16 && !mla && d.d_pool == 128 && d.d_sel == 128 && (hps == 1 || hps == 2 || hps == 4 || hps == 8)) return 100 + hps;
+    if (b16 && mla && d.d_pool == 512 && d.d_sel == 64 && (hps == 1 || hps == 16)) return 200 + hps;
     if (d.dtype == LCA_F32 && mla && d.d_pool == 128 && d.d_sel == 32 && (hps == 1 || hps == 4)) return 300 + hps;
     return 0;
 }
@@ -482,16 +497,20 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st)
         const hipError_t e = launch_decode_mla(a, st);
         if (e != hipSuccess) return e;
         const int wgs = a.splits / 4;    // one partial result per workgroup of four wavefronts
-        decode_merge_kernel<uint16_t><<<a.d.B * a.d.H, MERGE_THREADS, wgs * sizeof(float), st>>>(a.part, (uint16_t *)a.O, a.d.H / a.d.S, a.d.d_pool, wgs);
+        if (a.d.dtype == LCA_F16)
+            decode_merge_kernel<f16_t><<<a.d.B * a.d.H, MERGE_THREADS, wgs * sizeof(float), st>>>(a.part, (f16_t *)a.O, a.d.H / a.d.S, a.d.d_pool, wgs);
+        else
+            decode_merge_kernel<uint16_t><<<a.d.B * a.d.H, MERGE_THREADS, wgs * sizeof(float), st>>>(a.part, (uint16_t *)a.O, a.d.H / a.d.S, a.d.d_pool, wgs);
         return hipGetLastError();
     }
+    const bool f16 = a.d.dtype == LCA_F16;
     switch (shape_id(a.d)) {
-    case 101: return run_gqa<1>(a, st);
-    case 102: return run_gqa<2>(a, st);
-    case 104: return run_gqa<4>(a, st);
-    case 108: return run_gqa<8>(a, st);
-    case 201: return run<uint16_t, 512, 64, true, 1>(a, st);
-    case 216: return run<uint16_t, 512, 64, true, 16>(a, st);
+    case 101: return f16 ? run_gqa<f16_t, 1>(a, st) : run_gqa<uint16_t, 1>(a, st);
+    case 102: return f16 ? run_gqa<f16_t, 2>(a, st) : run_gqa<uint16_t, 2>(a, st);
+    case 104: return f16 ? run_gqa<f16_t, 4>(a, st) : run_gqa<uint16_t, 4>(a, st);
+    case 108: return f16 ? run_gqa<f16_t, 8>(a, st) : run_gqa<uint16_t, 8>(a, st);
+    case 201: return f16 ? run<f16_t, 512, 64, true, 1>(a, st) : run<uint16_t, 512, 64, true, 1>(a, st);
+    case 216: return f16 ? run<f16_t, 512, 64, true, 16>(a, st) : run<uint16_t, 512, 64, true, 16>(a, st);
     case 301: return run<float, 128, 32, true, 1>(a, st);
     case 304: return run<float, 128, 32, true, 4>(a, st);
     default: return hipErrorInvalidValue;

@@ -1,4 +1,4 @@
-// Decode step over a condensed cache at the MLA widths (d_c = 512, d_R = 64, bf16; section 4.3 of the paper,
+// Decode step over a condensed cache at the MLA widths (d_c = 512, d_R = 64, bf16 or fp16; section 4.3 of the paper,
 // decoding paragraph; absorbed form of section 3): the new token's query attends the m representatives and the
 // k raw tail rows, and the (up to 16) heads of a condensed set share every cache row.
 //
@@ -14,7 +14,7 @@
 // the S^T accumulators already are the B fragments of the second product when the transpose reads of a 16-lane
 // block take rows 4 apart (conflict-free on the 1040-byte stride).  Softmax keeps one fixed reference per head
 // (taken at the first tile), so the 128 accumulation registers are never rescaled; if a row sum ends beyond
-// 2^100 the wavefront collects the exact maximum of its range and runs it again.  The four wavefronts' results
+// 2^100 (or, in fp16, an exponential left the type's range and the sum is infinite) the wavefront collects the exact maximum of its range and runs it again.  The four wavefronts' results
 // (reference, sum, unnormalised output per head) are merged in LDS into one partial result per workgroup; the
 // workgroups' partial results are merged by decode_merge_kernel.
 #include "lca_internal.h"
@@ -24,7 +24,22 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// The kernel is a template over the 16-bit element type E (__bf16 or _Float16); these overloads pick the instructions.
+__device__ __forceinline__ floatx4 mfma_16x16x32(bf16x8 a, bf16x8 b, floatx4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
+__device__ __forceinline__ floatx4 mfma_16x16x32(f16x8 a, f16x8 b, floatx4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+__device__ __forceinline__ bf16x4 lds_read_tr16(__attribute__((address_space(3))) bf16x4 *p) { return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(p); }
+__device__ __forceinline__ f16x4 lds_read_tr16(__attribute__((address_space(3))) f16x4 *p)
+{
+    typedef __fp16 fp16x4 __attribute__((__vector_size__(4 * sizeof(__fp16))));     // the builtin's own spelling of four halves
+    return __builtin_bit_cast(f16x4, __builtin_amdgcn_ds_read_tr16_b64_v4f16((__attribute__((address_space(3))) fp16x4 *)p));
+}
+// A row sum beyond this (or not finite) makes the wavefront run its range again from the exact maxima.  The sum adds the
+// ROUNDED exponentials, so one that left fp16's range (65504) arrives here as an infinity.
+constexpr float SUM_LIMIT = 0x1p100f;
 
 constexpr int DP = 512, DS = 64, DQK = 576;
 constexpr int BN = 32;                          // entries per tile
@@ -59,8 +74,11 @@ __device__ __forceinline__ void dma_lanes(const void *addr, unsigned lds_addr)  
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(addr), "s"(lds_addr));
 }
 
+template <typename E>
 __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
 {
+    typedef E ex8 __attribute__((ext_vector_type(8)));
+    typedef E ex4 __attribute__((ext_vector_type(4)));
     __shared__ __attribute__((aligned(1024))) char bufs[4][BUF_BYTES];
     __shared__ float wave_ml[4][16][2];                                     // (reference, sum) per wavefront and head
 
@@ -82,13 +100,13 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
     auto ring_row = [&](int e) { const int t = kp.k_start + e - m; return t >= kp.k_cap ? t - kp.k_cap : t; };
 
     // Q^T fragments: lane (col = head of the set, q4) holds q[head, 32 ks + 8 q4 .. +7]; columns past the set's heads are zero
-    bf16x8 qf[NKS];
+    ex8 qf[NKS];
     {
         const uint16_t *qp = kp.q + ((size_t)bs * kp.hps + min(col, kp.hps - 1)) * DQK + 8 * q4;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + 32 * ks);
-            if (col >= kp.hps) qf[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            qf[ks] = *reinterpret_cast<const ex8 *>(qp + 32 * ks);
+            if (col >= kp.hps) qf[ks] = ex8{0, 0, 0, 0, 0, 0, 0, 0};
         }
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[ks]));   // loaded before the copies start (see the wait below)
@@ -103,7 +121,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
     floatx4 acc[NDT];
     float m_ref = NEG_BIG, l_run = 0.f, m_seen = NEG_BIG;
     const float c = kp.scale_log2;
-    typedef __attribute__((address_space(3))) bf16x4 *lds_b64_ptr;
+    typedef __attribute__((address_space(3))) ex4 *lds_b64_ptr;
 
     // copy of tile tl into this wavefront's buffer, S^T = K Q^T for its two blocks of 16 entries, and the logits in base 2
     // (scale, bias of the representatives, entries past the range hidden)
@@ -143,17 +161,17 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                   // ... has landed (the other wavefronts of the CU cover the wait)
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
-            bf16x8 kf[NKS];
+            ex8 kf[NKS];
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
                 const char *p = ks < DP / 32 ? buf + k_off + blk * 16 * RSB + 64 * ks
                                              : buf + ksel_row + blk * 16 * (DS * 2) + (((4 * (ks - DP / 32) + q4) ^ (krow & 7)) << 4);
-                kf[ks] = *reinterpret_cast<const bf16x8 *>(p);
+                kf[ks] = *reinterpret_cast<const ex8 *>(p);
             }
             __builtin_amdgcn_sched_barrier(0);
             floatx4 sacc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[ks], sacc, 0, 0, 0);
+            for (int ks = 0; ks < NKS; ++ks) sacc = mfma_16x16x32(kf[ks], qf[ks], sacc);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -188,23 +206,23 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
                 m_ref = (m_ref == NEG_BIG) ? mx : m_ref;
                 ref_missing = __builtin_amdgcn_ballot_w64(m_ref == NEG_BIG) != 0;
             }
-            // P^T in bf16 (B fragment: k-slot i < 4 is the key of block 0 register i, i >= 4 of block 1 register i-4) and its sum
-            bf16x8 pb;
+            // P^T in the element type (B fragment: k-slot i < 4 is the key of block 0 register i, i >= 4 of block 1 register i-4) and its sum
+            ex8 pb;
 #pragma unroll
             for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    pb[blk * 4 + r] = (__bf16)__builtin_amdgcn_exp2f(lg[blk][r] - m_ref);
+                    pb[blk * 4 + r] = (E)__builtin_amdgcn_exp2f(lg[blk][r] - m_ref);
                     l_run += (float)pb[blk * 4 + r];                       // the rounded value, the one the second product sees
                 }
             // O^T += V^T P^T: fragments of PV_GROUP value tiles requested together, one group ahead
-            bf16x4 vlo[2][PV_GROUP], vhi[2][PV_GROUP];
+            ex4 vlo[2][PV_GROUP], vhi[2][PV_GROUP];
             auto request = [&](int grp, int bsel) {
 #pragma unroll
                 for (int i = 0; i < PV_GROUP; ++i) {
                     const char *vp = buf + v_off + 32 * (grp * PV_GROUP + i);
-                    vlo[bsel][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp));
-                    vhi[bsel][i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(vp + 16 * RSB));
+                    vlo[bsel][i] = lds_read_tr16((lds_b64_ptr)(vp));
+                    vhi[bsel][i] = lds_read_tr16((lds_b64_ptr)(vp + 16 * RSB));
                 }
             };
             request(0, 0);
@@ -215,15 +233,15 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < PV_GROUP; ++i) {
-                    const bf16x8 a = __builtin_shufflevector(vlo[grp & 1][i], vhi[grp & 1][i], 0, 1, 2, 3, 4, 5, 6, 7);
-                    acc[grp * PV_GROUP + i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb, acc[grp * PV_GROUP + i], 0, 0, 0);
+                    const ex8 a = __builtin_shufflevector(vlo[grp & 1][i], vhi[grp & 1][i], 0, 1, 2, 3, 4, 5, 6, 7);
+                    acc[grp * PV_GROUP + i] = mfma_16x16x32(a, pb, acc[grp * PV_GROUP + i]);
                 }
             }
         }
 
         l_tot = l_run + __shfl_xor(l_run, 16, 64);
         l_tot += __shfl_xor(l_tot, 32, 64);
-        if (again || __builtin_amdgcn_ballot_w64(!(l_tot <= 0x1p100f)) == 0) break;
+        if (again || __builtin_amdgcn_ballot_w64(!(l_tot <= SUM_LIMIT)) == 0) break;
         // (wave-uniform) a head ran out of exponent headroom: exact maxima of the range, then the pass again
         m_seen = NEG_BIG;
         for (int tl = t_lo; tl < t_hi; ++tl) {
@@ -290,7 +308,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
 bool decode_mla_supported(const Dims &d)
 {
     const int hps = d.H / d.S;
-    return d.dtype == LCA_BF16 && d.mode == LCA_MODE_MLA && d.d_pool == DP && d.d_sel == DS && hps <= 16 && d.scale > 0.f;
+    return (d.dtype == LCA_BF16 || d.dtype == LCA_F16) && d.mode == LCA_MODE_MLA && d.d_pool == DP && d.d_sel == DS && hps <= 16 && d.scale > 0.f;
 }
 
 // partial results per (sequence, set): a multiple of 4 (one per wavefront), enough workgroups to fill the chip,
@@ -315,7 +333,10 @@ hipError_t launch_decode_mla(const DecodeArgs &a, hipStream_t st)
     kp.m_cap = a.m_cap; kp.k_cap = a.k_cap; kp.k_start = a.k_start;
     kp.scale_log2 = d.scale * 1.4426950408889634f;
     kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
-    decode_mla_kernel<<<d.B * d.S * (a.splits / 4), 256, 0, st>>>(kp);
+    if (d.dtype == LCA_F16)
+        decode_mla_kernel<_Float16><<<d.B * d.S * (a.splits / 4), 256, 0, st>>>(kp);
+    else
+        decode_mla_kernel<__bf16><<<d.B * d.S * (a.splits / 4), 256, 0, st>>>(kp);
     return hipGetLastError();
 }
 

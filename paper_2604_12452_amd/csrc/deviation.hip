@@ -15,6 +15,7 @@ constexpr int WAVE = 64;
 
 template <typename T> struct VElt;
 template <> struct VElt<uint16_t> { __device__ static float ld(const uint16_t *p) { return __uint_as_float((unsigned)*p << 16); } };
+template <> struct VElt<f16_t> { __device__ static float ld(const f16_t *p) { return f16_bits_to_float(p->bits); } };
 template <> struct VElt<float> { __device__ static float ld(const float *p) { return *p; } };
 
 __device__ __forceinline__ float wave_sum(float x)
@@ -103,7 +104,7 @@ size_t deviation_workspace_bytes(const Dims &d) { return (size_t)d.B * d.S * d.m
 
 hipError_t launch_deviation_stats(const DeviationArgs &a, hipStream_t st)
 {
-    return a.d.dtype == LCA_BF16 ? run<uint16_t>(a, st) : run<float>(a, st);
+    return a.d.dtype == LCA_BF16 ? run<uint16_t>(a, st) : a.d.dtype == LCA_F16 ? run<f16_t>(a, st) : run<float>(a, st);
 }
 
 }  // namespace lca

@@ -30,8 +30,8 @@ lca_status make_dims(const lca_desc *desc, lca::Dims &d)
     if (desc->g <= 0 || desc->g > 64) return fail(LCA_ERR_INVALID_ARG, "g must be in [1, 64], got %d", desc->g);
     if (desc->w < 0) return fail(LCA_ERR_INVALID_ARG, "w must be >= 0");
     if (desc->mode != LCA_MODE_MLA && desc->mode != LCA_MODE_GQA) return fail(LCA_ERR_INVALID_ARG, "unknown mode %d", desc->mode);
-    if (desc->dtype != LCA_BF16 && desc->dtype != LCA_F32) return fail(LCA_ERR_INVALID_ARG, "unknown dtype %d", desc->dtype);
-    const int mult = desc->dtype == LCA_BF16 ? 8 : 4;
+    if (desc->dtype != LCA_BF16 && desc->dtype != LCA_F32 && desc->dtype != LCA_F16) return fail(LCA_ERR_INVALID_ARG, "unknown dtype %d", desc->dtype);
+    const int mult = desc->dtype == LCA_F32 ? 4 : 8;
     if (desc->d_pool <= 0 || desc->d_sel <= 0 || desc->d_pool % mult || desc->d_sel % mult)
         return fail(LCA_ERR_INVALID_ARG, "d_pool and d_sel must be positive multiples of %d", mult);
     const int d_qk = desc->mode == LCA_MODE_MLA ? desc->d_pool + desc->d_sel : desc->d_sel;
@@ -46,7 +46,7 @@ lca_status make_dims(const lca_desc *desc, lca::Dims &d)
     d.g = desc->g; d.w = desc->w; d.n_q = n_q;
     d.m = desc->L > desc->w ? (desc->L - desc->w) / desc->g : 0;
     d.k = desc->L - d.m * desc->g;
-    d.mode = desc->mode; d.dtype = desc->dtype; d.elt = desc->dtype == LCA_BF16 ? 2 : 4;
+    d.mode = desc->mode; d.dtype = desc->dtype; d.elt = desc->dtype == LCA_F32 ? 4 : 2;
     d.scale = desc->scale; d.rep_logit_bias = desc->rep_logit_bias;
     if (desc->pool_reduce < 0 || desc->pool_reduce > LCA_REDUCE_MAXPOOL || desc->sel_reduce < 0 || desc->sel_reduce > LCA_REDUCE_MAXPOOL)
         return fail(LCA_ERR_INVALID_ARG, "unknown reduce strategy (%d, %d)", desc->pool_reduce, desc->sel_reduce);

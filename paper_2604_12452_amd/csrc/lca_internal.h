@@ -8,6 +8,12 @@
 
 namespace lca {
 
+// Element tag of IEEE binary16 storage: the kernels are templates over the element type, bf16 travels as bare
+// uint16_t bit patterns, so fp16 gets a distinct 2-byte type of its own.
+struct f16_t { uint16_t bits; };
+__device__ __forceinline__ float f16_bits_to_float(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+__device__ __forceinline__ uint16_t float_to_f16_bits(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }   // round to nearest even
+
 // Derived sizes of a validated descriptor.
 struct Dims {
     int B, L, H, S, P;        // P = KV heads physically present in POOL/SEL (1 for MLA, S for GQA)

@@ -25,7 +25,7 @@ def from_dev(t, dtype: str) -> np.ndarray:
 def lca_desc(wl: inputs.Workload, **over):
     from . import lca
     kw = dict(B=wl.B, L=wl.L, H=wl.H, S=wl.S, d_pool=wl.d_pool, d_sel=wl.d_sel, g=wl.g, w=wl.w, n_q=wl.n_q, mode=wl.mode,
-              dtype=lca.BF16 if wl.dtype == "bf16" else lca.F32, scale=wl.scale)
+              dtype={"bf16": lca.BF16, "f32": lca.F32, "f16": lca.F16}[wl.dtype], scale=wl.scale)
     kw.update(over)
     return lca.Desc(**kw)
 

@@ -36,7 +36,7 @@ class Workload:
     d_sel: int
     g: int
     w: int
-    dtype: str            # "bf16" | "f32"
+    dtype: str            # "bf16" | "f16" | "f32"
     mode: int = MODE_MLA
     n_q: int = 0          # 0 -> g
     theta: float = 10000.0
@@ -109,6 +109,8 @@ def to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
         return f32_to_bf16_bits(x.astype(np.float32))
     if dtype == "f32":
         return np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == "f16":
+        return np.ascontiguousarray(x, dtype=np.float16)      # one rounding to nearest even, also from float64
     raise ValueError(dtype)
 
 

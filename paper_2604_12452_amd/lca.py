@@ -16,7 +16,7 @@ LIB_PATH = os.environ.get("LCA_LIB_PATH", os.path.join(_PKG, "liblca.so"))   # o
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 MODE_MLA, MODE_GQA = 0, 1
-BF16, F32 = 0, 1
+BF16, F32, F16 = 0, 1, 2
 REDUCE_DEFAULT, REDUCE_WEIGHTED, REDUCE_MEAN, REDUCE_MAXSEL, REDUCE_MAXPOOL = range(5)
 
 EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condense", "lca_prefill_attn", "dense_mla_attn",
@@ -200,7 +200,7 @@ def deviation_stats(desc: Desc, POOL, SEL, pool_rep, sel_rep, stats, workspace, 
 # ---------------------------------------------------------------------------------------------
 def torch_dtype(desc: Desc):
     import torch
-    return torch.bfloat16 if desc.dtype == BF16 else torch.float32
+    return {BF16: torch.bfloat16, F32: torch.float32, F16: torch.float16}[desc.dtype]
 
 
 def alloc_workspace(desc: Desc, device="cuda"):

@@ -10,7 +10,11 @@ from paper_2604_12452_amd import inputs
 # bf16 in / fp32 accumulate: the bar the task states.  fp32: the kernels accumulate <= ~1200 products
 # and exponentials per output in fp32 with hardware exp (2 ulp) -> a few 1e-6 expected; 1e-4 leaves
 # two orders of margin and is still 100x tighter than the bf16 bar.
-TOL = {"bf16": 1e-2, "f32": 1e-4}
+# fp16 in / fp32 accumulate (unit roundoff 2^-11 = 4.9e-4): the cache store, the P^T operand and the output store each
+# round once, so up to ~3 roundoffs of the largest component in the worst case -> 2e-3 (a fifth of the bf16 bar, in
+# line with the 8x finer type; measured errors are around 5e-4).
+TOL = {"bf16": 1e-2, "f32": 1e-4, "f16": 2e-3}
+LSE_TOL = {"bf16": 1e-2, "f32": 1e-4, "f16": 1e-2}
 ANCHOR_MARGIN = 1e-3   # anchors must match bit-exactly where the oracle's top-two score gap exceeds this
 
 
@@ -76,7 +80,7 @@ def check_prefill(o, wl, run: GpuRun, rows, Qf_rows, POOLf, SELf, ref_cond, diff
     assert e2 <= tol, f"stage 2 (attention on the emitted cache) rel err {e2:.3e} > {tol}"
     if run.lse is not None:
         l_gpu = run.lse[:, rows.tolist()].cpu().numpy().astype(np.float64)
-        assert np.abs(l_gpu - lse2).max() <= (1e-2 if wl.dtype == "bf16" else 1e-4), "lse mismatch"
+        assert np.abs(l_gpu - lse2).max() <= LSE_TOL[wl.dtype], "lse mismatch"
     sel3 = ref_cond["sel_rep"].copy()
     if differ.any():
         sel3[differ] = sr[differ]
@@ -106,5 +110,5 @@ def check_dense(o, wl, run: GpuRun, rows, Qf_rows, POOLf, SELf, tol=None):
     assert e <= tol, f"dense rel err {e:.3e} > {tol}"
     if run.lse_dense is not None:
         l_gpu = run.lse_dense[:, rows.tolist()].cpu().numpy().astype(np.float64)
-        assert np.abs(l_gpu - lse_ref).max() <= (1e-2 if wl.dtype == "bf16" else 1e-4), "dense lse mismatch"
+        assert np.abs(l_gpu - lse_ref).max() <= LSE_TOL[wl.dtype], "dense lse mismatch"
     return e

@@ -45,6 +45,7 @@ def test_workspace_and_cache_bytes_are_host_only(lib):
     assert lca.cache_bytes(_desc(L=131072, S=16)) == (150994944, 150994944)
     gqa = lca.Desc(B=1, L=65536, H=32, S=8, d_pool=128, d_sel=128, g=16, w=1024, mode=lca.MODE_GQA)
     assert lca.cache_bytes(gqa) == (268435456, 20709376)
+    assert lca.workspace_size(_desc(dtype=lca.F16)) == lca.workspace_size(_desc())      # both 16-bit types are accepted
     assert lca.workspace_size(lca.Desc(B=32, L=65537, H=32, S=8, d_pool=128, d_sel=128, g=16, w=1024, mode=lca.MODE_GQA)) > 0
 
 

@@ -16,6 +16,8 @@ SHAPES = [
     (inputs.MODE_MLA, 512, 64, 16, 4, "bf16"),
     (inputs.MODE_MLA, 512, 64, 8, 8, "bf16"),
     (inputs.MODE_MLA, 128, 32, 4, 1, "f32"),
+    (inputs.MODE_GQA, 128, 128, 8, 2, "f16"),
+    (inputs.MODE_MLA, 512, 64, 16, 1, "f16"),
 ]
 
 

@@ -43,6 +43,15 @@ def test_cfg4_128k(oracle, g):
     _sampled_parity(oracle, inputs.configs()["cfg4"].with_(g=g), 40, dense_rows=6 if g == 16 else 0)
 
 
+def test_cfg4_128k_fp16(oracle):
+    """The 128K configuration with fp16 inputs, cache and output (the paper's implementation names both 16-bit types)."""
+    _sampled_parity(oracle, inputs.configs()["cfg4"].with_(dtype="f16"), 40, dense_rows=6)
+
+
+def test_cfg5_gqa_64k_fp16_prefill(oracle):
+    _sampled_parity(oracle, inputs.configs()["cfg5"].with_(dtype="f16"), 32, dense_rows=4)
+
+
 def test_cfg5_gqa_64k_prefill_and_decode(oracle):
     import torch
     from paper_2604_12452_amd import lca

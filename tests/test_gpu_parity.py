@@ -40,7 +40,7 @@ def _full_parity(oracle, wl, bias=0.0, dense=True):
 
 
 # ---- generic kernels (any widths), both element types, both modes --------------------------------
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("mode", [inputs.MODE_MLA, inputs.MODE_GQA])
 @pytest.mark.parametrize("L,g,w,H,S", [(333, 4, 10, 4, 2), (129, 8, 0, 2, 1), (70, 1, 5, 2, 2), (257, 64, 3, 6, 3), (40, 3, 7, 1, 1)])
 def test_generic_kernels_small_shapes(oracle, dtype, mode, L, g, w, H, S):
@@ -75,13 +75,14 @@ def test_cfg1_tiny_fp32_all_rows(oracle, S):
     (7, 2, 1, 3, 3, 2),           # fewer rows than a tile, two sequences: segments of a few rows behind one another
     (40, 4, 4, 4, 2, 3),          # three sequences back to back: nothing may leak across a sequence's end
 ])
-def test_mla_mfma_small_all_rows(oracle, L, g, w, H, S, B):
-    wl = inputs.Workload("mla_small", B=B, L=L, H=H, S=S, d_pool=512, d_sel=64, g=g, w=w, dtype="bf16", seed=7 + L)
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_mla_mfma_small_all_rows(oracle, L, g, w, H, S, B, dtype):
+    wl = inputs.Workload("mla_small", B=B, L=L, H=H, S=S, d_pool=512, d_sel=64, g=g, w=w, dtype=dtype, seed=7 + L)
     _full_parity(oracle, wl)
 
 
 def _random_shapes(mode, n, seed):
-    """Seeded draws of valid shapes for the bf16 MFMA kernels: lengths around the tile and block sizes, every group size,
+    """Seeded draws of valid shapes for the MFMA kernels: lengths around the tile and block sizes, every group size,
     windows from none to longer than the sequence, several head ratios."""
     rng = np.random.default_rng(seed)
     out = []
@@ -110,6 +111,19 @@ def test_gqa_mfma_random_shapes(oracle, L, g, w, H, S, B):
     _full_parity(oracle, wl)
 
 
+@pytest.mark.parametrize("L,g,w,H,S,B", _random_shapes(inputs.MODE_MLA, 8, 2026))
+def test_mla_mfma_random_shapes_fp16(oracle, L, g, w, H, S, B):
+    wl = inputs.Workload("mla_rand16", B=B, L=L, H=H, S=S, d_pool=512, d_sel=64, g=g, w=w, dtype="f16", seed=3000 + L + 7 * g + w, n_q=min(g, L))
+    _full_parity(oracle, wl)
+
+
+@pytest.mark.parametrize("L,g,w,H,S,B", _random_shapes(inputs.MODE_GQA, 8, 2027))
+def test_gqa_mfma_random_shapes_fp16(oracle, L, g, w, H, S, B):
+    wl = inputs.Workload("gqa_rand16", B=B, L=L, H=H, S=S, d_pool=128, d_sel=128, g=g, w=w, dtype="f16", mode=inputs.MODE_GQA,
+                         theta=500000.0, seed=4000 + L + 7 * g + w, n_q=min(g, L))
+    _full_parity(oracle, wl)
+
+
 def test_mla_mfma_multiplicity_bias(oracle):
     wl = inputs.Workload("mla_bias", B=1, L=400, H=2, S=1, d_pool=512, d_sel=64, g=16, w=32, dtype="bf16", seed=5)
     _full_parity(oracle, wl, bias=math.log(16.0), dense=False)
@@ -124,10 +138,11 @@ def test_mla_topic_shift_inputs(oracle):
 @pytest.mark.parametrize("B,L,g,w,H,S", [(1, 700, 16, 100, 8, 2), (1, 300, 8, 0, 4, 4), (1, 129, 16, 64, 4, 1), (2, 515, 16, 32, 4, 2),
                                            (2, 260, 4, 7, 16, 2), (1, 31, 4, 2, 8, 2), (1, 1100, 32, 256, 8, 1), (1, 333, 8, 40, 6, 2),
                                            (2, 777, 16, 128, 2, 2), (1, 513, 32, 0, 4, 2), (3, 70, 4, 5, 4, 1), (1, 1, 1, 0, 4, 1)])
-def test_gqa_mfma_small_all_rows(oracle, B, L, g, w, H, S):
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_gqa_mfma_small_all_rows(oracle, B, L, g, w, H, S, dtype):
     """Heads per KV head of 1, 2, 4 and 8 run the 128-wide kernel (4 wavefronts = heads x groups of 64 rows); 3 heads per
     KV head (the last case) is served by the older general MFMA kernel."""
-    wl = inputs.Workload("gqa_small", B=B, L=L, H=H, S=S, d_pool=128, d_sel=128, g=g, w=w, dtype="bf16", mode=inputs.MODE_GQA,
+    wl = inputs.Workload("gqa_small", B=B, L=L, H=H, S=S, d_pool=128, d_sel=128, g=g, w=w, dtype=dtype, mode=inputs.MODE_GQA,
                          theta=500000.0, seed=11 + L)
     _full_parity(oracle, wl)
 
@@ -169,6 +184,9 @@ def test_results_are_deterministic(oracle):
     (inputs.MODE_MLA, 512, 64, 16, 4, "bf16"),
     (inputs.MODE_MLA, 512, 64, 8, 8, "bf16"),
     (inputs.MODE_MLA, 128, 32, 4, 1, "f32"),
+    (inputs.MODE_GQA, 128, 128, 8, 2, "f16"),
+    (inputs.MODE_MLA, 512, 64, 16, 1, "f16"),
+    (inputs.MODE_MLA, 512, 64, 8, 8, "f16"),
 ])
 @pytest.mark.parametrize("L,g,w", [(1000, 16, 100), (77, 4, 9), (50, 16, 64)])
 def test_decode_step(oracle, mode, d_pool, d_sel, H, S, dtype, L, g, w):
@@ -200,12 +218,13 @@ def test_decode_step(oracle, mode, d_pool, d_sel, H, S, dtype, L, g, w):
 
 
 # ---- rows whose later logits dwarf the first tile's: the kernel's repeat pass ---------------------------
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("dense_only", [False, True])
-def test_mla_logits_far_above_first_tile(oracle, dense_only):
+def test_mla_logits_far_above_first_tile(oracle, dense_only, dtype):
     """A key late in the sequence scores ~100 nats above everything in the first key tile of each row.  The
     MLA kernel fixes its softmax reference at the first tile and must notice that its exponent headroom
-    (2^60) is exceeded and repeat the pass; the result must still match the oracle."""
-    wl = inputs.Workload("mla_spike", B=1, L=420, H=2, S=1, d_pool=512, d_sel=64, g=16, w=64, dtype="bf16", seed=77)
+    (2^60; fp16: 2^19) is exceeded and repeat the pass; the result must still match the oracle."""
+    wl = inputs.Workload("mla_spike", B=1, L=420, H=2, S=1, d_pool=512, d_sel=64, g=16, w=64, dtype=dtype, seed=77)
     Q, POOL, SEL = inputs.gen_all(wl)
     Qf = inputs.to_f64(Q, wl.dtype)
     # make tokens 300 (raw window of the last rows) and 40 (inside a condensed group) line up with the queries' mean direction
@@ -234,11 +253,12 @@ def test_mla_logits_far_above_first_tile(oracle, dense_only):
         hp.check_prefill(oracle, wl, run, rows, Qf, POOLf, SELf, ref, differ)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("dense_only", [False, True])
-def test_gqa_logits_far_above_first_tile(oracle, dense_only):
+def test_gqa_logits_far_above_first_tile(oracle, dense_only, dtype):
     """The same situation at the GQA widths: keys of two tokens score ~100 nats above the first key tile, in
     every KV head, so the 128-wide kernel's repeat pass has to run."""
-    wl = inputs.Workload("gqa_spike", B=1, L=420, H=8, S=2, d_pool=128, d_sel=128, g=16, w=64, dtype="bf16", mode=inputs.MODE_GQA,
+    wl = inputs.Workload("gqa_spike", B=1, L=420, H=8, S=2, d_pool=128, d_sel=128, g=16, w=64, dtype=dtype, mode=inputs.MODE_GQA,
                          theta=500000.0, seed=78)
     Q, POOL, SEL = inputs.gen_all(wl)
     Qf, SELf = inputs.to_f64(Q, wl.dtype), inputs.to_f64(SEL, wl.dtype)
