@@ -253,6 +253,37 @@ def test_mla_logits_far_above_first_tile(oracle, dense_only, dtype):
         hp.check_prefill(oracle, wl, run, rows, Qf, POOLf, SELf, ref, differ)
 
 
+@pytest.mark.parametrize("gain", [7.0, 9.0, 11.0, 13.0])
+def test_mla_fp16_logits_around_the_type_limit(oracle, gain):
+    """fp16 exponentials end at 65504 = 2^16: with the reference 4 binades above a row's first maximum, a later logit
+    up to ~2^20 times (13.9 nats) larger still fits, one beyond makes the kernel repeat the item.  The gains put the
+    largest logit of the late rows on both sides of that limit; every case must match the oracle."""
+    wl = inputs.Workload("mla_limit16", B=1, L=420, H=2, S=1, d_pool=512, d_sel=64, g=16, w=64, dtype="f16", seed=79)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    Qf, POOLf = inputs.to_f64(Q, wl.dtype), inputs.to_f64(POOL, wl.dtype)
+    qdir = Qf[0, :, :, :512].mean(axis=(0, 1))
+    qdir /= np.linalg.norm(qdir)
+    Qf[0, :, :, :512] += 2.0 * qdir
+    for tok in (40, 300):
+        POOLf[0, tok] = gain * qdir
+    Q, POOL = inputs.to_storage(Qf, wl.dtype), inputs.to_storage(POOLf, wl.dtype)
+    Qf, POOLf, SELf = (inputs.to_f64(x, wl.dtype) for x in (Q, POOL, SEL))
+    keys = np.concatenate([POOLf[0], SELf[0]], -1)
+    spreads = []
+    for t in range(301, wl.L):
+        for h in range(wl.H):
+            lg = keys[:t + 1] @ Qf[0, t, h]
+            spreads.append(lg.max() - lg[:32].max())
+    print(f"  gain {gain}: largest logit above the first tile's maximum by {min(spreads):.1f} .. {max(spreads):.1f} nats", flush=True)
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense()
+    ref, differ = hp.check_condense(oracle, wl, run, Qf[:, wl.L - wl.nq:], POOLf, SELf)
+    rows = np.arange(wl.L, dtype=np.int32)
+    run.prefill()
+    hp.check_prefill(oracle, wl, run, rows, Qf, POOLf, SELf, ref, differ)
+    run.dense()
+    hp.check_dense(oracle, wl, run, rows, Qf, POOLf, SELf)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("dense_only", [False, True])
 def test_gqa_logits_far_above_first_tile(oracle, dense_only, dtype):
