@@ -199,6 +199,21 @@ lca_status lca_deviation_stats(const lca_desc *desc, const void *POOL, const voi
                                const void *sel_rep, float *stats, void *workspace, size_t workspace_bytes,
                                void *stream);
 
+/*
+ * 8-bit copy of the representatives, for decoding over a cache half the size (the paper's limitations section
+ * names lower precisions as unexplored: the format is this library's).  Codes are OCP FP8 E4M3 bytes; every
+ * representative row has one power-of-two scale per component, chosen so that the row's largest magnitude
+ * lands in (224, 448] (1 for an all-zero row); a value x is stored as the code nearest to x / scale (ties to
+ * even, the sign of x kept) and stands for decode(code) * scale.  The raw tail stays in the 16-bit type.
+ * desc->L, the layout (may be NULL: m_cap = m) and the row counts are those of lca_decode_attn_cached; only
+ * rows [0, m) of every (sequence, set) are read and written.  desc->dtype must be a 16-bit type.
+ * In:  pool_rep [B,S,m_cap,d_pool], sel_rep [B,S,m_cap,d_sel].
+ * Out: pool_q8 [B,S,m_cap,d_pool], sel_q8 [B,S,m_cap,d_sel] bytes (8-byte aligned rows: d_pool, d_sel are multiples
+ *      of 8), scales [B,S,m_cap,2] float (pooled, selected).
+ */
+lca_status lca_quantize_cache(const lca_desc *desc, const lca_cache_layout *layout, const void *pool_rep, const void *sel_rep,
+                              uint8_t *pool_q8, uint8_t *sel_q8, float *scales, void *stream);
+
 /* Message for the calling thread's last non-OK status; never NULL. */
 const char *lca_last_error(void);
 

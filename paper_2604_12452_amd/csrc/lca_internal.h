@@ -80,6 +80,16 @@ int decode_mla_parts(const Dims &d);
 hipError_t launch_decode_mla(const DecodeArgs &a, hipStream_t st);
 hipError_t launch_cache_update(const UpdateArgs &a, hipStream_t st);
 
+// 8-bit copy of the representatives in use: codes [.., m_cap, d] and scales [.., m_cap, 2] (pooled, selected).
+struct QuantArgs {
+    Dims d;
+    const void *pool_rep, *sel_rep;
+    uint8_t *pool_q8, *sel_q8;
+    float *scales;
+    int m_cap;
+};
+hipError_t launch_quantize_cache(const QuantArgs &a, hipStream_t st);
+
 // Deviation statistics: per-group partial sums [B,S,m,6] in the workspace, then one reduction per (sequence, set).
 struct DeviationArgs {
     Dims d;

@@ -20,7 +20,8 @@ BF16, F32, F16 = 0, 1, 2
 REDUCE_DEFAULT, REDUCE_WEIGHTED, REDUCE_MEAN, REDUCE_MAXSEL, REDUCE_MAXPOOL = range(5)
 
 EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condense", "lca_prefill_attn", "dense_mla_attn",
-           "lca_decode_attn", "lca_decode_attn_cached", "lca_cache_update", "lca_deviation_stats", "lca_last_error")
+           "lca_decode_attn", "lca_decode_attn_cached", "lca_cache_update", "lca_deviation_stats", "lca_quantize_cache",
+           "lca_last_error")
 
 
 class LcaError(RuntimeError):
@@ -187,6 +188,13 @@ def cache_update(desc: Desc, layout: CacheLayout, q_recent, pool_tail, sel_tail,
     cd, cl = desc.c(), layout.c()
     _check(load().lca_cache_update(ctypes.byref(cd), ctypes.byref(cl), _ptr(q_recent), _ptr(pool_tail), _ptr(sel_tail), _ptr(pool_rep),
                                    _ptr(sel_rep), _ptr(anchor_idx), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
+
+
+def quantize_cache(desc: Desc, layout, pool_rep, sel_rep, pool_q8, sel_q8, scales, stream=None):
+    cd = desc.c()
+    cl = layout.c() if layout is not None else None
+    _check(load().lca_quantize_cache(ctypes.byref(cd), ctypes.byref(cl) if cl is not None else None, _ptr(pool_rep), _ptr(sel_rep),
+                                     _ptr(pool_q8), _ptr(sel_q8), _ptr(scales), _stream(stream)))
 
 
 def deviation_stats(desc: Desc, POOL, SEL, pool_rep, sel_rep, stats, workspace, stream=None):
