@@ -132,6 +132,17 @@ def decode_bench(wl, lca, hp, torch, tdt):
     nbytes = B * wd.S * (m + k) * (wd.d_pool + wd.d_sel) * 2
     out = {"B": B, "L": wd.L, "m": m, "k": k, "ms_decode_step": ms, "algorithmic_bytes": nbytes,
            "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    if wd.mode == 0 and wd.d_pool == 512 and wd.d_sel == 64:
+        # the same step over 8-bit representatives (E4M3 codes + row scales; the tail stays 16-bit)
+        pq, sq = torch.empty_like(pool_rep, dtype=torch.uint8), torch.empty_like(sel_rep, dtype=torch.uint8)
+        sc = torch.empty((B, wd.S, m, 2), dtype=torch.float32, device="cuda")
+        out["ms_quantize_cache"] = time_kernel(lambda: lca.quantize_cache(desc, None, pool_rep, sel_rep, pq, sq, sc), 10, 2)
+        ms8 = time_kernel(lambda: lca.decode_attn_q8(desc, None, q, pq, sq, sc, pool_tail, sel_tail, O, ws), 20, 3)
+        nb8 = B * wd.S * (m * (wd.d_pool + wd.d_sel + 8) + k * (wd.d_pool + wd.d_sel) * 2)
+        out["q8"] = {"ms_decode_step": ms8, "algorithmic_bytes": nb8, "GBps": nb8 / (ms8 * 1e-3) / 1e9,
+                     "frac_of_hbm_peak": nb8 / (ms8 * 1e-3) / 1e9 / PEAK_HBM_GBS, "speedup_vs_16bit_cache": ms / ms8,
+                     "cache_bytes_per_sequence": wd.S * m * (wd.d_pool + wd.d_sel + 8) + k * (wd.d_pool + wd.d_sel) * 2}
+        del pq, sq, sc
     # the same step over a growing cache (spare rows, ring tail that wraps), and the online update that runs every g-th step
     m_cap, k_cap = m + 64, wd.w + wd.g
     lay = lca.CacheLayout(m_cap=m_cap, k_cap=k_cap, k_start=k_cap - 100)

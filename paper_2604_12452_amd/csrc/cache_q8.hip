@@ -47,34 +47,40 @@ __device__ __forceinline__ int scale_exponent(float amax)
     return f <= 0.875f ? e - 9 : e - 8;
 }
 
-// one component (width d, a multiple of 8) of one row: codes to dst, the scale returned
+// one component (width d <= 1024, a multiple of 8) of one row: codes to dst, the scale returned
 template <typename T>
 __device__ __forceinline__ float quantize_component(const T *src, uint8_t *dst, int d, int lane)
 {
+    float f[2][8];
     float amax = 0.f;
-    for (int x = lane * 8; x < d; x += 512) {
-        float f[8];
-        unpack8<T>(*reinterpret_cast<const uint4 *>(src + x), f);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[i]));
+    for (int c = 0; c < 2; ++c) {
+        const int x = c * 512 + lane * 8;
+        if (x < d) {
+            unpack8<T>(*reinterpret_cast<const uint4 *>(src + x), f[c]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[c][i]));
+        }
     }
     amax = wave_max(amax);
     const int e = scale_exponent(amax);
-    for (int x = lane * 8; x < d; x += 512) {
-        float f[8];
-        unpack8<T>(*reinterpret_cast<const uint4 *>(src + x), f);      // (a second read of a row that is in the cache)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) f[i] = ldexpf(f[i], -e);           // exact
-        uint2 out;
-        unsigned w = 0;
-        w = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], w, false);
-        w = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], w, true);
-        out.x = w;
-        w = 0;
-        w = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], w, false);
-        w = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], w, true);
-        out.y = w;
-        *reinterpret_cast<uint2 *>(dst + x) = out;
+    for (int c = 0; c < 2; ++c) {
+        const int x = c * 512 + lane * 8;
+        if (x < d) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) f[c][i] = ldexpf(f[c][i], -e);     // exact
+            uint2 out;
+            unsigned w = 0;
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(f[c][0], f[c][1], w, false);
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(f[c][2], f[c][3], w, true);
+            out.x = w;
+            w = 0;
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(f[c][4], f[c][5], w, false);
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(f[c][6], f[c][7], w, true);
+            out.y = w;
+            *reinterpret_cast<uint2 *>(dst + x) = out;
+        }
     }
     return ldexpf(1.f, e);
 }

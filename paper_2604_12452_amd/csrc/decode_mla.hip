@@ -56,6 +56,8 @@ constexpr float LN2 = 0.6931471805599453f;
 
 struct DmParams {
     const uint16_t *q, *pool_rep, *sel_rep, *pool_tail, *sel_tail;
+    const uint8_t *pool_q8, *sel_q8;       // 8-bit representatives (E4M3 codes) and their row scales [.., m_cap, 2], or NULL
+    const float *scales;
     float *part;
     int S, hps, m, k, n_parts, m_cap, k_cap, k_start;
     float scale_log2, bias_log2;
@@ -74,7 +76,31 @@ __device__ __forceinline__ void dma_lanes(const void *addr, unsigned lds_addr)  
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(addr), "s"(lds_addr));
 }
 
-template <typename E>
+// Two E4M3 codes (the low or the high half of w) times a power-of-two scale, as two elements of type E: exact.
+template <typename E> __device__ __forceinline__ unsigned cvt2_fp8(unsigned w, float scale, bool high);
+template <> __device__ __forceinline__ unsigned cvt2_fp8<__bf16>(unsigned w, float scale, bool high)
+{
+    return high ? __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, scale, true))
+                : __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, scale, false));
+}
+template <> __device__ __forceinline__ unsigned cvt2_fp8<_Float16>(unsigned w, float scale, bool high)
+{
+    return high ? __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, scale, true))
+                : __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, scale, false));
+}
+// 16 codes -> 16 elements (two 16-byte pieces)
+template <typename E> __device__ __forceinline__ void cvt16_fp8(const uint4 &c, float scale, uint4 &lo, uint4 &hi)
+{
+    lo = make_uint4(cvt2_fp8<E>(c.x, scale, false), cvt2_fp8<E>(c.x, scale, true), cvt2_fp8<E>(c.y, scale, false), cvt2_fp8<E>(c.y, scale, true));
+    hi = make_uint4(cvt2_fp8<E>(c.z, scale, false), cvt2_fp8<E>(c.z, scale, true), cvt2_fp8<E>(c.w, scale, false), cvt2_fp8<E>(c.w, scale, true));
+}
+
+// Q8: the representatives come as E4M3 codes with a power-of-two scale per row and component.  A tile then holds
+// entries of one kind only (the list of tiles is the representatives' tiles followed by the tail's), and a tile of
+// representatives is fetched into registers (its 16 KB + 2 KB of codes are contiguous), converted -- one instruction
+// per two codes, the row's scale riding along -- and written into the same LDS layout the 16-bit tiles use; from
+// there on nothing differs.
+template <typename E, bool Q8>
 __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
 {
     typedef E ex8 __attribute__((ext_vector_type(8)));
@@ -88,9 +114,11 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
     const int part = (blockIdx.x % wg_per_bs) * 4 + wave, bs = blockIdx.x / wg_per_bs;
     const int b = bs / kp.S;
     const int m = kp.m, n = kp.m + kp.k;
-    const int tiles_total = (n + BN - 1) / BN, tiles_per_part = (tiles_total + kp.n_parts - 1) / kp.n_parts;
+    const int rep_tiles = Q8 ? (m + BN - 1) / BN : 0;                       // Q8: tiles [0, rep_tiles) hold representatives only
+    const int tiles_total = Q8 ? rep_tiles + (kp.k + BN - 1) / BN : (n + BN - 1) / BN;
+    const int tiles_per_part = (tiles_total + kp.n_parts - 1) / kp.n_parts;
     const int t_lo = min(part * tiles_per_part, tiles_total), t_hi = min(t_lo + tiles_per_part, tiles_total);
-    const int e_hi = min(n, t_hi * BN);
+    const int e_hi = Q8 ? n : min(n, t_hi * BN);
     char *buf = bufs[wave];
     const unsigned buf_lds = lds_address(buf);
 
@@ -125,14 +153,65 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
 
     // copy of tile tl into this wavefront's buffer, S^T = K Q^T for its two blocks of 16 entries, and the logits in base 2
     // (scale, bias of the representatives, entries past the range hidden)
-    auto tile_logits = [&](int tl, float (&lg)[2][4]) {
+    // Q8: the codes of one tile of representatives in registers.  Load i brings rows 2i, 2i+1 of the latent part (lane l:
+    // 16 codes at column 16 (l & 31) of row 2i + (l >> 5)), load j rows 16j .. 16j+15 of the RoPE part (lane l: 16 codes
+    // at column 16 (l & 3) of row 16j + (l >> 2)); lane r < 32 holds the two scales of row r.  Rows past the end repeat
+    // the last one.
+    uint4 q8_pool[BN / 2], q8_sel[2];
+    float2 q8_scale = float2{1.f, 1.f};
+    int q8_in_regs = -1;
+    auto fetch_q8 = [&](int tl) {
+        const uint8_t *pq = kp.pool_q8 + (size_t)bs * kp.m_cap * DP, *sq = kp.sel_q8 + (size_t)bs * kp.m_cap * DS;
         const int e0 = tl * BN;
+#pragma unroll
+        for (int i = 0; i < BN / 2; ++i) {
+            const int e = min(e0 + 2 * i + (lane >> 5), m - 1);
+            q8_pool[i] = *reinterpret_cast<const uint4 *>(pq + (size_t)e * DP + 16 * (lane & 31));
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int e = min(e0 + 16 * j + (lane >> 2), m - 1);
+            q8_sel[j] = *reinterpret_cast<const uint4 *>(sq + (size_t)e * DS + 16 * (lane & 3));
+        }
+        q8_scale = *reinterpret_cast<const float2 *>(kp.scales + ((size_t)bs * kp.m_cap + min(e0 + (lane & 31), m - 1)) * 2);
+        q8_in_regs = tl;
+    };
+
+    auto tile_logits = [&](int tl, float (&lg)[2][4]) {
+        // first entry of the tile and the end of the entries it may show (Q8: the end of its kind)
+        const bool q8_tile = Q8 && tl < rep_tiles;
+        const int e0 = !Q8 ? tl * BN : q8_tile ? tl * BN : m + (tl - rep_tiles) * BN;
+        const int seg_end = !Q8 ? e_hi : q8_tile ? m : n;
         // 32 latent rows (one load each), RoPE parts of 8 rows per load; rows past the range repeat its last row
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                  // this wavefront's reads of the previous tile are done
         const int e_last = e0 + BN - 1;
         // the usual tile: 32 consecutive rows of one buffer (no end of range, no rep/tail seam, no wrap of the ring)
         const bool in_rep = e_last < m, in_tail = e0 >= m && ring_row(e0) + BN <= kp.k_cap;
-        if (e_last < e_hi && (in_rep || in_tail)) {
+        if (q8_tile) {
+            if (q8_in_regs != tl) fetch_q8(tl);
+            // convert (one instruction per two codes, the row's scale riding along) and write the 16-bit layout
+#pragma unroll
+            for (int i = 0; i < BN / 2; ++i) {
+                const float s0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, q8_scale.x), 2 * i));
+                const float s1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, q8_scale.x), 2 * i + 1));
+                uint4 lo, hi;
+                cvt16_fp8<E>(q8_pool[i], lane < 32 ? s0 : s1, lo, hi);
+                char *dst = buf + (2 * i + (lane >> 5)) * RSB + 32 * (lane & 31);
+                *reinterpret_cast<uint4 *>(dst) = lo;
+                *reinterpret_cast<uint4 *>(dst + 16) = hi;
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int r = 16 * j + (lane >> 2), c0 = 2 * (lane & 3);        // chunk c of row r sits at slot c ^ (r & 7)
+                uint4 lo, hi;
+                cvt16_fp8<E>(q8_sel[j], __shfl(q8_scale.y, r, 64), lo, hi);
+                char *dst = buf + SEL_OFF + r * (DS * 2);
+                *reinterpret_cast<uint4 *>(dst + ((c0 ^ (r & 7)) << 4)) = lo;
+                *reinterpret_cast<uint4 *>(dst + (((c0 + 1) ^ (r & 7)) << 4)) = hi;
+            }
+            // the next tile's codes travel while this one is used
+            if (tl + 1 < t_hi && tl + 1 < rep_tiles) fetch_q8(tl + 1);
+        } else if (e_last < seg_end && (in_rep || in_tail)) {
             const size_t row0 = in_rep ? e0 : ring_row(e0);
             const char *pb0 = (const char *)((in_rep ? prep : ptail) + row0 * DP);
             const char *sb0 = (const char *)((in_rep ? srep : stail) + row0 * DS);
@@ -146,19 +225,19 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
         } else {
 #pragma unroll 4
             for (int r = 0; r < BN; ++r) {
-                const int e = min(e0 + r, e_hi - 1);
+                const int e = min(e0 + r, seg_end - 1);
                 const uint16_t *src = e < m ? prep + (size_t)e * DP : ptail + (size_t)ring_row(e) * DP;
                 dma_row(lane * 16, src, buf_lds + r * RSB);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int r = 8 * j + (lane >> 3);
-                const int e = min(e0 + r, e_hi - 1);
+                const int e = min(e0 + r, seg_end - 1);
                 const uint16_t *src = (e < m ? srep + (size_t)e * DS : stail + (size_t)ring_row(e) * DS) + (((lane & 7) ^ (r & 7)) << 3);
                 dma_lanes(src, buf_lds + SEL_OFF + 8 * j * (DS * 2));
             }
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                   // ... has landed (the other wavefronts of the CU cover the wait)
+        if (!q8_tile) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // ... has landed (the other wavefronts of the CU cover the wait)
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
             ex8 kf[NKS];
@@ -176,7 +255,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int e = e0 + blk * 16 + 4 * r + q4;                   // accumulator row 4 q4 + r sits in LDS row 4 r + q4
-                lg[blk][r] = e < e_hi ? fmaf(sacc[r], c, e < m ? kp.bias_log2 : 0.f) : -INFINITY;
+                lg[blk][r] = e < seg_end ? fmaf(sacc[r], c, e < m ? kp.bias_log2 : 0.f) : -INFINITY;
             }
         }
     };
@@ -315,7 +394,7 @@ bool decode_mla_supported(const Dims &d)
 // at least two tiles per wavefront where the cache is long enough
 int decode_mla_parts(const Dims &d)
 {
-    const int tiles = (d.m + d.k + BN - 1) / BN;
+    const int tiles = (d.m + BN - 1) / BN + (d.k + BN - 1) / BN;      // (an upper bound when the two kinds share tiles)
     int wgs = (256 + d.B * d.S - 1) / (d.B * d.S);
     const int max_wgs = (tiles + 7) / 8;
     if (wgs > max_wgs) wgs = max_wgs;
@@ -333,10 +412,15 @@ hipError_t launch_decode_mla(const DecodeArgs &a, hipStream_t st)
     kp.m_cap = a.m_cap; kp.k_cap = a.k_cap; kp.k_start = a.k_start;
     kp.scale_log2 = d.scale * 1.4426950408889634f;
     kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
-    if (d.dtype == LCA_F16)
-        decode_mla_kernel<_Float16><<<d.B * d.S * (a.splits / 4), 256, 0, st>>>(kp);
-    else
-        decode_mla_kernel<__bf16><<<d.B * d.S * (a.splits / 4), 256, 0, st>>>(kp);
+    kp.pool_q8 = a.pool_q8; kp.sel_q8 = a.sel_q8; kp.scales = a.scales;
+    const unsigned grid = d.B * d.S * (a.splits / 4);
+    if (a.pool_q8 != nullptr) {
+        if (d.dtype == LCA_F16) decode_mla_kernel<_Float16, true><<<grid, 256, 0, st>>>(kp);
+        else decode_mla_kernel<__bf16, true><<<grid, 256, 0, st>>>(kp);
+    } else {
+        if (d.dtype == LCA_F16) decode_mla_kernel<_Float16, false><<<grid, 256, 0, st>>>(kp);
+        else decode_mla_kernel<__bf16, false><<<grid, 256, 0, st>>>(kp);
+    }
     return hipGetLastError();
 }
 

@@ -274,6 +274,36 @@ lca_status lca_quantize_cache(const lca_desc *desc, const lca_cache_layout *layo
     return hip_status(lca::launch_quantize_cache(a, static_cast<hipStream_t>(stream)), "lca_quantize_cache");
 }
 
+lca_status lca_decode_attn_q8(const lca_desc *desc, const lca_cache_layout *layout, const void *q, const uint8_t *pool_q8, const uint8_t *sel_q8,
+                              const float *scales, const void *pool_tail, const void *sel_tail, void *O, void *workspace, size_t workspace_bytes_,
+                              void *stream)
+{
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    if (!lca::decode_mla_supported(d))
+        return fail(LCA_ERR_UNSUPPORTED, "lca_decode_attn_q8 is built for the MLA widths (512 + 64) in a 16-bit type with at most 16 heads per set");
+    if (layout != nullptr) LCA_TRY(check_layout(d, layout, d.k));
+    LCA_TRY(check_ptr(q, "q"));
+    LCA_TRY(check_ptr(pool_q8, "pool_q8", d.m > 0));
+    LCA_TRY(check_ptr(sel_q8, "sel_q8", d.m > 0));
+    if (d.m > 0 && (scales == nullptr || (reinterpret_cast<uintptr_t>(scales) & 7))) return fail(LCA_ERR_INVALID_ARG, "scales is NULL or not 8-byte aligned");
+    LCA_TRY(check_ptr(pool_tail, "pool_tail"));
+    LCA_TRY(check_ptr(sel_tail, "sel_tail"));
+    LCA_TRY(check_ptr(O, "O"));
+    LCA_TRY(check_ws(d, workspace, workspace_bytes_));
+    lca::DecodeArgs a;
+    a.d = d; a.q = q; a.pool_rep = nullptr; a.sel_rep = nullptr; a.pool_tail = pool_tail; a.sel_tail = sel_tail; a.O = O;
+    a.pool_q8 = pool_q8; a.sel_q8 = sel_q8; a.scales = scales;
+    a.part = static_cast<float *>(workspace);
+    a.splits = lca::decode_splits(d);
+    a.m_cap = layout ? layout->m_cap : d.m;
+    a.k_cap = layout ? layout->k_cap : d.k;
+    a.k_start = layout ? layout->k_start : 0;
+    // (with m = 0 there are no representatives: the kernel for the 16-bit cache reads the tail alone)
+    if (d.m == 0) { a.pool_q8 = nullptr; a.sel_q8 = nullptr; a.scales = nullptr; }
+    return hip_status(lca::launch_decode(a, static_cast<hipStream_t>(stream)), "lca_decode_attn_q8");
+}
+
 lca_status lca_deviation_stats(const lca_desc *desc, const void *POOL, const void *SEL, const void *pool_rep, const void *sel_rep, float *stats,
                                void *workspace, size_t workspace_bytes_, void *stream)
 {

@@ -45,6 +45,8 @@ struct CondenseArgs {
 struct DecodeArgs {
     Dims d;
     const void *q, *pool_rep, *sel_rep, *pool_tail, *sel_tail;
+    const uint8_t *pool_q8 = nullptr, *sel_q8 = nullptr;   // 8-bit representatives instead of pool_rep / sel_rep (MLA widths only)
+    const float *scales = nullptr;
     void *O;
     float *part;              // workspace: split partials
     int splits;

@@ -21,7 +21,7 @@ REDUCE_DEFAULT, REDUCE_WEIGHTED, REDUCE_MEAN, REDUCE_MAXSEL, REDUCE_MAXPOOL = ra
 
 EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condense", "lca_prefill_attn", "dense_mla_attn",
            "lca_decode_attn", "lca_decode_attn_cached", "lca_cache_update", "lca_deviation_stats", "lca_quantize_cache",
-           "lca_last_error")
+           "lca_decode_attn_q8", "lca_last_error")
 
 
 class LcaError(RuntimeError):
@@ -195,6 +195,14 @@ def quantize_cache(desc: Desc, layout, pool_rep, sel_rep, pool_q8, sel_q8, scale
     cl = layout.c() if layout is not None else None
     _check(load().lca_quantize_cache(ctypes.byref(cd), ctypes.byref(cl) if cl is not None else None, _ptr(pool_rep), _ptr(sel_rep),
                                      _ptr(pool_q8), _ptr(sel_q8), _ptr(scales), _stream(stream)))
+
+
+def decode_attn_q8(desc: Desc, layout, q, pool_q8, sel_q8, scales, pool_tail, sel_tail, O, workspace, stream=None):
+    cd = desc.c()
+    cl = layout.c() if layout is not None else None
+    _check(load().lca_decode_attn_q8(ctypes.byref(cd), ctypes.byref(cl) if cl is not None else None, _ptr(q), _ptr(pool_q8), _ptr(sel_q8),
+                                     _ptr(scales), _ptr(pool_tail), _ptr(sel_tail), _ptr(O), _ptr(workspace),
+                                     ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
 
 
 def deviation_stats(desc: Desc, POOL, SEL, pool_rep, sel_rep, stats, workspace, stream=None):
