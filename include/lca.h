@@ -206,13 +206,15 @@ lca_status lca_deviation_stats(const lca_desc *desc, const void *POOL, const voi
  * lands in (224, 448] (1 for an all-zero row); a value x is stored as the code nearest to x / scale (ties to
  * even, the sign of x kept) and stands for decode(code) * scale.  The raw tail stays in the 16-bit type.
  * desc->L, the layout (may be NULL: m_cap = m) and the row counts are those of lca_decode_attn_cached; only
- * rows [0, m) of every (sequence, set) are read and written.  desc->dtype must be a 16-bit type.
+ * rows [first_row, m) of every (sequence, set) are read and written (0 after a prefill; m - 1 after an
+ * lca_cache_update, which adds row m - 1).  desc->dtype must be a 16-bit type.  Invalid in addition:
+ * first_row outside [0, m].
  * In:  pool_rep [B,S,m_cap,d_pool], sel_rep [B,S,m_cap,d_sel].
  * Out: pool_q8 [B,S,m_cap,d_pool], sel_q8 [B,S,m_cap,d_sel] bytes (8-byte aligned rows: d_pool, d_sel are multiples
  *      of 8), scales [B,S,m_cap,2] float (pooled, selected).
  */
-lca_status lca_quantize_cache(const lca_desc *desc, const lca_cache_layout *layout, const void *pool_rep, const void *sel_rep,
-                              uint8_t *pool_q8, uint8_t *sel_q8, float *scales, void *stream);
+lca_status lca_quantize_cache(const lca_desc *desc, const lca_cache_layout *layout, int32_t first_row, const void *pool_rep,
+                              const void *sel_rep, uint8_t *pool_q8, uint8_t *sel_q8, float *scales, void *stream);
 
 /*
  * lca_decode_attn_cached over the 8-bit representatives lca_quantize_cache wrote (layout may be NULL: m_cap = m,

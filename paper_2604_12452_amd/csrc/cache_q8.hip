@@ -88,12 +88,13 @@ __device__ __forceinline__ float quantize_component(const T *src, uint8_t *dst, 
 template <typename T>
 __global__ __launch_bounds__(256) void quantize_kernel(const T *__restrict__ pool_rep, const T *__restrict__ sel_rep,
                                                        uint8_t *__restrict__ pool_q8, uint8_t *__restrict__ sel_q8,
-                                                       float *__restrict__ scales, int m, int m_cap, int sets, int d_pool, int d_sel)
+                                                       float *__restrict__ scales, int first, int n, int m_cap, int sets, int d_pool,
+                                                       int d_sel)
 {
     const int lane = threadIdx.x & 63;
-    const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);        // over (set, representative) pairs in use
-    if (row >= (long)sets * m) return;
-    const long r = (row / m) * m_cap + row % m;                        // row of the allocated buffers
+    const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);        // over (set, row in [first, first + n)) pairs
+    if (row >= (long)sets * n) return;
+    const long r = (row / n) * m_cap + first + row % n;                // row of the allocated buffers
     const float sp = quantize_component<T>(pool_rep + r * d_pool, pool_q8 + r * d_pool, d_pool, lane);
     const float ss = quantize_component<T>(sel_rep + r * d_sel, sel_q8 + r * d_sel, d_sel, lane);
     if (lane == 0) {
@@ -107,15 +108,16 @@ __global__ __launch_bounds__(256) void quantize_kernel(const T *__restrict__ poo
 hipError_t launch_quantize_cache(const QuantArgs &a, hipStream_t st)
 {
     const Dims &d = a.d;
-    if (d.m == 0) return hipSuccess;
-    const long rows = (long)d.B * d.S * d.m;
+    const int n = d.m - a.first_row;
+    if (n <= 0) return hipSuccess;
+    const long rows = (long)d.B * d.S * n;
     const unsigned grid = (unsigned)((rows + 3) / 4);
     if (d.dtype == LCA_F16)
-        quantize_kernel<f16_t><<<grid, 256, 0, st>>>((const f16_t *)a.pool_rep, (const f16_t *)a.sel_rep, a.pool_q8, a.sel_q8, a.scales, d.m, a.m_cap,
-                                                     d.B * d.S, d.d_pool, d.d_sel);
+        quantize_kernel<f16_t><<<grid, 256, 0, st>>>((const f16_t *)a.pool_rep, (const f16_t *)a.sel_rep, a.pool_q8, a.sel_q8, a.scales, a.first_row, n,
+                                                     a.m_cap, d.B * d.S, d.d_pool, d.d_sel);
     else
-        quantize_kernel<uint16_t><<<grid, 256, 0, st>>>((const uint16_t *)a.pool_rep, (const uint16_t *)a.sel_rep, a.pool_q8, a.sel_q8, a.scales, d.m,
-                                                        a.m_cap, d.B * d.S, d.d_pool, d.d_sel);
+        quantize_kernel<uint16_t><<<grid, 256, 0, st>>>((const uint16_t *)a.pool_rep, (const uint16_t *)a.sel_rep, a.pool_q8, a.sel_q8, a.scales, a.first_row,
+                                                        n, a.m_cap, d.B * d.S, d.d_pool, d.d_sel);
     return hipGetLastError();
 }
 

@@ -255,14 +255,15 @@ lca_status lca_cache_update(const lca_desc *desc, const lca_cache_layout *layout
     return hip_status(lca::launch_cache_update(a, static_cast<hipStream_t>(stream)), "lca_cache_update");
 }
 
-lca_status lca_quantize_cache(const lca_desc *desc, const lca_cache_layout *layout, const void *pool_rep, const void *sel_rep, uint8_t *pool_q8,
-                              uint8_t *sel_q8, float *scales, void *stream)
+lca_status lca_quantize_cache(const lca_desc *desc, const lca_cache_layout *layout, int32_t first_row, const void *pool_rep, const void *sel_rep,
+                              uint8_t *pool_q8, uint8_t *sel_q8, float *scales, void *stream)
 {
     lca::Dims d;
     LCA_TRY(make_dims(desc, d));
     if (d.dtype == LCA_F32) return fail(LCA_ERR_UNSUPPORTED, "lca_quantize_cache reads a 16-bit cache");
     if (layout != nullptr) LCA_TRY(check_layout(d, layout, d.k));
-    if (d.m == 0) return LCA_OK;
+    if (first_row < 0 || first_row > d.m) return fail(LCA_ERR_INVALID_ARG, "first_row (%d) must be in [0, m = %d]", first_row, d.m);
+    if (first_row == d.m) return LCA_OK;
     LCA_TRY(check_ptr(pool_rep, "pool_rep"));
     LCA_TRY(check_ptr(sel_rep, "sel_rep"));
     LCA_TRY(check_ptr(pool_q8, "pool_q8"));
@@ -271,6 +272,7 @@ lca_status lca_quantize_cache(const lca_desc *desc, const lca_cache_layout *layo
     lca::QuantArgs a;
     a.d = d; a.pool_rep = pool_rep; a.sel_rep = sel_rep; a.pool_q8 = pool_q8; a.sel_q8 = sel_q8; a.scales = scales;
     a.m_cap = layout ? layout->m_cap : d.m;
+    a.first_row = first_row;
     return hip_status(lca::launch_quantize_cache(a, static_cast<hipStream_t>(stream)), "lca_quantize_cache");
 }
 

@@ -88,7 +88,7 @@ struct QuantArgs {
     const void *pool_rep, *sel_rep;
     uint8_t *pool_q8, *sel_q8;
     float *scales;
-    int m_cap;
+    int m_cap, first_row;     // rows [first_row, d.m) of every (sequence, set)
 };
 hipError_t launch_quantize_cache(const QuantArgs &a, hipStream_t st);
 

@@ -190,10 +190,10 @@ def cache_update(desc: Desc, layout: CacheLayout, q_recent, pool_tail, sel_tail,
                                    _ptr(sel_rep), _ptr(anchor_idx), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
 
 
-def quantize_cache(desc: Desc, layout, pool_rep, sel_rep, pool_q8, sel_q8, scales, stream=None):
+def quantize_cache(desc: Desc, layout, pool_rep, sel_rep, pool_q8, sel_q8, scales, first_row=0, stream=None):
     cd = desc.c()
     cl = layout.c() if layout is not None else None
-    _check(load().lca_quantize_cache(ctypes.byref(cd), ctypes.byref(cl) if cl is not None else None, _ptr(pool_rep), _ptr(sel_rep),
+    _check(load().lca_quantize_cache(ctypes.byref(cd), ctypes.byref(cl) if cl is not None else None, ctypes.c_int32(first_row), _ptr(pool_rep), _ptr(sel_rep),
                                      _ptr(pool_q8), _ptr(sel_q8), _ptr(scales), _stream(stream)))
 
 

@@ -94,3 +94,75 @@ def test_decode_over_the_quantized_cache(oracle, dtype, H, S, L, g, w, ring):
                                hp.from_dev(run.POOL[:, None, m * g:], dtype), hp.from_dev(run.SEL[:, None, m * g:], dtype))
     print(f"  decode over 8-bit cache: err {err:.2e} against the oracle on the same codes; the codes cost {hp.vec_rel_err(ref, ref16):.2e}", flush=True)
     assert err <= hp.TOL[dtype]
+
+
+def test_decode_loop_over_the_quantized_cache(oracle):
+    """A decoding batch from an empty cache, as in the 16-bit loop test, with an 8-bit mirror of the representatives:
+    every online update writes its 16-bit row, lca_quantize_cache(first_row = m - 1) adds that row's codes (and must
+    leave every other row alone), and every step decodes over (codes, scales, ring) and is checked against the oracle."""
+    import torch
+    from oracle import q8
+    from paper_2604_12452_amd import lca
+    from tests.test_gpu_cache_update import Cache, _storage, _update_and_check
+    B, g, w, H, S = 2, 8, 21, 16, 1
+    steps = w + 5 * g + 3
+    wl = inputs.Workload("loop_q8", B=B, L=1, H=H, S=S, d_pool=512, d_sel=64, g=g, w=w, dtype="bf16", seed=0, scale=1.0 / np.sqrt(576.0))
+    rng = np.random.default_rng(78)
+    cache = Cache(wl, m_cap=6, k_cap=w + g + 2, k_start=5, rng=rng)
+    pq = torch.full((B, S, cache.m_cap, 512), 0x55, dtype=torch.uint8, device="cuda")
+    sq = torch.full((B, S, cache.m_cap, 64), 0x55, dtype=torch.uint8, device="cuda")
+    sc = torch.full((B, S, cache.m_cap, 2), float("nan"), dtype=torch.float32, device="cuda")
+    q_hist, m, worst = [], 0, 0.0
+    for L in range(1, steps + 1):
+        cache.push()
+        q_hist.append(_storage(rng, (B, H, wl.d_qk), "bf16", sigma=2.0))
+        wlL = wl.with_(L=L)
+        desc = hp.lca_desc(wlL)
+        if L >= w + g and (L - w) % g == 0:
+            _update_and_check(oracle, cache, L, np.stack(q_hist[-g:], axis=1), m)
+            m += 1
+            before = (pq.clone(), sq.clone(), sc.clone())
+            lca.quantize_cache(desc, cache.layout(), cache.pool_rep, cache.sel_rep, pq, sq, sc, first_row=m - 1)
+            torch.cuda.synchronize()
+            keep = [i for i in range(cache.m_cap) if i != m - 1]
+            for new, old in zip((pq, sq, sc), before):
+                assert torch.equal(new[:, :, keep].view(torch.uint8), old[:, :, keep].view(torch.uint8)), "a row other than m - 1 was touched"
+            for codes, src, col in ((pq, cache.pool_rep, 0), (sq, cache.sel_rep, 1)):
+                rc, rs = q8.quantize_rows(hp.from_dev(src[:, :, m - 1], "bf16"))
+                assert np.array_equal(codes[:, :, m - 1].cpu().numpy(), rc)
+                assert np.array_equal(sc[:, :, m - 1, col].cpu().numpy().astype(np.float64), rs)
+        od = hp.oracle_desc(oracle, wlL)
+        assert od.m == m and od.k == cache.k
+        O = torch.full((B, H, 512), float("nan"), dtype=torch.bfloat16, device="cuda")
+        ws = lca.alloc_workspace(desc)
+        lca.decode_attn_q8(desc, cache.layout(), hp.to_dev(q_hist[-1], "bf16"), pq, sq, sc, cache.pool_tail, cache.sel_tail, O, ws)
+        torch.cuda.synchronize()
+        scn = sc.cpu().numpy().astype(np.float64)
+        pr = q8.dequantize_rows(pq.cpu().numpy()[:, :, :m], scn[:, :, :m, 0])
+        sr = q8.dequantize_rows(sq.cpu().numpy()[:, :, :m], scn[:, :, :m, 1])
+        pool_tail, sel_tail = cache.tail_rows(0, cache.k)
+        ref = oracle.decode_attn(od, inputs.to_f64(q_hist[-1], "bf16"), pr, sr, pool_tail, sel_tail)
+        err = hp.vec_rel_err(hp.from_dev(O, "bf16"), ref)
+        assert err <= hp.TOL["bf16"], f"decode rel err {err:.3e} at L = {L}"
+        worst = max(worst, err)
+    assert m == 5
+    print(f"  {steps} steps, {m} updates, worst decode err over the 8-bit cache {worst:.2e}", flush=True)
+
+
+def test_quantize_and_q8_decode_reject_bad_arguments():
+    import ctypes
+    import torch
+    from paper_2604_12452_amd import lca
+    wl = inputs.Workload("bad", B=1, L=200, H=16, S=1, d_pool=512, d_sel=64, g=16, w=40, dtype="bf16")
+    desc = hp.lca_desc(wl)
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(lca.LcaError):
+        lca.quantize_cache(desc, None, buf, buf, buf, buf, buf, first_row=wl.m + 1)
+    with pytest.raises(lca.LcaError):
+        lca.quantize_cache(hp.lca_desc(wl.with_(dtype="f32", d_pool=128, d_sel=32)), None, buf, buf, buf, buf, buf)
+    gqa = inputs.Workload("bad", B=1, L=200, H=8, S=2, d_pool=128, d_sel=128, g=16, w=40, dtype="bf16", mode=inputs.MODE_GQA)
+    with pytest.raises(lca.LcaError) as e:
+        lca.decode_attn_q8(hp.lca_desc(gqa), None, buf, buf, buf, buf, buf, buf, buf, buf)
+    assert e.value.status == lca.ERR_UNSUPPORTED
+    lca.quantize_cache(desc, None, buf, buf, buf, buf, buf, first_row=wl.m)      # nothing to do: valid
+    torch.cuda.synchronize()
