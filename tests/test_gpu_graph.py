@@ -1,0 +1,59 @@
+"""The library under HIP graph capture: it allocates nothing, clears nothing with memsets and launches only on the
+caller's stream, so a serving loop can record a whole step once and replay it.  The graph is replayed several times
+with the program's own eager work and synchronisations in between, and every replay is compared bit for bit with the
+eager result."""
+import numpy as np
+import pytest
+
+from paper_2604_12452_amd import inputs
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("mode,d_pool,d_sel,H,S", [(inputs.MODE_MLA, 512, 64, 16, 1), (inputs.MODE_GQA, 128, 128, 8, 2)])
+def test_prefill_and_decode_replay_in_a_graph(mode, d_pool, d_sel, H, S):
+    import torch
+    from paper_2604_12452_amd import lca
+    wl = inputs.Workload("graph", B=2, L=700, H=H, S=S, d_pool=d_pool, d_sel=d_sel, g=16, w=100, dtype="bf16", mode=mode, seed=91)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    run = hp.GpuRun(wl, Q, POOL, SEL)
+    d = run.desc
+    m, g = wl.m, wl.g
+    pool_rep, sel_rep, anchor, _ = lca.alloc_condensed(d)
+    O = torch.empty((wl.B, wl.L, wl.H, wl.d_pool), dtype=torch.bfloat16, device="cuda")
+    Od = torch.empty((wl.B, wl.H, wl.d_pool), dtype=torch.bfloat16, device="cuda")
+    if mode == inputs.MODE_MLA:
+        pool_tail, sel_tail = run.POOL[:, None, m * g:].contiguous(), run.SEL[:, None, m * g:].contiguous()
+    else:
+        pool_tail, sel_tail = run.POOL[:, m * g:].permute(0, 2, 1, 3).contiguous(), run.SEL[:, m * g:].permute(0, 2, 1, 3).contiguous()
+    q = run.Q[:, wl.L - 1].contiguous()
+    ws = run.ws
+
+    def step():
+        lca.condense(d, run.Q, run.POOL, run.SEL, pool_rep, sel_rep, anchor, None, ws)
+        lca.prefill_attn(d, run.Q, run.POOL, run.SEL, pool_rep, sel_rep, O, None, ws)
+        lca.decode_attn(d, q, pool_rep, sel_rep, pool_tail, sel_tail, Od, ws)
+
+    outs = (pool_rep, sel_rep, anchor, O, Od)
+    step()
+    torch.cuda.synchronize()
+    want = [x.clone() for x in outs]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capturing stream
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for replay in range(4):
+        for x in outs:                           # eager work between the replays: wipe every output
+            x.view(torch.uint8).fill_(0xA5)
+        junk = (torch.randn(1 << 20, device="cuda") * 2).sum()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(outs, want):
+            assert torch.equal(got.view(torch.uint8), ref.view(torch.uint8)), f"replay {replay} differs from the eager run"
+        assert bool(torch.isfinite(junk))
