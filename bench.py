@@ -199,6 +199,9 @@ def main():
     ap.add_argument("--decode-only", action="store_true", help="time only the decode step of 32 sequences over their condensed caches")
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
                     help="16-bit element type of the inputs, the cache and the output (the metric is quoted on bf16)")
+    ap.add_argument("--set", action="append", default=[], metavar="FIELD=INT",
+                    help="override an integer field of the configuration's workload (B, L, H, S, g, w, n_q), e.g. --config cfg5 "
+                         "--set H=28 --set S=4 --set L=131072 for the head layout of the GQA model the paper reports on")
     ap.add_argument("--sweep", action="store_true",
                     help="time the prefill over group sizes, windows, numbers of summary queries and pooling strategies instead")
     ap.add_argument("--pmc-calib", action="store_true",
@@ -215,6 +218,10 @@ def main():
         sys.exit("bench.py: no GPU visible")
     lca.load()   # fails loudly when liblca.so is missing
     wl = inputs.configs()[args.config].with_(dtype=args.dtype)
+    if args.set:
+        over = {k: int(v) for k, v in (kv.split("=") for kv in args.set)}
+        assert set(over) <= {"B", "L", "H", "S", "g", "w", "n_q"}, over
+        wl = wl.with_(name=wl.name + "+" + ",".join(args.set), **over)
     tdt = torch.bfloat16 if args.dtype == "bf16" else torch.float16
     if args.pmc_calib:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)

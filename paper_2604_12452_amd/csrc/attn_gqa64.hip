@@ -1,4 +1,4 @@
-// bf16 / fp16 MFMA attention kernel for the GQA widths (d_k = d_v = 128) with 1, 2 or a multiple of 4 query heads per KV
+// bf16 / fp16 MFMA attention kernel for the GQA widths (d_k = d_v = 128), any number of query heads per KV
 // head, on gfx950: prefill over the condensed context with hard-selected keys and pooled values per KV head
 // (section 5.4 of the paper; attention as in section 4.3, Eq. 10 with the per-query partition of appendix
 // A.2) and, with dense = 1, plain causal attention (section 3, Eq. 5).
@@ -85,7 +85,7 @@ struct G64Params {
     uint16_t *O;
     float *lse;
     int B, L, H, S, g, w, m, dense;
-    int hw, hgs;        // query heads per work item (min(H/S, 4): the wavefronts are hw heads x 4/hw groups of 64 rows); head groups per KV head
+    int hw, hgs;        // query heads per work item (4, 2 or 1, a divisor of H/S: the wavefronts are hw heads x 4/hw groups of 64 rows); head groups per KV head
     int n_qb, n_units;  // query blocks (of 256/hw rows) per sequence; KV-sharing units = B * S * hgs
     unsigned g_magic, units_magic, hgs_magic, s_magic;     // for divisions by g, n_units, hgs and S (udiv_small)
     float scale_log2, bias_log2;
@@ -731,14 +731,18 @@ __global__ __launch_bounds__(64 * NW, 1) void attn_gqa64_kernel(const G64Params 
 
 }  // namespace
 
+// Query heads that share one work item (and with it every K/V tile read): the largest of 4, 2, 1 that divides the heads
+// per KV head; the heads of a KV head then form hps / that many groups (7 heads per KV head: seven groups of one).
+static int heads_per_item(int hps) { return hps % NW == 0 ? NW : hps % 2 == 0 ? 2 : 1; }
+
 bool attn_gqa64_supported(const Dims &d)
 {
     const int hps = d.H / d.S;
     // segment sizes and row offsets travel as 32-bit byte counts
     // ... and item indices are divided with udiv_small
-    const int hw = hps < NW ? hps : NW, rows = BMW * (NW / (hw > 0 ? hw : 1));
+    const int hw = heads_per_item(hps), rows = BMW * (NW / hw);
     const long n_units = (long)d.B * d.S * (hps / hw), n_items = ((long)d.L + rows - 1) / rows * n_units;
-    return (d.dtype == LCA_BF16 || d.dtype == LCA_F16) && d.mode == LCA_MODE_GQA && d.d_pool == D && d.d_sel == D && d.scale > 0.f && (hps == 1 || hps == 2 || hps % NW == 0) &&
+    return (d.dtype == LCA_BF16 || d.dtype == LCA_F16) && d.mode == LCA_MODE_GQA && d.d_pool == D && d.d_sel == D && d.scale > 0.f &&
            (long)(d.L + 4 * BN) * d.S * RB < (1l << 32) && (n_items + 8 * GRID) * n_units < (1l << 32) && (long)d.L * d.g < (1l << 31);
 }
 
@@ -751,7 +755,7 @@ hipError_t launch_attn_gqa64(const AttnArgs &a, hipStream_t st)
     kp.O = (uint16_t *)a.O; kp.lse = a.lse;
     kp.B = d.B; kp.L = d.L; kp.H = d.H; kp.S = d.S; kp.g = d.g; kp.w = d.w; kp.m = d.m; kp.dense = a.dense;
     const int hps = d.H / d.S;
-    kp.hw = hps < NW ? hps : NW;
+    kp.hw = heads_per_item(hps);
     kp.hgs = hps / kp.hw;
     const int rows = BMW * (NW / kp.hw);
     kp.n_qb = (d.L + rows - 1) / rows;

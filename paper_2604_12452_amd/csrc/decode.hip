@@ -464,7 +464,7 @@ int shape_id(const Dims &d)
     const int hps = d.H / d.S;
     const bool mla = d.mode == LCA_MODE_MLA;
     const bool b16 = d.dtype == LCA_BF16 || d.dtype == LCA_F16;    // the 16-bit types share the shapes; the launcher picks the type
-    if (b16 && !mla && d.d_pool == 128 && d.d_sel == 128 && (hps == 1 || hps == 2 || hps == 4 || hps == 8)) return 100 + hps;
+    if (b16 && !mla && d.d_pool == 128 && d.d_sel == 128 && hps >= 1 && hps <= 8) return 100 + hps;
     if (b16 && mla && d.d_pool == 512 && d.d_sel == 64 && (hps == 1 || hps == 16)) return 200 + hps;
     if (d.dtype == LCA_F32 && mla && d.d_pool == 128 && d.d_sel == 32 && (hps == 1 || hps == 4)) return 300 + hps;
     return 0;
@@ -507,7 +507,11 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st)
     switch (shape_id(a.d)) {
     case 101: return f16 ? run_gqa<f16_t, 1>(a, st) : run_gqa<uint16_t, 1>(a, st);
     case 102: return f16 ? run_gqa<f16_t, 2>(a, st) : run_gqa<uint16_t, 2>(a, st);
+    case 103: return f16 ? run_gqa<f16_t, 3>(a, st) : run_gqa<uint16_t, 3>(a, st);
     case 104: return f16 ? run_gqa<f16_t, 4>(a, st) : run_gqa<uint16_t, 4>(a, st);
+    case 105: return f16 ? run_gqa<f16_t, 5>(a, st) : run_gqa<uint16_t, 5>(a, st);
+    case 106: return f16 ? run_gqa<f16_t, 6>(a, st) : run_gqa<uint16_t, 6>(a, st);
+    case 107: return f16 ? run_gqa<f16_t, 7>(a, st) : run_gqa<uint16_t, 7>(a, st);
     case 108: return f16 ? run_gqa<f16_t, 8>(a, st) : run_gqa<uint16_t, 8>(a, st);
     case 201: return f16 ? run<f16_t, 512, 64, true, 1>(a, st) : run<uint16_t, 512, 64, true, 1>(a, st);
     case 216: return f16 ? run<f16_t, 512, 64, true, 16>(a, st) : run<uint16_t, 512, 64, true, 16>(a, st);

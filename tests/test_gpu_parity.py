@@ -137,11 +137,13 @@ def test_mla_topic_shift_inputs(oracle):
 # ---- MFMA kernel at the GQA widths (128 / 128) --------------------------------------------------------
 @pytest.mark.parametrize("B,L,g,w,H,S", [(1, 700, 16, 100, 8, 2), (1, 300, 8, 0, 4, 4), (1, 129, 16, 64, 4, 1), (2, 515, 16, 32, 4, 2),
                                            (2, 260, 4, 7, 16, 2), (1, 31, 4, 2, 8, 2), (1, 1100, 32, 256, 8, 1), (1, 333, 8, 40, 6, 2),
-                                           (2, 777, 16, 128, 2, 2), (1, 513, 32, 0, 4, 2), (3, 70, 4, 5, 4, 1), (1, 1, 1, 0, 4, 1)])
+                                           (2, 777, 16, 128, 2, 2), (1, 513, 32, 0, 4, 2), (3, 70, 4, 5, 4, 1), (1, 1, 1, 0, 4, 1),
+                                           (1, 300, 16, 50, 14, 2), (2, 200, 8, 30, 7, 1), (1, 150, 4, 10, 6, 1), (1, 130, 16, 20, 5, 1)])
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 def test_gqa_mfma_small_all_rows(oracle, B, L, g, w, H, S, dtype):
-    """Heads per KV head of 1, 2, 4 and 8 run the 128-wide kernel (4 wavefronts = heads x groups of 64 rows); 3 heads per
-    KV head (the last case) is served by the older general MFMA kernel."""
+    """Any number of heads per KV head runs the 128-wide kernel: its 4 wavefronts are 4, 2 or 1 heads (the largest of
+    these that divides the heads per KV head) x groups of 64 rows; 7 heads per KV head is the shape of the GQA model the
+    paper reports on, 3, 5 and 6 cover the other divisors."""
     wl = inputs.Workload("gqa_small", B=B, L=L, H=H, S=S, d_pool=128, d_sel=128, g=g, w=w, dtype=dtype, mode=inputs.MODE_GQA,
                          theta=500000.0, seed=11 + L)
     _full_parity(oracle, wl)
@@ -187,6 +189,10 @@ def test_results_are_deterministic(oracle):
     (inputs.MODE_GQA, 128, 128, 8, 2, "f16"),
     (inputs.MODE_MLA, 512, 64, 16, 1, "f16"),
     (inputs.MODE_MLA, 512, 64, 8, 8, "f16"),
+    (inputs.MODE_GQA, 128, 128, 14, 2, "bf16"),      # 7 heads per KV head
+    (inputs.MODE_GQA, 128, 128, 6, 2, "bf16"),
+    (inputs.MODE_GQA, 128, 128, 5, 1, "f16"),
+    (inputs.MODE_GQA, 128, 128, 6, 1, "bf16"),
 ])
 @pytest.mark.parametrize("L,g,w", [(1000, 16, 100), (77, 4, 9), (50, 16, 64)])
 def test_decode_step(oracle, mode, d_pool, d_sel, H, S, dtype, L, g, w):
