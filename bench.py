@@ -233,7 +233,7 @@ def main():
         dec = decode_bench(wl, lca, hp, torch, tdt)
         print(json.dumps({"metric": f"LCA decode step over the condensed cache ({wl.name})", "value": dec["ms_decode_step"], "unit": "ms",
                           "n_gpus": 1, "higher_is_better": False, "dtype": args.dtype, "data": "synthetic",
-                          "roofline": {"bound": "hbm", "kernel": ("decode_mla_kernel" if wl.mode == inputs.MODE_MLA else "decode_gqa_kernel") + " (lca_decode_attn)", "achieved": dec["GBps"], "peak": PEAK_HBM_GBS,
+                          "roofline": {"bound": "hbm", "kernel": ("decode_mla_kernel" if wl.mode == inputs.MODE_MLA else "decode_gqa_mfma_kernel") + " (lca_decode_attn)", "achieved": dec["GBps"], "peak": PEAK_HBM_GBS,
                                        "unit": "GB/s", "frac": dec["frac_of_hbm_peak"], "traffic": None}, "extra": dec}))
         return
     if args.sweep:

@@ -6,6 +6,8 @@
 //                         64/LPR rows per wavefront step, online softmax per lane group, then one
 //                         merge per workgroup; writes (max, sum, unnormalised output) partials.
 //   decode_merge_kernel   merges the splits and writes O.
+// The MLA and GQA layer widths have matrix-core kernels of their own (decode_mla.hip, decode_gqa_mfma.hip), which
+// share the merge kernel; decode_split_kernel serves the other instantiated shapes.
 #include "lca_internal.h"
 
 namespace lca {
@@ -226,154 +228,6 @@ __global__ __launch_bounds__(WAVE *NWAVE) void decode_split_kernel(const T *__re
     for (int x = tid; x < H * (DP + 2); x += WAVE * NWAVE) dst[x] = comb[x];
 }
 
-// Sum over the 16 lanes of a DPP row (every lane gets the total): four rotate-and-add steps.
-__device__ __forceinline__ float row16_allreduce_sum(float x)
-{
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x128, 0xf, 0xf, false));   // row_ror:8
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x124, 0xf, 0xf, false));   // row_ror:4
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x122, 0xf, 0xf, false));   // row_ror:2
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x121, 0xf, 0xf, false));   // row_ror:1
-    return x;
-}
-
-// Decode split kernel for the GQA widths (d_k = d_v = 128, bf16): 16 lanes per cache row, each lane owns one
-// 16-byte chunk of the key AND of the value of that row; 4 rows per wavefront step, GQ_UNROLL steps in flight
-// (all loads of an iteration are issued before any arithmetic), one softmax rescale per iteration.
-constexpr int GQ_UNROLL = 4;
-template <typename T, int HPS>
-__global__ __launch_bounds__(WAVE *NWAVE) void decode_gqa_kernel(const T *__restrict__ q, const T *__restrict__ pool_rep,
-                                                                 const T *__restrict__ sel_rep, const T *__restrict__ pool_tail,
-                                                                 const T *__restrict__ sel_tail, float *__restrict__ part, int S, int m,
-                                                                 int k, int splits, float scale, float rep_bias, int m_cap, int k_cap,
-                                                                 int k_start)
-{
-    constexpr int D = 128, H = HPS, RPW = 4;
-    __shared__ float comb[H * (D + 2)];
-    const int tid = threadIdx.x, wave = tid / WAVE, lane = tid % WAVE, sub = lane & 15, grp = lane >> 4;
-    const int split = blockIdx.x % splits, s = (blockIdx.x / splits) % S, b = blockIdx.x / (splits * S);
-    const int n = m + k;
-    const int per = (n + splits - 1) / splits;
-    const int e_lo = split * per, e_hi = min(n, e_lo + per);
-
-    // this lane's 8 columns of every head's query, pre-multiplied by the scale
-    float qv[H][8];
-#pragma unroll
-    for (int h = 0; h < H; ++h) {
-        float f[8];
-        DElt<T>::unpack(*reinterpret_cast<const uint4 *>(q + (((size_t)b * S + s) * H + h) * D + sub * 8), f);
-#pragma unroll
-        for (int x = 0; x < 8; ++x) qv[h][x] = f[x] * scale;
-    }
-    const T *krep = sel_rep + ((size_t)b * S + s) * m_cap * D, *vrep = pool_rep + ((size_t)b * S + s) * m_cap * D;
-    const T *ktail = sel_tail + ((size_t)b * S + s) * k_cap * D, *vtail = pool_tail + ((size_t)b * S + s) * k_cap * D;
-
-    float mr[H], lr[H], acc[H][8];
-#pragma unroll
-    for (int h = 0; h < H; ++h) {
-        mr[h] = -INFINITY;
-        lr[h] = 0.f;
-#pragma unroll
-        for (int x = 0; x < 8; ++x) acc[h][x] = 0.f;
-    }
-
-    for (int base = e_lo + wave * RPW; base < e_hi; base += NWAVE * RPW * GQ_UNROLL) {
-        uint4 kd[GQ_UNROLL], vd[GQ_UNROLL];
-        bool valid[GQ_UNROLL], rep[GQ_UNROLL];
-#pragma unroll
-        for (int u = 0; u < GQ_UNROLL; ++u) {
-            const int e = base + u * NWAVE * RPW + grp;
-            valid[u] = e < e_hi;
-            const int ec = valid[u] ? e : e_hi - 1;
-            rep[u] = ec < m;
-            int r = k_start + (ec - m);                         // the tail is a ring of k_cap rows
-            r = r >= k_cap ? r - k_cap : r;
-            const T *kp = rep[u] ? krep + (size_t)ec * D : ktail + (size_t)r * D;
-            const T *vp = rep[u] ? vrep + (size_t)ec * D : vtail + (size_t)r * D;
-            kd[u] = *reinterpret_cast<const uint4 *>(kp + sub * 8);
-            vd[u] = *reinterpret_cast<const uint4 *>(vp + sub * 8);
-        }
-        float logit[GQ_UNROLL][H];
-#pragma unroll
-        for (int u = 0; u < GQ_UNROLL; ++u) {
-            float f[8];
-            DElt<T>::unpack(kd[u], f);
-#pragma unroll
-            for (int h = 0; h < H; ++h) {
-                float a = 0.f;
-#pragma unroll
-                for (int x = 0; x < 8; ++x) a = fmaf(f[x], qv[h][x], a);
-                a = row16_allreduce_sum(a);
-                logit[u][h] = valid[u] ? a + (rep[u] ? rep_bias : 0.f) : -INFINITY;
-            }
-        }
-#pragma unroll
-        for (int h = 0; h < H; ++h) {
-            float m_new = mr[h];
-#pragma unroll
-            for (int u = 0; u < GQ_UNROLL; ++u) m_new = fmaxf(m_new, logit[u][h]);
-            const float m_eff = m_new == -INFINITY ? 0.f : m_new;
-            const float corr = __expf(mr[h] - m_eff);
-            mr[h] = m_new;
-            lr[h] *= corr;
-#pragma unroll
-            for (int x = 0; x < 8; ++x) acc[h][x] *= corr;
-#pragma unroll
-            for (int u = 0; u < GQ_UNROLL; ++u) {
-                const float pe = __expf(logit[u][h] - m_eff);
-                lr[h] += pe;
-                float f[8];
-                DElt<T>::unpack(vd[u], f);
-#pragma unroll
-                for (int x = 0; x < 8; ++x) acc[h][x] = fmaf(pe, f[x], acc[h][x]);
-            }
-        }
-    }
-
-    // merge the four 16-lane groups of this wavefront (same columns, different rows)
-#pragma unroll
-    for (int h = 0; h < H; ++h) {
-#pragma unroll
-        for (int mask = 16; mask < WAVE; mask <<= 1) {
-            const float om = __shfl_xor(mr[h], mask, WAVE), ol = __shfl_xor(lr[h], mask, WAVE);
-            const float m_new = fmaxf(mr[h], om);
-            const float m_eff = m_new == -INFINITY ? 0.f : m_new;
-            const float ca = __expf(mr[h] - m_eff), cb = __expf(om - m_eff);
-            lr[h] = lr[h] * ca + ol * cb;
-#pragma unroll
-            for (int x = 0; x < 8; ++x) acc[h][x] = acc[h][x] * ca + __shfl_xor(acc[h][x], mask, WAVE) * cb;
-            mr[h] = m_new;
-        }
-    }
-    // merge the wavefronts one after another through LDS
-    for (int wv = 0; wv < NWAVE; ++wv) {
-        if (wave == wv && grp == 0) {
-#pragma unroll
-            for (int h = 0; h < H; ++h) {
-                float *cm = comb + h * (D + 2);
-                float ca = 1.f, cb = 0.f, m_new = mr[h], l_new = lr[h];
-                if (wv > 0) {
-                    const float om = cm[0], ol = cm[1];
-                    m_new = fmaxf(mr[h], om);
-                    const float m_eff = m_new == -INFINITY ? 0.f : m_new;
-                    ca = __expf(mr[h] - m_eff);
-                    cb = __expf(om - m_eff);
-                    l_new = lr[h] * ca + ol * cb;
-                }
-#pragma unroll
-                for (int x = 0; x < 8; ++x) {
-                    float *dst = cm + 2 + sub * 8 + x;
-                    *dst = acc[h][x] * ca + (wv > 0 ? *dst * cb : 0.f);
-                }
-                __builtin_amdgcn_wave_barrier();
-                if (sub == 0) { cm[0] = m_new; cm[1] = l_new; }
-            }
-        }
-        __syncthreads();
-    }
-    float *dst = part + ((((size_t)b * S + s) * splits + split) * H) * (D + 2);
-    for (int x = tid; x < H * (D + 2); x += WAVE * NWAVE) dst[x] = comb[x];
-}
-
 // One workgroup per (b, set, head-in-set): blockIdx.x = (b*S + s)*HPS + h.  The weights of the splits,
 // exp(max_sp - max) / sum, are computed once into LDS; then every thread owns two adjacent columns and sums
 // the splits' rows with 8-byte loads, eight of them in flight.  DP is even; rows start 8 bytes into a
@@ -432,19 +286,6 @@ __global__ __launch_bounds__(MERGE_THREADS) void decode_merge_kernel(const float
     }
 }
 
-template <typename T, int HPS>
-hipError_t run_gqa(const DecodeArgs &a, hipStream_t st)
-{
-    const Dims &d = a.d;
-    decode_gqa_kernel<T, HPS><<<d.B * d.S * a.splits, WAVE * NWAVE, 0, st>>>(
-        (const T *)a.q, (const T *)a.pool_rep, (const T *)a.sel_rep, (const T *)a.pool_tail,
-        (const T *)a.sel_tail, a.part, d.S, d.m, d.k, a.splits, d.scale, d.rep_logit_bias, a.m_cap, a.k_cap, a.k_start);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    decode_merge_kernel<T><<<d.B * d.H, MERGE_THREADS, a.splits * sizeof(float), st>>>(a.part, (T *)a.O, HPS, 128, a.splits);
-    return hipGetLastError();
-}
-
 template <typename T, int DP, int DS, bool MLA, int HPS>
 hipError_t run(const DecodeArgs &a, hipStream_t st)
 {
@@ -464,7 +305,6 @@ int shape_id(const Dims &d)
     const int hps = d.H / d.S;
     const bool mla = d.mode == LCA_MODE_MLA;
     const bool b16 = d.dtype == LCA_BF16 || d.dtype == LCA_F16;    // the 16-bit types share the shapes; the launcher picks the type
-    if (b16 && !mla && d.d_pool == 128 && d.d_sel == 128 && hps >= 1 && hps <= 8) return 100 + hps;
     if (b16 && mla && d.d_pool == 512 && d.d_sel == 64 && (hps == 1 || hps == 16)) return 200 + hps;
     if (d.dtype == LCA_F32 && mla && d.d_pool == 128 && d.d_sel == 32 && (hps == 1 || hps == 4)) return 300 + hps;
     return 0;
@@ -472,11 +312,12 @@ int shape_id(const Dims &d)
 
 }  // namespace
 
-bool decode_supported(const Dims &d) { return decode_mla_supported(d) || shape_id(d) != 0; }
+bool decode_supported(const Dims &d) { return decode_mla_supported(d) || decode_gqa_mfma_supported(d) || shape_id(d) != 0; }
 
 int decode_splits(const Dims &d)
 {
     if (decode_mla_supported(d)) return decode_mla_parts(d);
+    if (decode_gqa_mfma_supported(d)) return decode_gqa_mfma_parts(d);
     const int n = d.m + d.k;
     int splits = (TARGET_BLOCKS + d.B * d.S - 1) / (d.B * d.S);
     const int max_splits = (n + 63) / 64;
@@ -503,16 +344,18 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st)
             decode_merge_kernel<uint16_t><<<a.d.B * a.d.H, MERGE_THREADS, wgs * sizeof(float), st>>>(a.part, (uint16_t *)a.O, a.d.H / a.d.S, a.d.d_pool, wgs);
         return hipGetLastError();
     }
+    if (decode_gqa_mfma_supported(a.d)) {     // matrix-core kernel at the GQA widths, then the common merge
+        const hipError_t e = launch_decode_gqa_mfma(a, st);
+        if (e != hipSuccess) return e;
+        const int wgs = a.splits / 4;
+        if (a.d.dtype == LCA_F16)
+            decode_merge_kernel<f16_t><<<a.d.B * a.d.H, MERGE_THREADS, wgs * sizeof(float), st>>>(a.part, (f16_t *)a.O, a.d.H / a.d.S, a.d.d_pool, wgs);
+        else
+            decode_merge_kernel<uint16_t><<<a.d.B * a.d.H, MERGE_THREADS, wgs * sizeof(float), st>>>(a.part, (uint16_t *)a.O, a.d.H / a.d.S, a.d.d_pool, wgs);
+        return hipGetLastError();
+    }
     const bool f16 = a.d.dtype == LCA_F16;
     switch (shape_id(a.d)) {
-    case 101: return f16 ? run_gqa<f16_t, 1>(a, st) : run_gqa<uint16_t, 1>(a, st);
-    case 102: return f16 ? run_gqa<f16_t, 2>(a, st) : run_gqa<uint16_t, 2>(a, st);
-    case 103: return f16 ? run_gqa<f16_t, 3>(a, st) : run_gqa<uint16_t, 3>(a, st);
-    case 104: return f16 ? run_gqa<f16_t, 4>(a, st) : run_gqa<uint16_t, 4>(a, st);
-    case 105: return f16 ? run_gqa<f16_t, 5>(a, st) : run_gqa<uint16_t, 5>(a, st);
-    case 106: return f16 ? run_gqa<f16_t, 6>(a, st) : run_gqa<uint16_t, 6>(a, st);
-    case 107: return f16 ? run_gqa<f16_t, 7>(a, st) : run_gqa<uint16_t, 7>(a, st);
-    case 108: return f16 ? run_gqa<f16_t, 8>(a, st) : run_gqa<uint16_t, 8>(a, st);
     case 201: return f16 ? run<f16_t, 512, 64, true, 1>(a, st) : run<uint16_t, 512, 64, true, 1>(a, st);
     case 216: return f16 ? run<f16_t, 512, 64, true, 16>(a, st) : run<uint16_t, 512, 64, true, 16>(a, st);
     case 301: return run<float, 128, 32, true, 1>(a, st);

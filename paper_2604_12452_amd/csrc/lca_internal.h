@@ -80,6 +80,9 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st);
 bool decode_mla_supported(const Dims &d);
 int decode_mla_parts(const Dims &d);
 hipError_t launch_decode_mla(const DecodeArgs &a, hipStream_t st);
+bool decode_gqa_mfma_supported(const Dims &d);
+int decode_gqa_mfma_parts(const Dims &d);
+hipError_t launch_decode_gqa_mfma(const DecodeArgs &a, hipStream_t st);
 hipError_t launch_cache_update(const UpdateArgs &a, hipStream_t st);
 
 // 8-bit copy of the representatives in use: codes [.., m_cap, d] and scales [.., m_cap, 2] (pooled, selected).
