@@ -7,16 +7,16 @@
 // 16x16x32 MFMAs:
 //   S^T[key, head]  = K Q^T       A = 16 key rows from LDS (16-byte reads), B = Q^T in registers (18 k-steps)
 //   O^T[dv, head]  += V^T P^T     A = V^T through LDS transpose reads,       B = P^T = exp2(S^T - ref)
-// Every WAVEFRONT works alone on its own range of entries with its own 36.5 KB LDS buffer (no barriers): it
-// copies a tile of 32 entries with direct-to-LDS loads (32 latent rows of 1 KB at a 1040-byte stride, the RoPE
-// parts XOR-swizzled), waits for it, and uses it twice — all 576 columns as keys, the first 512 as values.  The
-// other wavefronts of the CU cover the wait.  S^T row m of a block of 16 comes from LDS row 4(m%4) + m/4, so that
-// the S^T accumulators already are the B fragments of the second product when the transpose reads of a 16-lane
-// block take rows 4 apart (conflict-free on the 1040-byte stride).  Softmax keeps one fixed reference per head
-// (taken at the first tile), so the 128 accumulation registers are never rescaled; if a row sum ends beyond
-// 2^100 (or, in fp16, an exponential left the type's range and the sum is infinite) the wavefront collects the exact maximum of its range and runs it again.  The four wavefronts' results
-// (reference, sum, unnormalised output per head) are merged in LDS into one partial result per workgroup; the
-// workgroups' partial results are merged by decode_merge_kernel.
+// Every WAVEFRONT works alone on its own range of entries (no barriers in the loop) with two 18 KB LDS buffers of its
+// own: a tile is 16 entries (16 latent rows of 1 KB at a 1040-byte stride, the RoPE parts XOR-swizzled), copied with
+// direct-to-LDS loads; the copy of tile t+1 is in flight while tile t is used -- twice: all 576 columns as keys, the
+// first 512 as values.  S^T row m of the tile comes from LDS row 4(m%4) + m/4, so that the S^T accumulators already
+// are the B fragments of the second product (16x16x16 MFMAs) when the transpose reads of a 16-lane block take rows 4
+// apart (conflict-free on the 1040-byte stride).  Softmax keeps one fixed reference per head (taken at the first
+// tile), so the 128 accumulation registers are never rescaled; if a row sum ends beyond 2^100 (or, in fp16, an
+// exponential left the type's range and the sum is infinite) the wavefront collects the exact maximum of its range
+// and runs it again.  The four wavefronts' results (reference, sum, unnormalised output per head) are merged in LDS
+// into one partial result per workgroup; the workgroups' partial results are merged by decode_merge_kernel.
 #include "lca_internal.h"
 
 namespace lca {
@@ -31,6 +31,12 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 // The kernel is a template over the 16-bit element type E (__bf16 or _Float16); these overloads pick the instructions.
 __device__ __forceinline__ floatx4 mfma_16x16x32(bf16x8 a, bf16x8 b, floatx4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
 __device__ __forceinline__ floatx4 mfma_16x16x32(f16x8 a, f16x8 b, floatx4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+__device__ __forceinline__ floatx4 mfma_16x16x16(bf16x4 a, bf16x4 b, floatx4 c)
+{
+    typedef short shortx4 __attribute__((ext_vector_type(4)));
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, a), __builtin_bit_cast(shortx4, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ floatx4 mfma_16x16x16(f16x4 a, f16x4 b, floatx4 c) { return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0); }
 __device__ __forceinline__ bf16x4 lds_read_tr16(__attribute__((address_space(3))) bf16x4 *p) { return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(p); }
 __device__ __forceinline__ f16x4 lds_read_tr16(__attribute__((address_space(3))) f16x4 *p)
 {
@@ -42,15 +48,16 @@ __device__ __forceinline__ f16x4 lds_read_tr16(__attribute__((address_space(3)))
 constexpr float SUM_LIMIT = 0x1p100f;
 
 constexpr int DP = 512, DS = 64, DQK = 576;
-constexpr int BN = 32;                          // entries per tile
+constexpr int BN = 16;                          // entries per tile
 constexpr int RSB = 1040;                       // LDS row stride of the latent part: 1024 + 16
-constexpr int SEL_OFF = BN * RSB;               // RoPE part: 32 rows x 128 B, chunks swizzled by row & 7
-constexpr int BUF_BYTES = SEL_OFF + BN * DS * 2;   // 37 376 per wavefront
+constexpr int SEL_OFF = BN * RSB;               // RoPE part: 16 rows x 128 B, chunks swizzled by row & 7
+constexpr int BUF_BYTES = SEL_OFF + BN * DS * 2;   // 18 688; two per wavefront
+constexpr int COPIES = BN + BN / 8;             // direct-to-LDS loads per 16-bit tile: 18
 constexpr int NKS = DQK / 32;                   // 18 k-steps of S^T
 constexpr int NDT = DP / 16;                    // 32 value tiles
 constexpr int PV_GROUP = 8;                     // value tiles whose V^T fragments are requested together
 constexpr int MROW = DP + 4;                    // floats per head of a wavefront's rescaled output in LDS (merge at the end)
-static_assert(16 * MROW * 4 <= BUF_BYTES, "the rescaled output of 16 heads fits a wavefront's tile buffer");
+static_assert(16 * MROW * 4 <= 2 * BUF_BYTES, "the rescaled output of 16 heads fits a wavefront's two tile buffers");
 constexpr float NEG_BIG = -1.0e30f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -97,15 +104,15 @@ template <typename E> __device__ __forceinline__ void cvt16_fp8(const uint4 &c, 
 
 // Q8: the representatives come as E4M3 codes with a power-of-two scale per row and component.  A tile then holds
 // entries of one kind only (the list of tiles is the representatives' tiles followed by the tail's), and a tile of
-// representatives is fetched into registers (its 16 KB + 2 KB of codes are contiguous), converted -- one instruction
-// per two codes, the row's scale riding along -- and written into the same LDS layout the 16-bit tiles use; from
-// there on nothing differs.
+// representatives is fetched into registers (its 8 KB + 1 KB of codes are contiguous) while the tile before it is used,
+// converted -- one instruction per two codes, the row's scale riding along -- and written into the same LDS layout
+// the 16-bit tiles use; from there on nothing differs.
 template <typename E, bool Q8>
 __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
 {
     typedef E ex8 __attribute__((ext_vector_type(8)));
     typedef E ex4 __attribute__((ext_vector_type(4)));
-    __shared__ __attribute__((aligned(1024))) char bufs[4][BUF_BYTES];
+    __shared__ __attribute__((aligned(1024))) char bufs[4][2][BUF_BYTES];
     __shared__ float wave_ml[4][16][2];                                     // (reference, sum) per wavefront and head
 
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 15, q4 = lane >> 4;
@@ -119,13 +126,17 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
     const int tiles_per_part = (tiles_total + kp.n_parts - 1) / kp.n_parts;
     const int t_lo = min(part * tiles_per_part, tiles_total), t_hi = min(t_lo + tiles_per_part, tiles_total);
     const int e_hi = Q8 ? n : min(n, t_hi * BN);
-    char *buf = bufs[wave];
-    const unsigned buf_lds = lds_address(buf);
+    char *buf0 = bufs[wave][0];
+    const unsigned buf_lds = lds_address(buf0);
 
     // source rows: entry e < m is representative e, else tail token e - m in ring row (k_start + e - m) mod k_cap
     const uint16_t *prep = kp.pool_rep + (size_t)bs * kp.m_cap * DP, *srep = kp.sel_rep + (size_t)bs * kp.m_cap * DS;
     const uint16_t *ptail = kp.pool_tail + (size_t)b * kp.k_cap * DP, *stail = kp.sel_tail + (size_t)b * kp.k_cap * DS;
     auto ring_row = [&](int e) { const int t = kp.k_start + e - m; return t >= kp.k_cap ? t - kp.k_cap : t; };
+    // first entry of tile tl and the end of the entries it may show (Q8: the end of its kind)
+    auto is_q8 = [&](int tl) { return Q8 && tl < rep_tiles; };
+    auto first_entry = [&](int tl) { return !Q8 ? tl * BN : tl < rep_tiles ? tl * BN : m + (tl - rep_tiles) * BN; };
+    auto segment_end = [&](int tl) { return !Q8 ? e_hi : tl < rep_tiles ? m : n; };
 
     // Q^T fragments: lane (col = head of the set, q4) holds q[head, 32 ks + 8 q4 .. +7]; columns past the set's heads are zero
     ex8 qf[NKS];
@@ -137,29 +148,25 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
             if (col >= kp.hps) qf[ks] = ex8{0, 0, 0, 0, 0, 0, 0, 0};
         }
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[ks]));   // loaded before the copies start (see the wait below)
+        for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[ks]));   // loaded before the copies start (the waits below count copies)
     }
 
-    // per-lane LDS offsets
-    const int krow = 4 * (col & 3) + (col >> 2);                            // LDS row behind S^T row `col` of a block of 16
-    const int k_off = krow * RSB + 16 * q4;                                 // + 16*blk*RSB + 64*ks
-    const int ksel_row = SEL_OFF + krow * (DS * 2);                         // + 16*blk*128, chunk c at slot c ^ (row & 7)
-    const int v_off = (4 * (col >> 2) + q4) * RSB + 8 * (col & 3);          // + 16*hh*RSB + 32*t: transpose read of 4 keys x 4 columns
+    // per-lane LDS offsets inside a tile buffer
+    const int krow = 4 * (col & 3) + (col >> 2);                            // LDS row behind S^T row `col` of the tile's 16 entries
+    const int k_off = krow * RSB + 16 * q4;                                 // + 64*ks
+    const int ksel_row = SEL_OFF + krow * (DS * 2);                         // chunk c at slot c ^ (row & 7)
+    const int v_off = (4 * (col >> 2) + q4) * RSB + 8 * (col & 3);          // + 32*t: transpose read of 4 keys (rows 4 apart) x 4 columns
 
     floatx4 acc[NDT];
     float m_ref = NEG_BIG, l_run = 0.f, m_seen = NEG_BIG;
     const float c = kp.scale_log2;
     typedef __attribute__((address_space(3))) ex4 *lds_b64_ptr;
 
-    // copy of tile tl into this wavefront's buffer, S^T = K Q^T for its two blocks of 16 entries, and the logits in base 2
-    // (scale, bias of the representatives, entries past the range hidden)
     // Q8: the codes of one tile of representatives in registers.  Load i brings rows 2i, 2i+1 of the latent part (lane l:
-    // 16 codes at column 16 (l & 31) of row 2i + (l >> 5)), load j rows 16j .. 16j+15 of the RoPE part (lane l: 16 codes
-    // at column 16 (l & 3) of row 16j + (l >> 2)); lane r < 32 holds the two scales of row r.  Rows past the end repeat
-    // the last one.
-    uint4 q8_pool[BN / 2], q8_sel[2];
+    // 16 codes at column 16 (l & 31) of row 2i + (l >> 5)), one more the RoPE part (lane l: 16 codes at column 16 (l & 3)
+    // of row l >> 2); lane r < 16 holds the two scales of row r.  Rows past the end repeat the last one.
+    uint4 q8_pool[BN / 2], q8_sel;
     float2 q8_scale = float2{1.f, 1.f};
-    int q8_in_regs = -1;
     auto fetch_q8 = [&](int tl) {
         const uint8_t *pq = kp.pool_q8 + (size_t)bs * kp.m_cap * DP, *sq = kp.sel_q8 + (size_t)bs * kp.m_cap * DS;
         const int e0 = tl * BN;
@@ -168,103 +175,110 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
             const int e = min(e0 + 2 * i + (lane >> 5), m - 1);
             q8_pool[i] = *reinterpret_cast<const uint4 *>(pq + (size_t)e * DP + 16 * (lane & 31));
         }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int e = min(e0 + 16 * j + (lane >> 2), m - 1);
-            q8_sel[j] = *reinterpret_cast<const uint4 *>(sq + (size_t)e * DS + 16 * (lane & 3));
-        }
-        q8_scale = *reinterpret_cast<const float2 *>(kp.scales + ((size_t)bs * kp.m_cap + min(e0 + (lane & 31), m - 1)) * 2);
-        q8_in_regs = tl;
+        q8_sel = *reinterpret_cast<const uint4 *>(sq + (size_t)min(e0 + (lane >> 2), m - 1) * DS + 16 * (lane & 3));
+        q8_scale = *reinterpret_cast<const float2 *>(kp.scales + ((size_t)bs * kp.m_cap + min(e0 + (lane & 15), m - 1)) * 2);
     };
-
-    auto tile_logits = [&](int tl, float (&lg)[2][4]) {
-        // first entry of the tile and the end of the entries it may show (Q8: the end of its kind)
-        const bool q8_tile = Q8 && tl < rep_tiles;
-        const int e0 = !Q8 ? tl * BN : q8_tile ? tl * BN : m + (tl - rep_tiles) * BN;
-        const int seg_end = !Q8 ? e_hi : q8_tile ? m : n;
-        // 32 latent rows (one load each), RoPE parts of 8 rows per load; rows past the range repeat its last row
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                  // this wavefront's reads of the previous tile are done
-        const int e_last = e0 + BN - 1;
-        // the usual tile: 32 consecutive rows of one buffer (no end of range, no rep/tail seam, no wrap of the ring)
+    // ... converted (one instruction per two codes, the row's scale riding along) and written in the 16-bit layout
+    auto convert_q8 = [&](char *buf) {
+#pragma unroll
+        for (int i = 0; i < BN / 2; ++i) {
+            const float s0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, q8_scale.x), 2 * i));
+            const float s1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, q8_scale.x), 2 * i + 1));
+            uint4 lo, hi;
+            cvt16_fp8<E>(q8_pool[i], lane < 32 ? s0 : s1, lo, hi);
+            char *dst = buf + (2 * i + (lane >> 5)) * RSB + 32 * (lane & 31);
+            *reinterpret_cast<uint4 *>(dst) = lo;
+            *reinterpret_cast<uint4 *>(dst + 16) = hi;
+        }
+        const int r = lane >> 2, c0 = 2 * (lane & 3);                       // chunk c of row r sits at slot c ^ (r & 7)
+        uint4 lo, hi;
+        cvt16_fp8<E>(q8_sel, __shfl(q8_scale.y, r, 64), lo, hi);
+        char *dst = buf + SEL_OFF + r * (DS * 2);
+        *reinterpret_cast<uint4 *>(dst + ((c0 ^ (r & 7)) << 4)) = lo;
+        *reinterpret_cast<uint4 *>(dst + (((c0 + 1) ^ (r & 7)) << 4)) = hi;
+    };
+    // 16-bit tiles: COPIES direct-to-LDS loads into tile buffer `bi` -- 16 latent rows (one load each) and the RoPE parts
+    // of 8 rows per load; rows past the range repeat its last row
+    auto issue_dma = [&](int tl, int bi) {
+        const int e0 = first_entry(tl), seg_end = segment_end(tl), e_last = e0 + BN - 1;
+        const unsigned dst = buf_lds + bi * BUF_BYTES;
+        // the usual tile: 16 consecutive rows of one buffer (no end of range, no rep/tail seam, no wrap of the ring)
         const bool in_rep = e_last < m, in_tail = e0 >= m && ring_row(e0) + BN <= kp.k_cap;
-        if (q8_tile) {
-            if (q8_in_regs != tl) fetch_q8(tl);
-            // convert (one instruction per two codes, the row's scale riding along) and write the 16-bit layout
-#pragma unroll
-            for (int i = 0; i < BN / 2; ++i) {
-                const float s0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, q8_scale.x), 2 * i));
-                const float s1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, q8_scale.x), 2 * i + 1));
-                uint4 lo, hi;
-                cvt16_fp8<E>(q8_pool[i], lane < 32 ? s0 : s1, lo, hi);
-                char *dst = buf + (2 * i + (lane >> 5)) * RSB + 32 * (lane & 31);
-                *reinterpret_cast<uint4 *>(dst) = lo;
-                *reinterpret_cast<uint4 *>(dst + 16) = hi;
-            }
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int r = 16 * j + (lane >> 2), c0 = 2 * (lane & 3);        // chunk c of row r sits at slot c ^ (r & 7)
-                uint4 lo, hi;
-                cvt16_fp8<E>(q8_sel[j], __shfl(q8_scale.y, r, 64), lo, hi);
-                char *dst = buf + SEL_OFF + r * (DS * 2);
-                *reinterpret_cast<uint4 *>(dst + ((c0 ^ (r & 7)) << 4)) = lo;
-                *reinterpret_cast<uint4 *>(dst + (((c0 + 1) ^ (r & 7)) << 4)) = hi;
-            }
-            // the next tile's codes travel while this one is used
-            if (tl + 1 < t_hi && tl + 1 < rep_tiles) fetch_q8(tl + 1);
-        } else if (e_last < seg_end && (in_rep || in_tail)) {
+        if (e_last < seg_end && (in_rep || in_tail)) {
             const size_t row0 = in_rep ? e0 : ring_row(e0);
             const char *pb0 = (const char *)((in_rep ? prep : ptail) + row0 * DP);
             const char *sb0 = (const char *)((in_rep ? srep : stail) + row0 * DS);
 #pragma unroll
-            for (int r = 0; r < BN; ++r) dma_row(lane * 16, pb0 + r * (DP * 2), buf_lds + r * RSB);
+            for (int r = 0; r < BN; ++r) dma_row(lane * 16, pb0 + r * (DP * 2), dst + r * RSB);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < BN / 8; ++j) {
                 const int r = 8 * j + (lane >> 3);
-                dma_row(r * (DS * 2) + (((lane & 7) ^ (r & 7)) << 4), sb0, buf_lds + SEL_OFF + 8 * j * (DS * 2));
+                dma_row(r * (DS * 2) + (((lane & 7) ^ (r & 7)) << 4), sb0, dst + SEL_OFF + 8 * j * (DS * 2));
             }
         } else {
 #pragma unroll 4
             for (int r = 0; r < BN; ++r) {
                 const int e = min(e0 + r, seg_end - 1);
                 const uint16_t *src = e < m ? prep + (size_t)e * DP : ptail + (size_t)ring_row(e) * DP;
-                dma_row(lane * 16, src, buf_lds + r * RSB);
+                dma_row(lane * 16, src, dst + r * RSB);
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < BN / 8; ++j) {
                 const int r = 8 * j + (lane >> 3);
                 const int e = min(e0 + r, seg_end - 1);
                 const uint16_t *src = (e < m ? srep + (size_t)e * DS : stail + (size_t)ring_row(e) * DS) + (((lane & 7) ^ (r & 7)) << 3);
-                dma_lanes(src, buf_lds + SEL_OFF + 8 * j * (DS * 2));
-            }
-        }
-        if (!q8_tile) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // ... has landed (the other wavefronts of the CU cover the wait)
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-            ex8 kf[NKS];
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-                const char *p = ks < DP / 32 ? buf + k_off + blk * 16 * RSB + 64 * ks
-                                             : buf + ksel_row + blk * 16 * (DS * 2) + (((4 * (ks - DP / 32) + q4) ^ (krow & 7)) << 4);
-                kf[ks] = *reinterpret_cast<const ex8 *>(p);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            floatx4 sacc = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) sacc = mfma_16x16x32(kf[ks], qf[ks], sacc);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int e = e0 + blk * 16 + 4 * r + q4;                   // accumulator row 4 q4 + r sits in LDS row 4 r + q4
-                lg[blk][r] = e < seg_end ? fmaf(sacc[r], c, e < m ? kp.bias_log2 : 0.f) : -INFINITY;
+                dma_lanes(src, dst + SEL_OFF + 8 * j * (DS * 2));
             }
         }
     };
-    auto head_max = [&](const float (&lg)[2][4]) {
-        float mx = NEG_BIG;
+    auto issue = [&](int tl, int bi) {
+        if (is_q8(tl)) fetch_q8(tl);
+        else issue_dma(tl, bi);
+    };
+    // One sweep over the wavefront's tiles.  Tile tl sits in buffer (tl - t_lo) & 1; tile tl+1 is on its way -- by direct-to-LDS
+    // copy into the other buffer, or into the registers -- while `body` uses tile tl.  (A tile of codes is never followed
+    // by one before it in kind, so behind the copies of a 16-bit tile only copies of a 16-bit tile can be in flight.)
+    auto sweep = [&](auto &&body) {
+        if (t_lo < t_hi) issue(t_lo, 0);
+        for (int tl = t_lo; tl < t_hi; ++tl) {
+            const int bi = (tl - t_lo) & 1;
+            char *buf = buf0 + bi * BUF_BYTES;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");              // this wavefront's reads of tile tl-1 (and tl-2) are done
+            if (is_q8(tl)) {
+                convert_q8(buf);
+                if (tl + 1 < t_hi) issue(tl + 1, bi ^ 1);
+            } else if (tl + 1 < t_hi) {
+                issue_dma(tl + 1, bi ^ 1);
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(COPIES) : "memory");   // tile tl has landed, tile tl+1 may still travel
+            } else {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+            body(tl, buf);
+        }
+    };
+    // S^T = K Q^T for the tile's 16 entries, and the logits in base 2 (scale, bias of the representatives, entries past the
+    // range hidden): accumulator register r of this lane is entry 4 r + q4 of the tile
+    auto tile_logits = [&](int tl, const char *buf, float (&lg)[4]) {
+        const int e0 = first_entry(tl), seg_end = segment_end(tl);
+        ex8 kf[NKS];
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
+        for (int ks = 0; ks < NKS; ++ks) {
+            const char *p = ks < DP / 32 ? buf + k_off + 64 * ks : buf + ksel_row + (((4 * (ks - DP / 32) + q4) ^ (krow & 7)) << 4);
+            kf[ks] = *reinterpret_cast<const ex8 *>(p);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        floatx4 sacc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int r = 0; r < 4; ++r) mx = fmaxf(mx, lg[blk][r]);
+        for (int ks = 0; ks < NKS; ++ks) sacc = mfma_16x16x32(kf[ks], qf[ks], sacc);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int e = e0 + 4 * r + q4;                                  // accumulator row 4 q4 + r sits in LDS row 4 r + q4
+            lg[r] = e < seg_end ? fmaf(sacc[r], c, e < m ? kp.bias_log2 : 0.f) : -INFINITY;
+        }
+    };
+    auto head_max = [&](const float (&lg)[4]) {
+        float mx = fmaxf(fmaxf(fmaxf(lg[0], lg[1]), fmaxf(lg[2], lg[3])), NEG_BIG);
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         return fmaxf(mx, __shfl_xor(mx, 32, 64));
     };
@@ -277,32 +291,27 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
         m_ref = again ? m_seen : NEG_BIG;
         bool ref_missing = !again;
 
-        for (int tl = t_lo; tl < t_hi; ++tl) {
-            float lg[2][4];
-            tile_logits(tl, lg);
+        sweep([&](int tl, const char *buf) {
+            float lg[4];
+            tile_logits(tl, buf, lg);
             if (ref_missing) {                                              // the first tile fixes the reference
                 const float mx = head_max(lg);
                 m_ref = (m_ref == NEG_BIG) ? mx : m_ref;
                 ref_missing = __builtin_amdgcn_ballot_w64(m_ref == NEG_BIG) != 0;
             }
-            // P^T in the element type (B fragment: k-slot i < 4 is the key of block 0 register i, i >= 4 of block 1 register i-4) and its sum
-            ex8 pb;
+            // P^T in the element type (B fragment of a 16x16x16 product: k-slot r of this lane is the key of register r) and
+            // its sum (of the rounded values, the ones the second product sees)
+            ex4 pb;
 #pragma unroll
-            for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    pb[blk * 4 + r] = (E)__builtin_amdgcn_exp2f(lg[blk][r] - m_ref);
-                    l_run += (float)pb[blk * 4 + r];                       // the rounded value, the one the second product sees
-                }
+            for (int r = 0; r < 4; ++r) {
+                pb[r] = (E)__builtin_amdgcn_exp2f(lg[r] - m_ref);
+                l_run += (float)pb[r];
+            }
             // O^T += V^T P^T: fragments of PV_GROUP value tiles requested together, one group ahead
-            ex4 vlo[2][PV_GROUP], vhi[2][PV_GROUP];
+            ex4 vf[2][PV_GROUP];
             auto request = [&](int grp, int bsel) {
 #pragma unroll
-                for (int i = 0; i < PV_GROUP; ++i) {
-                    const char *vp = buf + v_off + 32 * (grp * PV_GROUP + i);
-                    vlo[bsel][i] = lds_read_tr16((lds_b64_ptr)(vp));
-                    vhi[bsel][i] = lds_read_tr16((lds_b64_ptr)(vp + 16 * RSB));
-                }
+                for (int i = 0; i < PV_GROUP; ++i) vf[bsel][i] = lds_read_tr16((lds_b64_ptr)(buf + v_off + 32 * (grp * PV_GROUP + i)));
             };
             request(0, 0);
 #pragma unroll
@@ -311,25 +320,24 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
                 if (grp + 1 < NDT / PV_GROUP) request(grp + 1, (grp + 1) & 1);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < PV_GROUP; ++i) {
-                    const ex8 a = __builtin_shufflevector(vlo[grp & 1][i], vhi[grp & 1][i], 0, 1, 2, 3, 4, 5, 6, 7);
-                    acc[grp * PV_GROUP + i] = mfma_16x16x32(a, pb, acc[grp * PV_GROUP + i]);
-                }
+                for (int i = 0; i < PV_GROUP; ++i) acc[grp * PV_GROUP + i] = mfma_16x16x16(vf[grp & 1][i], pb, acc[grp * PV_GROUP + i]);
             }
-        }
+        });
 
         l_tot = l_run + __shfl_xor(l_run, 16, 64);
         l_tot += __shfl_xor(l_tot, 32, 64);
         if (again || __builtin_amdgcn_ballot_w64(!(l_tot <= SUM_LIMIT)) == 0) break;
         // (wave-uniform) a head ran out of exponent headroom: exact maxima of the range, then the pass again
         m_seen = NEG_BIG;
-        for (int tl = t_lo; tl < t_hi; ++tl) {
-            float lg[2][4];
-            tile_logits(tl, lg);
+        sweep([&](int tl, const char *buf) {
+            float lg[4];
+            tile_logits(tl, buf, lg);
             m_seen = fmaxf(m_seen, head_max(lg));
-        }
+        });
         again = true;
     }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                      // the last tile's reads are done before the buffers are reused
+    char *buf = buf0;                                                       // the merge uses the wavefront's two buffers as one
 
     // The four wavefronts' results (reference, sum, unnormalised output per head) are merged here, through LDS, so that
     // one partial result per workgroup goes to memory: each wavefront publishes its references and sums, rescales its
@@ -352,7 +360,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
     }
     {
         const float f = any ? __builtin_amdgcn_exp2f(m_ref - m_all) : 0.f;
-        float *mine = reinterpret_cast<float *>(buf) + col * MROW + 4 * q4;   // [head][MROW] floats, 33 KB of the 36.5 KB buffer
+        float *mine = reinterpret_cast<float *>(buf) + col * MROW + 4 * q4;   // [head][MROW] floats, 33 KB of the two buffers' 36.5 KB
 #pragma unroll
         for (int t = 0; t < NDT; ++t) {
             floatx4 v = acc[t];
@@ -369,7 +377,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
         float2 sum = float2{0.f, 0.f};
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const float2 v = *reinterpret_cast<const float2 *>(reinterpret_cast<const float *>(bufs[w]) + h * MROW + x);
+            const float2 v = *reinterpret_cast<const float2 *>(reinterpret_cast<const float *>(bufs[w][0]) + h * MROW + x);
             sum.x += v.x;
             sum.y += v.y;
         }
@@ -391,12 +399,12 @@ bool decode_mla_supported(const Dims &d)
 }
 
 // partial results per (sequence, set): a multiple of 4 (one per wavefront), enough workgroups to fill the chip,
-// at least two tiles per wavefront where the cache is long enough
+// at least four tiles per wavefront where the cache is long enough
 int decode_mla_parts(const Dims &d)
 {
     const int tiles = (d.m + BN - 1) / BN + (d.k + BN - 1) / BN;      // (an upper bound when the two kinds share tiles)
     int wgs = (256 + d.B * d.S - 1) / (d.B * d.S);
-    const int max_wgs = (tiles + 7) / 8;
+    const int max_wgs = (tiles + 15) / 16;
     if (wgs > max_wgs) wgs = max_wgs;
     if (wgs < 1) wgs = 1;
     return 4 * wgs;
