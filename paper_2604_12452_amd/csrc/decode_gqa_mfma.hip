@@ -88,18 +88,7 @@ __global__ __launch_bounds__(256, 1) void decode_gqa_mfma_kernel(const DgParams 
     const uint16_t *krep = kp.k_rep + (size_t)bs * kp.m_cap * D, *vrep = kp.v_rep + (size_t)bs * kp.m_cap * D;
     const uint16_t *ktail = kp.k_tail + (size_t)bs * kp.k_cap * D, *vtail = kp.v_tail + (size_t)bs * kp.k_cap * D;
 
-    // Q^T fragments: lane (col = head of the KV head, q4) holds q[head, 32 ks + 8 q4 .. +7]; columns past the heads are zero
-    ex8 qf[NKS];
-    {
-        const uint16_t *qp = kp.q + ((size_t)bs * kp.hps + min(col, kp.hps - 1)) * D + 8 * q4;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            qf[ks] = *reinterpret_cast<const ex8 *>(qp + 32 * ks);
-            if (col >= kp.hps) qf[ks] = ex8{0, 0, 0, 0, 0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[ks]));   // loaded before the copies start (the waits below count copies only)
-    }
+    ex8 qf[NKS];        // Q^T fragments, loaded below once the first tile's copy is on its way
 
     // per-lane LDS offsets inside a tile buffer: chunk c (16 bytes) of row r sits at slot c ^ (r & 15)
     const int krow = 4 * (col & 3) + (col >> 2);                            // LDS row behind S^T row `col` of a block of 16
@@ -158,9 +147,26 @@ __global__ __launch_bounds__(256, 1) void decode_gqa_mfma_kernel(const DgParams 
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         return fmaxf(mx, __shfl_xor(mx, 32, 64));
     };
+    // (the queries travel together with the first tile: their latency is paid once, not before the first copy starts)
+    bool q_loaded = false;
+    auto load_q = [&]() {
+        // Q^T fragments: lane (col = head of the KV head, q4) holds q[head, 32 ks + 8 q4 .. +7]; columns past the heads are zero
+        {
+            const uint16_t *qp = kp.q + ((size_t)bs * kp.hps + min(col, kp.hps - 1)) * D + 8 * q4;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                qf[ks] = *reinterpret_cast<const ex8 *>(qp + 32 * ks);
+                if (col >= kp.hps) qf[ks] = ex8{0, 0, 0, 0, 0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[ks]));   // here before the loop starts (its waits count copies)
+        }
+        q_loaded = true;
+    };
     // One sweep over the wavefront's tiles: tile tl+1 is copied into the other buffer while `body` uses tile tl.
     auto sweep = [&](auto &&body) {
         if (t_lo < t_hi) issue_copy(t_lo, 0);
+        if (!q_loaded) load_q();
         for (int tl = t_lo; tl < t_hi; ++tl) {
             const int b = (tl - t_lo) & 1;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");              // this wavefront's reads of the other buffer (tile tl-1) are done

@@ -138,18 +138,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
     auto first_entry = [&](int tl) { return !Q8 ? tl * BN : tl < rep_tiles ? tl * BN : m + (tl - rep_tiles) * BN; };
     auto segment_end = [&](int tl) { return !Q8 ? e_hi : tl < rep_tiles ? m : n; };
 
-    // Q^T fragments: lane (col = head of the set, q4) holds q[head, 32 ks + 8 q4 .. +7]; columns past the set's heads are zero
-    ex8 qf[NKS];
-    {
-        const uint16_t *qp = kp.q + ((size_t)bs * kp.hps + min(col, kp.hps - 1)) * DQK + 8 * q4;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            qf[ks] = *reinterpret_cast<const ex8 *>(qp + 32 * ks);
-            if (col >= kp.hps) qf[ks] = ex8{0, 0, 0, 0, 0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[ks]));   // loaded before the copies start (the waits below count copies)
-    }
+    ex8 qf[NKS];        // Q^T fragments, loaded below once the first tile's copy is on its way
 
     // per-lane LDS offsets inside a tile buffer
     const int krow = 4 * (col & 3) + (col >> 2);                            // LDS row behind S^T row `col` of the tile's 16 entries
@@ -235,11 +224,28 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
         if (is_q8(tl)) fetch_q8(tl);
         else issue_dma(tl, bi);
     };
+    // (the queries travel together with the first tile: their latency is paid once, not before the first copy starts)
+    bool q_loaded = false;
+    auto load_q = [&]() {
+        // Q^T fragments: lane (col = head of the set, q4) holds q[head, 32 ks + 8 q4 .. +7]; columns past the set's heads are zero
+        {
+            const uint16_t *qp = kp.q + ((size_t)bs * kp.hps + min(col, kp.hps - 1)) * DQK + 8 * q4;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                qf[ks] = *reinterpret_cast<const ex8 *>(qp + 32 * ks);
+                if (col >= kp.hps) qf[ks] = ex8{0, 0, 0, 0, 0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[ks]));   // here before the loop starts (its waits count copies)
+        }
+        q_loaded = true;
+    };
     // One sweep over the wavefront's tiles.  Tile tl sits in buffer (tl - t_lo) & 1; tile tl+1 is on its way -- by direct-to-LDS
     // copy into the other buffer, or into the registers -- while `body` uses tile tl.  (A tile of codes is never followed
     // by one before it in kind, so behind the copies of a 16-bit tile only copies of a 16-bit tile can be in flight.)
     auto sweep = [&](auto &&body) {
         if (t_lo < t_hi) issue(t_lo, 0);
+        if (!q_loaded) load_q();
         for (int tl = t_lo; tl < t_hi; ++tl) {
             const int bi = (tl - t_lo) & 1;
             char *buf = buf0 + bi * BUF_BYTES;
