@@ -136,6 +136,9 @@ lca_status dense_mla_attn(const lca_desc *desc, const void *Q, const void *POOL,
  * In:  q [B,H,d_qk]; pool_rep [B,S,m,d_pool], sel_rep [B,S,m,d_sel];
  *      pool_tail [B,P,k,d_pool], sel_tail [B,P,k,d_sel] with P = 1 (MLA) or S (GQA).
  * Out: O [B,H,d_pool].
+ * Built for: the MLA widths (512 + 64) and the GQA widths (128 / 128) in bf16 or fp16 with at most 16 query
+ * heads per condensed set (matrix-core kernels); MLA 512 + 64 with one set per head or 16 heads per set, and
+ * fp32 MLA 128 + 32 with 1 or 4 heads per set (general kernel).  Other shapes return LCA_ERR_UNSUPPORTED.
  */
 lca_status lca_decode_attn(const lca_desc *desc, const void *q, const void *pool_rep, const void *sel_rep,
                            const void *pool_tail, const void *sel_tail, void *O,
