@@ -145,20 +145,20 @@ def decode_bench(wl, lca, hp, torch, tdt):
     du = hp.lca_desc(wu)
     ws = torch.empty(max(lca.workspace_size(desc), lca.workspace_size(du), 256), dtype=torch.uint8, device="cuda")
     ms = time_kernel(rotating(lambda i: (lambda: lca.decode_attn(desc, q, *caches[i], O, ws))), 21, 3)
-    nbytes = B * wd.S * (m + k) * (wd.d_pool + wd.d_sel) * 2
+    nbytes = B * (wd.S * m + wd.kv_heads * k) * (wd.d_pool + wd.d_sel) * 2
     out = {"B": B, "L": wd.L, "m": m, "k": k, "ms_decode_step": ms, "algorithmic_bytes": nbytes,
            "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
-    if wd.mode == 0 and wd.d_pool == 512 and wd.d_sel == 64:
+    if (wd.mode == 0 and wd.d_pool == 512 and wd.d_sel == 64) or (wd.mode == 1 and wd.d_pool == 128 and wd.d_sel == 128):
         # the same step over 8-bit representatives (E4M3 codes + row scales; the tail stays 16-bit)
         q8c = [(torch.empty_like(c[0], dtype=torch.uint8), torch.empty_like(c[1], dtype=torch.uint8),
                 torch.empty((B, wd.S, m, 2), dtype=torch.float32, device="cuda")) for c in caches]
         out["ms_quantize_cache"] = time_kernel(
             rotating(lambda i: (lambda: lca.quantize_cache(desc, None, caches[i][0], caches[i][1], *q8c[i]))), 9, 3)
         ms8 = time_kernel(rotating(lambda i: (lambda: lca.decode_attn_q8(desc, None, q, *q8c[i], caches[i][2], caches[i][3], O, ws))), 21, 3)
-        nb8 = B * wd.S * (m * (wd.d_pool + wd.d_sel + 8) + k * (wd.d_pool + wd.d_sel) * 2)
+        nb8 = B * (wd.S * m * (wd.d_pool + wd.d_sel + 8) + wd.kv_heads * k * (wd.d_pool + wd.d_sel) * 2)
         out["q8"] = {"ms_decode_step": ms8, "algorithmic_bytes": nb8, "GBps": nb8 / (ms8 * 1e-3) / 1e9,
                      "frac_of_hbm_peak": nb8 / (ms8 * 1e-3) / 1e9 / PEAK_HBM_GBS, "speedup_vs_16bit_cache": ms / ms8,
-                     "cache_bytes_per_sequence": wd.S * m * (wd.d_pool + wd.d_sel + 8) + k * (wd.d_pool + wd.d_sel) * 2}
+                     "cache_bytes_per_sequence": wd.S * m * (wd.d_pool + wd.d_sel + 8) + wd.kv_heads * k * (wd.d_pool + wd.d_sel) * 2}
         del q8c
     del caches
     # the same step over a growing cache (spare rows, ring tail that wraps), and the online update that runs every g-th step

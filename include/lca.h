@@ -223,8 +223,8 @@ lca_status lca_quantize_cache(const lca_desc *desc, const lca_cache_layout *layo
  * lca_decode_attn_cached over the 8-bit representatives lca_quantize_cache wrote (layout may be NULL: m_cap = m,
  * k_cap = k, k_start = 0); the raw tail is read in desc->dtype as there.  Each stored value enters the products as
  * decode(code) * scale, which is exact in either 16-bit type; everything else is the decode step of section 4.3.
- * Built for the MLA widths (d_pool = 512, d_sel = 64, a 16-bit dtype, at most 16 heads per set); other shapes
- * return LCA_ERR_UNSUPPORTED.
+ * Built for the MLA widths (d_pool = 512, d_sel = 64) and the GQA widths (128 / 128), a 16-bit dtype, at most 16
+ * heads per set; other shapes return LCA_ERR_UNSUPPORTED.
  */
 lca_status lca_decode_attn_q8(const lca_desc *desc, const lca_cache_layout *layout, const void *q, const uint8_t *pool_q8,
                               const uint8_t *sel_q8, const float *scales, const void *pool_tail, const void *sel_tail,

@@ -51,6 +51,8 @@ constexpr float SUM_LIMIT = 0x1p100f;
 
 struct DgParams {
     const uint16_t *q, *k_rep, *v_rep, *k_tail, *v_tail;
+    const uint8_t *k_q8, *v_q8;            // 8-bit representatives (E4M3 codes) and their row scales [.., m_cap, 2] = (value, key), or NULL
+    const float *scales;
     float *part;
     int S, hps, m, k, n_parts, m_cap, k_cap, k_start;
     float scale_log2, bias_log2;
@@ -65,7 +67,30 @@ __device__ __forceinline__ void dma_lanes(const void *addr, unsigned lds_addr)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(addr), "s"(lds_addr));
 }
 
-template <typename E>
+// Two E4M3 codes (the low or the high half of w) times a power-of-two scale, as two elements of type E: exact.
+template <typename E> __device__ __forceinline__ unsigned cvt2_fp8(unsigned w, float scale, bool high);
+template <> __device__ __forceinline__ unsigned cvt2_fp8<__bf16>(unsigned w, float scale, bool high)
+{
+    return high ? __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, scale, true))
+                : __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, scale, false));
+}
+template <> __device__ __forceinline__ unsigned cvt2_fp8<_Float16>(unsigned w, float scale, bool high)
+{
+    return high ? __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, scale, true))
+                : __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, scale, false));
+}
+template <typename E> __device__ __forceinline__ void cvt16_fp8(const uint4 &c, float scale, uint4 &lo, uint4 &hi)
+{
+    lo = make_uint4(cvt2_fp8<E>(c.x, scale, false), cvt2_fp8<E>(c.x, scale, true), cvt2_fp8<E>(c.y, scale, false), cvt2_fp8<E>(c.y, scale, true));
+    hi = make_uint4(cvt2_fp8<E>(c.z, scale, false), cvt2_fp8<E>(c.z, scale, true), cvt2_fp8<E>(c.w, scale, false), cvt2_fp8<E>(c.w, scale, true));
+}
+
+// Q8: the representatives come as E4M3 codes with a power-of-two scale per row and component.  A tile then holds
+// entries of one kind only (the list of tiles is the representatives' tiles followed by the tail's), and a tile of
+// representatives (4 KB of key codes, 4 KB of value codes, contiguous) is fetched into registers while the tile before it
+// is used, converted -- one instruction per two codes, the row's scale riding along -- and written into the LDS
+// layout of the 16-bit tiles; from there on nothing differs.
+template <typename E, bool Q8>
 __global__ __launch_bounds__(256, 1) void decode_gqa_mfma_kernel(const DgParams kp)
 {
     typedef E ex8 __attribute__((ext_vector_type(8)));
@@ -78,9 +103,15 @@ __global__ __launch_bounds__(256, 1) void decode_gqa_mfma_kernel(const DgParams 
     const int wg_per_bs = kp.n_parts / 4;
     const int part = (blockIdx.x % wg_per_bs) * 4 + wave, bs = blockIdx.x / wg_per_bs;
     const int m = kp.m, n = kp.m + kp.k;
-    const int tiles_total = (n + BN - 1) / BN, tiles_per_part = (tiles_total + kp.n_parts - 1) / kp.n_parts;
+    const int rep_tiles = Q8 ? (m + BN - 1) / BN : 0;                       // Q8: tiles [0, rep_tiles) hold representatives only
+    const int tiles_total = Q8 ? rep_tiles + (kp.k + BN - 1) / BN : (n + BN - 1) / BN;
+    const int tiles_per_part = (tiles_total + kp.n_parts - 1) / kp.n_parts;
     const int t_lo = min(part * tiles_per_part, tiles_total), t_hi = min(t_lo + tiles_per_part, tiles_total);
-    const int e_hi = min(n, t_hi * BN);
+    const int e_hi = Q8 ? n : min(n, t_hi * BN);
+    // first entry of tile tl and the end of the entries it may show (Q8: the end of its kind)
+    auto is_q8 = [&](int tl) { return Q8 && tl < rep_tiles; };
+    auto first_entry = [&](int tl) { return !Q8 ? tl * BN : tl < rep_tiles ? tl * BN : m + (tl - rep_tiles) * BN; };
+    auto segment_end = [&](int tl) { return !Q8 ? e_hi : tl < rep_tiles ? m : n; };
     char *buf0 = bufs[wave][0];
     const unsigned buf_lds = lds_address(buf0);
 
@@ -106,11 +137,11 @@ __global__ __launch_bounds__(256, 1) void decode_gqa_mfma_kernel(const DgParams 
     // copy of tile tl into tile buffer `b`: load i brings rows 4i .. 4i+3 of the keys (i < 8) or of the values; lane l
     // fills slot l & 15 of row 4i + (l >> 4), i.e. fetches chunk (l & 15) ^ (row & 15); rows past the range repeat its last row
     auto issue_copy = [&](int tl, int b) {
-        const int e0 = tl * BN;
+        const int e0 = first_entry(tl), seg_end = segment_end(tl);
 #pragma unroll
         for (int i = 0; i < BN / 4; ++i) {
             const int r = 4 * i + (lane >> 4);
-            const int e = min(e0 + r, e_hi - 1);
+            const int e = min(e0 + r, seg_end - 1);
             int t = kp.k_start + e - m;
             t = t >= kp.k_cap ? t - kp.k_cap : t;
             const size_t off = (e < m ? (size_t)e : (size_t)t) * D + (((lane & 15) ^ (r & 15)) << 3);
@@ -119,10 +150,46 @@ __global__ __launch_bounds__(256, 1) void decode_gqa_mfma_kernel(const DgParams 
         }
     };
 
+    // Q8: the codes of one tile of representatives in registers.  Load i (of 4 for the keys, 4 for the values) brings rows
+    // 8i .. 8i+7 (lane l: 16 codes at column 16 (l & 7) of row 8i + (l >> 3)); lane r < 32 holds the two scales of row r.
+    // Rows past the end repeat the last one.
+    uint4 q8_k[BN / 8], q8_v[BN / 8];
+    float2 q8_scale = float2{1.f, 1.f};
+    auto fetch_q8 = [&](int tl) {
+        const uint8_t *kq = kp.k_q8 + (size_t)bs * kp.m_cap * D, *vq = kp.v_q8 + (size_t)bs * kp.m_cap * D;
+        const int e0 = tl * BN;
+#pragma unroll
+        for (int i = 0; i < BN / 8; ++i) {
+            const size_t off = (size_t)min(e0 + 8 * i + (lane >> 3), m - 1) * D + 16 * (lane & 7);
+            q8_k[i] = *reinterpret_cast<const uint4 *>(kq + off);
+            q8_v[i] = *reinterpret_cast<const uint4 *>(vq + off);
+        }
+        q8_scale = *reinterpret_cast<const float2 *>(kp.scales + ((size_t)bs * kp.m_cap + min(e0 + (lane & 31), m - 1)) * 2);
+    };
+    // ... converted (the row's scale riding along) and written in the 16-bit layout: chunk c of row r at slot c ^ (r & 15)
+    auto convert_q8 = [&](char *buf) {
+#pragma unroll
+        for (int i = 0; i < BN / 8; ++i) {
+            const int r = 8 * i + (lane >> 3), c0 = 2 * (lane & 7);
+            const float sv = __shfl(q8_scale.x, r, 64), sk = __shfl(q8_scale.y, r, 64);
+            uint4 lo, hi;
+            cvt16_fp8<E>(q8_k[i], sk, lo, hi);
+            *reinterpret_cast<uint4 *>(buf + r * RB + ((c0 ^ (r & 15)) << 4)) = lo;
+            *reinterpret_cast<uint4 *>(buf + r * RB + (((c0 + 1) ^ (r & 15)) << 4)) = hi;
+            cvt16_fp8<E>(q8_v[i], sv, lo, hi);
+            *reinterpret_cast<uint4 *>(buf + V_OFF + r * RB + ((c0 ^ (r & 15)) << 4)) = lo;
+            *reinterpret_cast<uint4 *>(buf + V_OFF + r * RB + (((c0 + 1) ^ (r & 15)) << 4)) = hi;
+        }
+    };
+    auto issue = [&](int tl, int b) {
+        if (is_q8(tl)) fetch_q8(tl);
+        else issue_copy(tl, b);
+    };
+
     // S^T = K Q^T for the two blocks of 16 entries of the tile in `buf`, and the logits in base 2 (scale, bias of the
     // representatives, entries past the range hidden)
     auto tile_logits = [&](int tl, const char *buf, float (&lg)[2][4]) {
-        const int e0 = tl * BN;
+        const int e0 = first_entry(tl), seg_end = segment_end(tl);
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
             ex8 kf[NKS];
@@ -134,7 +201,7 @@ __global__ __launch_bounds__(256, 1) void decode_gqa_mfma_kernel(const DgParams 
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int e = e0 + blk * 16 + 4 * r + q4;                   // accumulator row 4 q4 + r sits in LDS row 4 r + q4
-                lg[blk][r] = e < e_hi ? fmaf(sacc[r], c, e < m ? kp.bias_log2 : 0.f) : -INFINITY;
+                lg[blk][r] = e < seg_end ? fmaf(sacc[r], c, e < m ? kp.bias_log2 : 0.f) : -INFINITY;
             }
         }
     };
@@ -163,20 +230,26 @@ __global__ __launch_bounds__(256, 1) void decode_gqa_mfma_kernel(const DgParams 
         }
         q_loaded = true;
     };
-    // One sweep over the wavefront's tiles: tile tl+1 is copied into the other buffer while `body` uses tile tl.
+    // One sweep over the wavefront's tiles.  Tile tl sits in buffer (tl - t_lo) & 1; tile tl+1 is on its way -- by direct-to-LDS
+    // copy into the other buffer, or into the registers -- while `body` uses tile tl.  (A tile of codes is never followed
+    // by one before it in kind, so behind the copies of a 16-bit tile only copies of a 16-bit tile can be in flight.)
     auto sweep = [&](auto &&body) {
-        if (t_lo < t_hi) issue_copy(t_lo, 0);
+        if (t_lo < t_hi) issue(t_lo, 0);
         if (!q_loaded) load_q();
         for (int tl = t_lo; tl < t_hi; ++tl) {
             const int b = (tl - t_lo) & 1;
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");              // this wavefront's reads of the other buffer (tile tl-1) are done
-            if (tl + 1 < t_hi) {
+            char *buf = buf0 + b * TILE_BYTES;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");              // this wavefront's reads of tile tl-1 (and tl-2) are done
+            if (is_q8(tl)) {
+                convert_q8(buf);
+                if (tl + 1 < t_hi) issue(tl + 1, b ^ 1);
+            } else if (tl + 1 < t_hi) {
                 issue_copy(tl + 1, b ^ 1);
                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"(COPIES) : "memory");   // tile tl has landed, tile tl+1 may still travel
             } else {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
-            body(tl, buf0 + b * TILE_BYTES);
+            body(tl, buf);
         }
     };
 
@@ -295,7 +368,7 @@ bool decode_gqa_mfma_supported(const Dims &d)
 // least four tiles per wavefront where the cache is long enough
 int decode_gqa_mfma_parts(const Dims &d)
 {
-    const int tiles = (d.m + d.k + BN - 1) / BN;
+    const int tiles = (d.m + BN - 1) / BN + (d.k + BN - 1) / BN;      // (an upper bound when the two kinds share tiles)
     int wgs = (256 + d.B * d.S - 1) / (d.B * d.S);
     const int max_wgs = (tiles + 15) / 16;
     if (wgs > max_wgs) wgs = max_wgs;
@@ -313,9 +386,15 @@ hipError_t launch_decode_gqa_mfma(const DecodeArgs &a, hipStream_t st)
     kp.m_cap = a.m_cap; kp.k_cap = a.k_cap; kp.k_start = a.k_start;
     kp.scale_log2 = d.scale * 1.4426950408889634f;
     kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
+    kp.k_q8 = a.sel_q8; kp.v_q8 = a.pool_q8; kp.scales = a.scales;
     const unsigned grid = d.B * d.S * (a.splits / 4);
-    if (d.dtype == LCA_F16) decode_gqa_mfma_kernel<_Float16><<<grid, 256, 0, st>>>(kp);
-    else decode_gqa_mfma_kernel<__bf16><<<grid, 256, 0, st>>>(kp);
+    if (a.pool_q8 != nullptr) {
+        if (d.dtype == LCA_F16) decode_gqa_mfma_kernel<_Float16, true><<<grid, 256, 0, st>>>(kp);
+        else decode_gqa_mfma_kernel<__bf16, true><<<grid, 256, 0, st>>>(kp);
+    } else {
+        if (d.dtype == LCA_F16) decode_gqa_mfma_kernel<_Float16, false><<<grid, 256, 0, st>>>(kp);
+        else decode_gqa_mfma_kernel<__bf16, false><<<grid, 256, 0, st>>>(kp);
+    }
     return hipGetLastError();
 }
 

@@ -282,8 +282,9 @@ lca_status lca_decode_attn_q8(const lca_desc *desc, const lca_cache_layout *layo
 {
     lca::Dims d;
     LCA_TRY(make_dims(desc, d));
-    if (!lca::decode_mla_supported(d))
-        return fail(LCA_ERR_UNSUPPORTED, "lca_decode_attn_q8 is built for the MLA widths (512 + 64) in a 16-bit type with at most 16 heads per set");
+    if (!lca::decode_mla_supported(d) && !lca::decode_gqa_mfma_supported(d))
+        return fail(LCA_ERR_UNSUPPORTED,
+                    "lca_decode_attn_q8 is built for the MLA widths (512 + 64) and the GQA widths (128 / 128) in a 16-bit type with at most 16 heads per set");
     if (layout != nullptr) LCA_TRY(check_layout(d, layout, d.k));
     LCA_TRY(check_ptr(q, "q"));
     LCA_TRY(check_ptr(pool_q8, "pool_q8", d.m > 0));

@@ -52,10 +52,13 @@ def test_quantize_cache_codes_and_scales_bit_exact(dtype, d_pool, d_sel, mode):
     assert torch.isnan(sc[:, :, m:]).all()
 
 
+MLA, GQA = inputs.MODE_MLA, inputs.MODE_GQA
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
-@pytest.mark.parametrize("H,S", [(16, 1), (16, 4), (8, 8), (5, 1)])
+@pytest.mark.parametrize("mode,H,S", [(MLA, 16, 1), (MLA, 16, 4), (MLA, 8, 8), (MLA, 5, 1), (GQA, 8, 2), (GQA, 14, 2), (GQA, 4, 4), (GQA, 16, 1)])
 @pytest.mark.parametrize("L,g,w,ring", [(1000, 16, 100, False), (2100, 16, 64, True), (77, 4, 9, False), (50, 16, 64, False), (333, 8, 0, True)])
-def test_decode_over_the_quantized_cache(oracle, dtype, H, S, L, g, w, ring):
+def test_decode_over_the_quantized_cache(oracle, dtype, mode, H, S, L, g, w, ring):
     """Condense on the GPU, quantise the representatives, decode the newest token over (codes, scales, raw tail) and
     compare with the oracle's decode step over the dequantised representatives (exact in the 16-bit type) and the
     same tail.  `ring`: spare representative rows and a tail ring that wraps."""
@@ -63,35 +66,41 @@ def test_decode_over_the_quantized_cache(oracle, dtype, H, S, L, g, w, ring):
     from oracle import q8
     from paper_2604_12452_amd import lca
     B = 3
-    wl = inputs.Workload("decode_q8", B=B, L=L, H=H, S=S, d_pool=512, d_sel=64, g=g, w=w, dtype=dtype, seed=31 + L)
+    d_pool, d_sel = (512, 64) if mode == MLA else (128, 128)
+    wl = inputs.Workload("decode_q8", B=B, L=L, H=H, S=S, d_pool=d_pool, d_sel=d_sel, g=g, w=w, dtype=dtype, mode=mode, seed=31 + L,
+                         theta=10000.0 if mode == MLA else 500000.0)
     print(f"[case] {wl} ring={ring}", flush=True)
     Q, POOL, SEL = inputs.gen_all(wl)
     run = hp.GpuRun(wl, Q, POOL, SEL).condense(alpha=False)
-    m, k = wl.m, wl.k
+    m, k, P = wl.m, wl.k, wl.kv_heads
     tdt = lca.torch_dtype(run.desc)
     m_cap, k_cap, k_start = (m + 5, k + 7, k + 3) if ring else (m, k, 0)
     layout = lca.CacheLayout(m_cap=m_cap, k_cap=k_cap, k_start=k_start) if ring else None
-    pool_rep = torch.full((B, S, m_cap, 512), float("nan"), dtype=tdt, device="cuda")
-    sel_rep = torch.full((B, S, m_cap, 64), float("nan"), dtype=tdt, device="cuda")
+    pool_rep = torch.full((B, S, m_cap, d_pool), float("nan"), dtype=tdt, device="cuda")
+    sel_rep = torch.full((B, S, m_cap, d_sel), float("nan"), dtype=tdt, device="cuda")
     pool_rep[:, :, :m], sel_rep[:, :, :m] = run.pool_rep, run.sel_rep
-    pool_tail = torch.full((B, 1, k_cap, 512), float("nan"), dtype=tdt, device="cuda")
-    sel_tail = torch.full((B, 1, k_cap, 64), float("nan"), dtype=tdt, device="cuda")
+    pool_tail = torch.full((B, P, k_cap, d_pool), float("nan"), dtype=tdt, device="cuda")
+    sel_tail = torch.full((B, P, k_cap, d_sel), float("nan"), dtype=tdt, device="cuda")
     idx = (k_start + torch.arange(k, device="cuda")) % k_cap
-    pool_tail[:, 0, idx], sel_tail[:, 0, idx] = run.POOL[:, m * g:], run.SEL[:, m * g:]
+    if mode == MLA:
+        raw_pool, raw_sel = run.POOL[:, None, m * g:], run.SEL[:, None, m * g:]
+    else:
+        raw_pool, raw_sel = run.POOL[:, m * g:].permute(0, 2, 1, 3), run.SEL[:, m * g:].permute(0, 2, 1, 3)
+    pool_tail[:, :, idx], sel_tail[:, :, idx] = raw_pool, raw_sel
     pq, sq, sc = _quantize_on_gpu(lca, torch, run.desc, layout, pool_rep, sel_rep)
     q = run.Q[:, L - 1].contiguous()
-    O = torch.full((B, H, 512), float("nan"), dtype=tdt, device="cuda")
+    O = torch.full((B, H, d_pool), float("nan"), dtype=tdt, device="cuda")
     lca.decode_attn_q8(run.desc, layout, q, pq, sq, sc, pool_tail, sel_tail, O, run.ws)
     torch.cuda.synchronize()
     scn = sc.cpu().numpy().astype(np.float64)
     pr = q8.dequantize_rows(pq.cpu().numpy()[:, :, :m], scn[:, :, :m, 0])
     sr = q8.dequantize_rows(sq.cpu().numpy()[:, :, :m], scn[:, :, :m, 1])
     od = hp.oracle_desc(oracle, wl)
-    ref = oracle.decode_attn(od, hp.from_dev(q, dtype), pr, sr, hp.from_dev(run.POOL[:, None, m * g:], dtype), hp.from_dev(run.SEL[:, None, m * g:], dtype))
+    tails = (hp.from_dev(raw_pool.contiguous(), dtype), hp.from_dev(raw_sel.contiguous(), dtype))
+    ref = oracle.decode_attn(od, hp.from_dev(q, dtype), pr, sr, *tails)
     err = hp.vec_rel_err(hp.from_dev(O, dtype), ref)
     # what 8 bits cost against the 16-bit cache (reported, not gated: it is the format's error, not the kernel's)
-    ref16 = oracle.decode_attn(od, hp.from_dev(q, dtype), hp.from_dev(run.pool_rep, dtype), hp.from_dev(run.sel_rep, dtype),
-                               hp.from_dev(run.POOL[:, None, m * g:], dtype), hp.from_dev(run.SEL[:, None, m * g:], dtype))
+    ref16 = oracle.decode_attn(od, hp.from_dev(q, dtype), hp.from_dev(run.pool_rep, dtype), hp.from_dev(run.sel_rep, dtype), *tails)
     print(f"  decode over 8-bit cache: err {err:.2e} against the oracle on the same codes; the codes cost {hp.vec_rel_err(ref, ref16):.2e}", flush=True)
     assert err <= hp.TOL[dtype]
 
@@ -160,9 +169,9 @@ def test_quantize_and_q8_decode_reject_bad_arguments():
         lca.quantize_cache(desc, None, buf, buf, buf, buf, buf, first_row=wl.m + 1)
     with pytest.raises(lca.LcaError):
         lca.quantize_cache(hp.lca_desc(wl.with_(dtype="f32", d_pool=128, d_sel=32)), None, buf, buf, buf, buf, buf)
-    gqa = inputs.Workload("bad", B=1, L=200, H=8, S=2, d_pool=128, d_sel=128, g=16, w=40, dtype="bf16", mode=inputs.MODE_GQA)
+    odd = inputs.Workload("bad", B=1, L=200, H=4, S=1, d_pool=128, d_sel=32, g=16, w=40, dtype="bf16")      # widths without an 8-bit decode kernel
     with pytest.raises(lca.LcaError) as e:
-        lca.decode_attn_q8(hp.lca_desc(gqa), None, buf, buf, buf, buf, buf, buf, buf, buf)
+        lca.decode_attn_q8(hp.lca_desc(odd), None, buf, buf, buf, buf, buf, buf, buf, buf)
     assert e.value.status == lca.ERR_UNSUPPORTED
     lca.quantize_cache(desc, None, buf, buf, buf, buf, buf, first_row=wl.m)      # nothing to do: valid
     torch.cuda.synchronize()
