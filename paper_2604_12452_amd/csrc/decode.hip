@@ -338,6 +338,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st)
         const hipError_t e = launch_decode_mla(a, st);
         if (e != hipSuccess) return e;
         const int wgs = a.splits / 4;    // one partial result per workgroup of four wavefronts
+        if (wgs == 1) return hipSuccess; // ... unless a workgroup had a (sequence, set) to itself: then it wrote O
         if (a.d.dtype == LCA_F16)
             decode_merge_kernel<f16_t><<<a.d.B * a.d.H, MERGE_THREADS, wgs * sizeof(float), st>>>(a.part, (f16_t *)a.O, a.d.H / a.d.S, a.d.d_pool, wgs);
         else
@@ -348,6 +349,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t st)
         const hipError_t e = launch_decode_gqa_mfma(a, st);
         if (e != hipSuccess) return e;
         const int wgs = a.splits / 4;
+        if (wgs == 1) return hipSuccess; // a workgroup had a (sequence, KV head) to itself and wrote O
         if (a.d.dtype == LCA_F16)
             decode_merge_kernel<f16_t><<<a.d.B * a.d.H, MERGE_THREADS, wgs * sizeof(float), st>>>(a.part, (f16_t *)a.O, a.d.H / a.d.S, a.d.d_pool, wgs);
         else

@@ -54,6 +54,7 @@ struct DgParams {
     const uint8_t *k_q8, *v_q8;            // 8-bit representatives (E4M3 codes) and their row scales [.., m_cap, 2] = (value, key), or NULL
     const float *scales;
     float *part;
+    void *O;                               // not NULL: one workgroup per (sequence, KV head), which then writes the final output itself
     int S, hps, m, k, n_parts, m_cap, k_cap, k_start;
     float scale_log2, bias_log2;
 };
@@ -97,6 +98,7 @@ __global__ __launch_bounds__(256, 1) void decode_gqa_mfma_kernel(const DgParams 
     typedef E ex4 __attribute__((ext_vector_type(4)));
     __shared__ __attribute__((aligned(1024))) char bufs[4][2][TILE_BYTES];
     __shared__ float wave_ml[4][16][2];                                     // (reference, sum) per wavefront and head
+    __shared__ float l_heads[16];                                           // merged sum per head
 
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 15, q4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -338,17 +340,21 @@ __global__ __launch_bounds__(256, 1) void decode_gqa_mfma_kernel(const DgParams 
             *reinterpret_cast<floatx4 *>(mine + 16 * t) = v;
         }
     }
+    if (wave == 0 && q4 == 0) l_heads[col] = l_all;
     __syncthreads();
-    // partial result of this workgroup, natural-log units: wavefront w writes value columns [32 w, 32 w + 32) of every head
-    // (lane l: head l >> 5 + 2 j in step j, column 32 w + (l & 31))
+    // wavefront w adds up value columns [32 w, 32 w + 32) of every head (lane l: head l >> 5 + 2 j in step j, column
+    // 32 w + (l & 31)) and writes them: as this workgroup's partial result (natural-log units), or -- when the workgroup
+    // has the whole (sequence, KV head) to itself -- normalised, as the final output
     float *dst0 = kp.part + ((size_t)bs * wg_per_bs + blockIdx.x % wg_per_bs) * kp.hps * (D + 2);
     for (int h = lane >> 5; h < kp.hps; h += 2) {
         const int x = 32 * wave + (lane & 31);
         float sum = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; ++w) sum += reinterpret_cast<const float *>(bufs[w][0])[h * MROW + x];
-        dst0[(size_t)h * (D + 2) + 2 + x] = sum;
+        if (kp.O != nullptr) reinterpret_cast<E *>(kp.O)[((size_t)bs * kp.hps + h) * D + x] = (E)(sum / l_heads[h]);
+        else dst0[(size_t)h * (D + 2) + 2 + x] = sum;
     }
+    if (kp.O != nullptr) return;
     if (wave == 0 && q4 == 0 && col < kp.hps) {
         float *dst = dst0 + (size_t)col * (D + 2);
         dst[0] = m_all == -INFINITY ? -INFINITY : m_all * LN2;
@@ -387,6 +393,7 @@ hipError_t launch_decode_gqa_mfma(const DecodeArgs &a, hipStream_t st)
     kp.scale_log2 = d.scale * 1.4426950408889634f;
     kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
     kp.k_q8 = a.sel_q8; kp.v_q8 = a.pool_q8; kp.scales = a.scales;
+    kp.O = a.splits == 4 ? a.O : nullptr;
     const unsigned grid = d.B * d.S * (a.splits / 4);
     if (a.pool_q8 != nullptr) {
         if (d.dtype == LCA_F16) decode_gqa_mfma_kernel<_Float16, true><<<grid, 256, 0, st>>>(kp);

@@ -66,6 +66,7 @@ struct DmParams {
     const uint8_t *pool_q8, *sel_q8;       // 8-bit representatives (E4M3 codes) and their row scales [.., m_cap, 2], or NULL
     const float *scales;
     float *part;
+    void *O;                               // not NULL: one workgroup per (sequence, set), which then writes the final output itself
     int S, hps, m, k, n_parts, m_cap, k_cap, k_start;
     float scale_log2, bias_log2;
 };
@@ -114,6 +115,7 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
     typedef E ex4 __attribute__((ext_vector_type(4)));
     __shared__ __attribute__((aligned(1024))) char bufs[4][2][BUF_BYTES];
     __shared__ float wave_ml[4][16][2];                                     // (reference, sum) per wavefront and head
+    __shared__ float l_heads[16];                                           // merged sum per head
 
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 15, q4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -375,8 +377,11 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
             *reinterpret_cast<floatx4 *>(mine + 16 * t) = v;
         }
     }
+    if (wave == 0 && q4 == 0) l_heads[col] = l_all;
     __syncthreads();
-    // partial result of this workgroup, natural-log units: wavefront w writes value columns [128 w, 128 w + 128) of every head
+    // wavefront w adds up value columns [128 w, 128 w + 128) of every head and writes them: as this workgroup's partial
+    // result (natural-log units), or -- when the workgroup has the whole (sequence, set) to itself -- normalised, as the
+    // final output
     float *dst0 = kp.part + ((size_t)bs * wg_per_bs + blockIdx.x % wg_per_bs) * kp.hps * (DP + 2);
     for (int h = 0; h < kp.hps; ++h) {
         const int x = 128 * wave + 2 * lane;
@@ -387,8 +392,15 @@ __global__ __launch_bounds__(256, 1) void decode_mla_kernel(const DmParams kp)
             sum.x += v.x;
             sum.y += v.y;
         }
-        *reinterpret_cast<float2 *>(dst0 + (size_t)h * (DP + 2) + 2 + x) = sum;
+        if (kp.O != nullptr) {
+            typedef E ex2 __attribute__((ext_vector_type(2)));
+            const float inv = 1.f / l_heads[h];
+            *reinterpret_cast<ex2 *>(reinterpret_cast<E *>(kp.O) + ((size_t)bs * kp.hps + h) * DP + x) = ex2{(E)(sum.x * inv), (E)(sum.y * inv)};
+        } else {
+            *reinterpret_cast<float2 *>(dst0 + (size_t)h * (DP + 2) + 2 + x) = sum;
+        }
     }
+    if (kp.O != nullptr) return;
     if (wave == 0 && q4 == 0 && col < kp.hps) {
         float *dst = dst0 + (size_t)col * (DP + 2);
         dst[0] = m_all == -INFINITY ? -INFINITY : m_all * LN2;
@@ -427,6 +439,7 @@ hipError_t launch_decode_mla(const DecodeArgs &a, hipStream_t st)
     kp.scale_log2 = d.scale * 1.4426950408889634f;
     kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
     kp.pool_q8 = a.pool_q8; kp.sel_q8 = a.sel_q8; kp.scales = a.scales;
+    kp.O = a.splits == 4 ? a.O : nullptr;
     const unsigned grid = d.B * d.S * (a.splits / 4);
     if (a.pool_q8 != nullptr) {
         if (d.dtype == LCA_F16) decode_mla_kernel<_Float16, true><<<grid, 256, 0, st>>>(kp);
