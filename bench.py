@@ -351,6 +351,19 @@ def main():
         extra.update({"ms_dense_mla_attn": ms_dense, "dense_TFLOPs": dflops / (ms_dense * 1e-3) / 1e12,
                       "speedup_vs_dense_mla": ms_dense / ms_per_step, "dense_tokens_per_s": wl.B * wl.L / (ms_dense * 1e-3)})
         del O2
+        if mla:
+            # the value up-projection fused into the attention kernel's epilogue (Eq. 5's W^UV), next to the separate pass it saves:
+            # the library's batched GEMM over the stored latent output
+            W_up = (torch.randn((wl.H, 128, wl.d_pool), dtype=torch.float32, device="cuda") / wl.d_pool ** 0.5).to(tdt)
+            O_up = torch.empty((d.B, d.L, d.H, 128), dtype=tdt, device="cuda")
+            ms_up = time_kernel(lambda: lca.prefill_attn_up(d, run.Q, run.POOL, run.SEL, run.pool_rep, run.sel_rep, W_up, O_up, None, run.ws),
+                                max(3, args.steps // 2), 1)
+            Wt = W_up.transpose(1, 2).contiguous()                                     # [H, d_pool, 128]
+            Oh = O.view(d.B * d.L, d.H, wl.d_pool).transpose(0, 1)                     # [H, B L, d_pool], strided view
+            ms_proj = time_kernel(lambda: torch.bmm(Oh, Wt), 5, 2)
+            extra["fused_up_projection"] = {"ms_attn_up": ms_up, "ms_attn": ms_attn, "ms_separate_projection_library_gemm": ms_proj,
+                                            "output_bytes": d.B * d.L * d.H * 128 * 2, "latent_output_bytes": d.B * d.L * d.H * wl.d_pool * 2}
+            del W_up, O_up, Wt, Oh
         # variants: g = 32, and one condensed set per head (S = H)
         for tag, kw in ((("g32", dict(g=32)), ("per_head_sets", dict(S=wl.H))) if mla else ()):
             w2 = wl.with_(**kw)

@@ -121,6 +121,21 @@ lca_status lca_prefill_attn(const lca_desc *desc, const void *Q, const void *POO
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * lca_prefill_attn with the head's value up-projection applied before the output is written (section 3, Eq. 5:
+ * o_t = (sum_i p_i c_i) W^UV -- the matrix the absorbed form leaves to the output side; Algorithm 1 keeps it
+ * outside the attention).  The kernel multiplies while the latent output of its rows is still in registers, so the
+ * output is a quarter of the size and the separate projection pass over O is saved.  The latent output is rounded
+ * once to desc->dtype before the product, as it would be if it were stored and projected afterwards.
+ * In:  as lca_prefill_attn, plus W_up [H, 128, d_pool]: row u of head h holds W^UV_h[:, u] (output dimension major,
+ *      the layout of a linear layer's weight).
+ * Out: O_up [B,L,H,128]; lse as there.
+ * Built for the MLA widths (d_pool = 512, d_sel = 64) in bf16 or fp16; other shapes return LCA_ERR_UNSUPPORTED.
+ */
+lca_status lca_prefill_attn_up(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL,
+                               const void *pool_rep, const void *sel_rep, const void *W_up, void *O_up, float *lse,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Dense causal attention, the in-run baseline (section 3, Eq. 5; absorbed form for MLA): row t
  * attends every token i <= t.  desc->g, w, n_q and rep_logit_bias are ignored.  Same layouts as
  * lca_prefill_attn without the representatives.

@@ -240,6 +240,12 @@ def deviation_stats(d: Desc, POOL, SEL, pool_rep, sel_rep) -> np.ndarray:
     return stats
 
 
+def up_project(O, W_up) -> np.ndarray:
+    """Value up-projection of a latent-space output (section 3, Eq. 5: o = (sum_i p_i c_i) W^UV_h): O [B, n, H, d_v] and
+    W_up [H, d_up, d_v] (row u of head h = column u of W^UV_h) -> [B, n, H, d_up].  A plain contraction."""
+    return np.einsum("bnhd,hud->bnhu", np.asarray(O, dtype=np.float64), np.asarray(W_up, dtype=np.float64))
+
+
 def cache_bytes(d: Desc, elt_bytes: int):
     """(dense_bytes, condensed_bytes) of the KV cache for one attention layer."""
     a, b = ctypes.c_uint64(0), ctypes.c_uint64(0)

@@ -71,6 +71,7 @@ constexpr int NDV = DV / 32;            // 16 value tiles
 #define LCA_CHAIN_DEPTH 6
 #endif
 constexpr int CHAIN_DEPTH = LCA_CHAIN_DEPTH;   // key fragments in flight ahead of the S^T chain
+constexpr int DU = 128;                  // UP variant: width of a head's value after the up-projection
 constexpr int MLA_GRID = 256;            // workgroups of the persistent kernel = CUs of the chip
 constexpr float NEG_BIG = -1.0e30f;     // stands for -inf in running maxima (keeps exp2 arguments finite)
 constexpr float L_LIMIT = 0x1p90f;      // a row sum beyond this (or not finite) makes the workgroup repeat the item from exact maxima
@@ -85,6 +86,7 @@ struct MlaParams {
     const uint16_t *Q, *POOL, *SEL, *pool_rep, *sel_rep;
     uint16_t *O;
     float *lse;
+    const uint16_t *W_up;   // UP variant: value up-projection W^UV in fragment order (pack_up_kernel), and O is [B, L, H, DU]
     int B, L, H, S, g, w, m, dense, n_qb;
     float scale_log2, bias_log2;
 };
@@ -542,7 +544,63 @@ __device__ __forceinline__ float row_max(const floatx16 &sv, float c, float bias
 // (while the first key fragments of tile tl+1 arrive), the S^T chain of tile tl+1 with the softmax of tile tl
 // in its shadow and the copy of tile tl+3 in its last slots, then the O^T update of tile tl with the loop's
 // bookkeeping for iteration tl+1 in its shadow.
+// UP variant, after the last tile: the head's value up-projection (section 3, Eq. 5: o = (sum_i p_i c_i) W^UV, the matrix
+// the absorbed form leaves to the output side) applied to this wavefront's 32 rows while O^T is still in registers:
+//   U^T[u, query] = sum_dv W[u, dv] O^T[dv, query]      A = W (4 tiles of 32 output dimensions, from memory), B = O^T
+// Registers 8 hh .. 8 hh + 7 of accumulator tile i of lane group G are the rows dv = 32 i + 16 hh + {0..3, 8..11} + 4 G:
+// normalised and rounded to the element type they ARE a B fragment of a 32x32x16 product whose k-slot (G, j) stands for
+// that dv, so the A fragment of lane (u, G) is W[u][the same eight dv] -- two 8-byte pieces 16 bytes apart -- and
+// nothing moves between lanes.  The output rounds O once to the element type before the product, as a separate
+// projection of the stored O would.
 template <bool F16>
+__device__ __forceinline__ void up_project(const floatx16 (&acc)[NDV], float inv, const uint16_t *Wp_h, int lane, floatx16 (&up)[DU / 32])
+{
+    // Wp_h: this head's matrix in fragment order (pack_up_kernel): fragment (k-step, output tile) is 1 KB, lane l's 16 bytes at 16 l
+    const char *wl = reinterpret_cast<const char *>(Wp_h) + lane * 16;
+    constexpr int NF = 2 * NDV * (DU / 32), AHEAD = 8;     // 128 fragments, this many requested ahead of their use
+    bf16x8 wf[AHEAD];
+#pragma unroll
+    for (int f = 0; f < AHEAD; ++f) wf[f] = *reinterpret_cast<const bf16x8 *>(wl + f * 1024);
+#pragma unroll
+    for (int mt = 0; mt < DU / 32; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) up[mt][r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < NDV; ++i) {
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            union { bf16x8 v; bf16x2 b[4]; f16x2 h[4]; } of;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float x0 = acc[i][8 * hh + 2 * j] * inv, x1 = acc[i][8 * hh + 2 * j + 1] * inv;
+                if (F16) of.h[j] = f16x2{(_Float16)x0, (_Float16)x1};
+                else of.b[j] = bf16x2{(__bf16)x0, (__bf16)x1};
+            }
+#pragma unroll
+            for (int mt = 0; mt < DU / 32; ++mt) {
+                const int f = (2 * i + hh) * (DU / 32) + mt;
+                up[mt] = pv_mfma<F16>(wf[f % AHEAD], of.v, up[mt]);
+                if (f + AHEAD < NF) wf[f % AHEAD] = *reinterpret_cast<const bf16x8 *>(wl + (f + AHEAD) * 1024);
+            }
+            LCA_FENCE();
+        }
+    }
+}
+
+// W^UV of every head, [H, DU, DV] (output dimension major), into fragment order: for head h, k-step s = 2 i + hh and output
+// tile mt, lane (u = l & 31, G = l >> 5) gets W[h][32 mt + u][32 i + 16 hh + {0..3, 8..11} + 4 G] as its 16 bytes.
+__global__ __launch_bounds__(256) void pack_up_kernel(const uint16_t *__restrict__ W, uint16_t *__restrict__ Wp, int H)
+{
+    const int lane = threadIdx.x & 63;
+    const long frag = (long)blockIdx.x * 4 + (threadIdx.x >> 6);       // over (h, k-step, output tile)
+    if (frag >= (long)H * 2 * NDV * (DU / 32)) return;
+    const int mt = frag % (DU / 32), s = (frag / (DU / 32)) % (2 * NDV), h = frag / ((DU / 32) * 2 * NDV);
+    const uint16_t *src = W + ((size_t)h * DU + 32 * mt + (lane & 31)) * DV + 16 * s + 4 * (lane >> 5);
+    uint2 lo = *reinterpret_cast<const uint2 *>(src), hi = *reinterpret_cast<const uint2 *>(src + 8);
+    *reinterpret_cast<uint4 *>(Wp + (size_t)frag * 512 + lane * 8) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+}
+
+template <bool F16, bool UP>
 __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
 {
     __shared__ __attribute__((aligned(1024))) char stages[NSTAGE][STAGE_BYTES];
@@ -707,15 +765,21 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         kidx += n_slots;
         const bool has_next = item(kidx, nb, nh, nqb);
         const int out_b = cur.b, out_h = cur.h, out_t0 = cur.t0, out_t_row = cur.t_row;
+        const float l_tot = st.l_run + __shfl_xor(st.l_run, 32, 64);
+        const float inv = 1.f / l_tot;
+        floatx16 up[UP ? DU / 32 : 1];
         if (has_next) {
             cur = make_blk(kp, nb, nh, nqb, wave, n);
             issue_first_copies(cur, wave, lds0, voff_pool, voff_sel);
-            load_q(kp, cur, wave, lane, qf);
+            if (!UP) load_q(kp, cur, wave, lane, qf);
+        }
+        if constexpr (UP) {
+            // (the projection needs the registers the next item's queries would take: those are requested after it)
+            up_project<F16>(acc, inv, kp.W_up + (size_t)out_h * DU * DV, lane, up);
+            if (has_next) load_q(kp, cur, wave, lane, qf);
         }
 
         // ---- epilogue: normalise, transpose through LDS stage 3 (four passes of 128 value columns), store coalesced ----
-        const float l_tot = st.l_run + __shfl_xor(st.l_run, 32, 64);
-        const float inv = 1.f / l_tot;
         constexpr int ORS = 128 * 2 + 16;                    // staging row stride (bytes)
         static_assert(4 * 32 * ORS <= STAGE_BYTES, "output staging must fit in one tile stage");
         char *obuf = &stages[3][0] + wave * 32 * ORS;
@@ -724,12 +788,13 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         // offsets instead of 64-bit address arithmetic per store, and rows past the end of the sequence fall outside
         // the descriptor's range and are dropped.
         const int rows_valid = min(max(L - t_wfirst, 0), 32);
+        constexpr int DO = UP ? DU : DV;                     // width of an output row
         const __amdgpu_buffer_rsrc_t o_rs = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(kp.O + (((size_t)out_b * L + t_wfirst) * H + out_h) * DV), (short)0,
-            rows_valid > 0 ? ((rows_valid - 1) * H * DV + DV) * 2 : 0, RSRC_WORD3);
-        const int o_voff = ((lane >> 4) * H * DV + (lane & 15) * 8) * 2;
+            (void *)(kp.O + (((size_t)out_b * L + t_wfirst) * H + out_h) * DO), (short)0,
+            rows_valid > 0 ? ((rows_valid - 1) * H * DO + DO) * 2 : 0, RSRC_WORD3);
+        const int o_voff = ((lane >> 4) * H * DO + (lane & 15) * 8) * 2;
 #pragma unroll
-        for (int pass = 0; pass < 4; ++pass) {
+        for (int pass = 0; pass < DO / 128; ++pass) {
 #pragma unroll
             for (int d4 = 0; d4 < 4; ++d4)
 #pragma unroll
@@ -737,8 +802,9 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
                     union { bf16x4 h; f16x4 hf; uint2 u; } o;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        if (F16) o.hf[i] = (_Float16)(acc[pass * 4 + d4][r4 * 4 + i] * inv);
-                        else o.h[i] = (__bf16)(acc[pass * 4 + d4][r4 * 4 + i] * inv);
+                        const float x = UP ? up[d4][r4 * 4 + i] : acc[pass * 4 + d4][r4 * 4 + i] * inv;
+                        if (F16) o.hf[i] = (_Float16)x;
+                        else o.h[i] = (__bf16)x;
                     }
                     *reinterpret_cast<uint2 *>(obuf + n * ORS + (d4 * 32 + 8 * r4 + 4 * G) * 2) = o.u;
                 }
@@ -748,7 +814,7 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
                 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
                 const int r = r4 * 4 + (lane >> 4);
                 const uintx4 v = *reinterpret_cast<const uintx4 *>(obuf + r * ORS + (lane & 15) * 16);
-                __builtin_amdgcn_raw_buffer_store_b128(v, o_rs, o_voff, (r4 * 4 * H * DV + pass * 128) * 2, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(v, o_rs, o_voff, (r4 * 4 * H * DO + pass * 128) * 2, 0);
             }
             __builtin_amdgcn_wave_barrier();
         }
@@ -769,6 +835,8 @@ bool attn_mla_supported(const Dims &d)
     return (d.dtype == LCA_BF16 || d.dtype == LCA_F16) && d.mode == LCA_MODE_MLA && d.d_pool == DP && d.d_sel == DS && d.scale > 0.f && d.L <= (1 << 21);
 }
 
+size_t attn_mla_up_workspace_bytes(const Dims &d) { return attn_mla_supported(d) ? (size_t)d.H * DU * DV * 2 : 0; }
+
 hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st)
 {
     const Dims &d = a.d;
@@ -784,10 +852,18 @@ hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st)
     const long items = (((long)kp.n_qb * d.B + 15) / 16) * 16 * d.H;
     long grid = items < MLA_GRID ? items : MLA_GRID;
     grid = (grid + 7) / 8 * 8;
-    if (d.dtype == LCA_F16)
-        attn_mla_kernel<true><<<(unsigned)grid, 256, 0, st>>>(kp);
-    else
-        attn_mla_kernel<false><<<(unsigned)grid, 256, 0, st>>>(kp);
+    kp.W_up = nullptr;
+    if (a.W_up != nullptr) {
+        // the matrices in fragment order, in the caller's workspace (2 MB for 16 heads; microseconds)
+        const long frags = (long)d.H * 2 * NDV * (DU / 32);
+        pack_up_kernel<<<(unsigned)((frags + 3) / 4), 256, 0, st>>>((const uint16_t *)a.W_up, (uint16_t *)a.up_scratch, d.H);
+        kp.W_up = (const uint16_t *)a.up_scratch;
+        if (d.dtype == LCA_F16) attn_mla_kernel<true, true><<<(unsigned)grid, 256, 0, st>>>(kp);
+        else attn_mla_kernel<false, true><<<(unsigned)grid, 256, 0, st>>>(kp);
+    } else {
+        if (d.dtype == LCA_F16) attn_mla_kernel<true, false><<<(unsigned)grid, 256, 0, st>>>(kp);
+        else attn_mla_kernel<false, false><<<(unsigned)grid, 256, 0, st>>>(kp);
+    }
     return hipGetLastError();
 }
 

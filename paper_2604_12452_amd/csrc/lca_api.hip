@@ -60,8 +60,9 @@ size_t qbar_bytes(const lca::Dims &d) { return (((size_t)d.B * d.S * d.d_qk * si
 size_t workspace_bytes(const lca::Dims &d)
 {
     size_t need = qbar_bytes(d);
-    const size_t dec = lca::decode_workspace_bytes(d), dev = lca::deviation_workspace_bytes(d);
+    const size_t dec = lca::decode_workspace_bytes(d), dev = lca::deviation_workspace_bytes(d), up = lca::attn_mla_up_workspace_bytes(d);
     need = need > dec ? need : dec;
+    need = need > up ? need : up;
     return need > dev ? need : dev;
 }
 
@@ -162,6 +163,29 @@ lca_status lca_prefill_attn(const lca_desc *desc, const void *Q, const void *POO
     lca::AttnArgs a;
     a.d = d; a.Q = Q; a.POOL = POOL; a.SEL = SEL; a.pool_rep = pool_rep; a.sel_rep = sel_rep; a.O = O; a.lse = lse; a.dense = 0;
     return run_attn(a, static_cast<hipStream_t>(stream), "lca_prefill_attn");
+}
+
+lca_status lca_prefill_attn_up(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL, const void *pool_rep,
+                               const void *sel_rep, const void *W_up, void *O_up, float *lse, void *workspace, size_t workspace_bytes_,
+                               void *stream)
+{
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    if (!lca::attn_mla_supported(d))
+        return fail(LCA_ERR_UNSUPPORTED, "lca_prefill_attn_up is built for the MLA widths (512 + 64) in a 16-bit type, up-projection to 128 per head");
+    LCA_TRY(check_ptr(Q, "Q"));
+    LCA_TRY(check_ptr(POOL, "POOL"));
+    LCA_TRY(check_ptr(SEL, "SEL"));
+    LCA_TRY(check_ptr(pool_rep, "pool_rep", d.m > 0));
+    LCA_TRY(check_ptr(sel_rep, "sel_rep", d.m > 0));
+    LCA_TRY(check_ptr(W_up, "W_up"));
+    LCA_TRY(check_ptr(O_up, "O_up"));
+    LCA_TRY(check_ws(d, workspace, workspace_bytes_));
+    lca::AttnArgs a;
+    a.d = d; a.Q = Q; a.POOL = POOL; a.SEL = SEL; a.pool_rep = pool_rep; a.sel_rep = sel_rep; a.O = O_up; a.lse = lse; a.dense = 0;
+    a.W_up = W_up;
+    a.up_scratch = workspace;
+    return hip_status(lca::launch_attn_mla(a, static_cast<hipStream_t>(stream)), "lca_prefill_attn_up");
 }
 
 lca_status dense_mla_attn(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL, void *O, float *lse,

@@ -31,6 +31,8 @@ struct AttnArgs {
     void *O;
     float *lse;
     int dense;                // 1: every row sees all tokens i <= t, representatives unused
+    const void *W_up = nullptr;   // MLA kernel only: value up-projection [H, 128, d_pool]; O is then [B, L, H, 128]
+    void *up_scratch = nullptr;   // ... and H * 128 * d_pool elements of workspace for the matrices in fragment order
 };
 
 struct CondenseArgs {
@@ -68,6 +70,7 @@ hipError_t launch_condense(const CondenseArgs &a, hipStream_t st);
 hipError_t launch_summary_query(const Dims &d, const void *Q, int L, float *qbar, hipStream_t st);
 hipError_t launch_attn_simple(const AttnArgs &a, hipStream_t st);
 bool attn_mla_supported(const Dims &d);
+size_t attn_mla_up_workspace_bytes(const Dims &d);
 hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st);
 bool attn_gqa64_supported(const Dims &d);
 hipError_t launch_attn_gqa64(const AttnArgs &a, hipStream_t st);

@@ -21,7 +21,7 @@ REDUCE_DEFAULT, REDUCE_WEIGHTED, REDUCE_MEAN, REDUCE_MAXSEL, REDUCE_MAXPOOL = ra
 
 EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condense", "lca_prefill_attn", "dense_mla_attn",
            "lca_decode_attn", "lca_decode_attn_cached", "lca_cache_update", "lca_deviation_stats", "lca_quantize_cache",
-           "lca_decode_attn_q8", "lca_last_error")
+           "lca_decode_attn_q8", "lca_prefill_attn_up", "lca_last_error")
 
 
 class LcaError(RuntimeError):
@@ -163,6 +163,12 @@ def prefill_attn(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, O, lse, workspace,
     _check(load().lca_prefill_attn(ctypes.byref(cd), _ptr(Q), _ptr(POOL), _ptr(SEL), _ptr(pool_rep), _ptr(sel_rep),
                                    _ptr(O), _ptr(lse), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)),
                                    _stream(stream)))
+
+
+def prefill_attn_up(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, W_up, O_up, lse, workspace, stream=None):
+    cd = desc.c()
+    _check(load().lca_prefill_attn_up(ctypes.byref(cd), _ptr(Q), _ptr(POOL), _ptr(SEL), _ptr(pool_rep), _ptr(sel_rep), _ptr(W_up),
+                                      _ptr(O_up), _ptr(lse), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
 
 
 def dense_attn(desc: Desc, Q, POOL, SEL, O, lse, workspace, stream=None):

@@ -384,3 +384,42 @@ def test_deviation_stats(oracle, dtype, mode, d_pool, d_sel, L, g, w, S):
     np.testing.assert_allclose(got, ref, rtol=2e-5, atol=1e-7)      # fp32 sums of at most a few thousand terms against fp64
     if od.m == 0:
         assert (got == 0).all()
+
+
+# ---- attention with the value up-projection fused into the kernel's epilogue ---------------------------------
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("L,g,w,H,S,B", [(700, 16, 100, 2, 1, 1), (300, 8, 64, 4, 2, 2), (129, 16, 16, 3, 1, 1), (40, 4, 4, 4, 2, 3), (1, 1, 0, 1, 1, 1)])
+def test_mla_prefill_with_fused_up_projection(oracle, dtype, L, g, w, H, S, B):
+    """lca_prefill_attn_up against the oracle's attention followed by the oracle's up-projection (every row), and against
+    the library's own two-step result: its latent output, rounded as stored, projected in float64."""
+    import torch
+    from paper_2604_12452_amd import lca
+    wl = inputs.Workload("mla_up", B=B, L=L, H=H, S=S, d_pool=512, d_sel=64, g=g, w=w, dtype=dtype, seed=57 + L)
+    print(f"[case] {wl}", flush=True)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    Qf, POOLf, SELf = (inputs.to_f64(x, wl.dtype) for x in (Q, POOL, SEL))
+    rng = np.random.default_rng(5 + L)
+    W = inputs.to_storage(rng.standard_normal((H, 128, 512)) / np.sqrt(512.0), dtype)      # [H, d_up, d_c]
+    Wf = inputs.to_f64(W, dtype)
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense()
+    ref, differ = hp.check_condense(oracle, wl, run, Qf[:, wl.L - wl.nq:], POOLf, SELf)
+    run.prefill()
+    tdt = lca.torch_dtype(run.desc)
+    O_up = torch.full((B, L, H, 128), float("nan"), dtype=tdt, device="cuda")
+    lse = torch.full((B, L, H), float("nan"), dtype=torch.float32, device="cuda")
+    lca.prefill_attn_up(run.desc, run.Q, run.POOL, run.SEL, run.pool_rep, run.sel_rep, hp.to_dev(W, dtype), O_up, lse, run.ws)
+    torch.cuda.synchronize()
+    got = hp.from_dev(O_up, dtype)
+    assert np.isfinite(got).all()
+    # (a) the oracle end to end: attention over the GPU's own emitted cache (its rounded representatives and anchors), then W
+    od = hp.oracle_desc(oracle, wl)
+    rows = np.arange(L, dtype=np.int32)
+    O_lat, lse_ref = oracle.lca_attn_rows(od, rows, Qf, POOLf, SELf, hp.from_dev(run.pool_rep, dtype), hp.from_dev(run.sel_rep, dtype), want_lse=True)
+    want = oracle.up_project(O_lat, Wf)
+    err = hp.vec_rel_err(got, want)
+    # (b) the two-step path of the library itself
+    two_step = oracle.up_project(hp.from_dev(run.O, dtype), Wf)
+    err2 = hp.vec_rel_err(got, two_step)
+    print(f"  fused up-projection: err {err:.2e} against the oracle, {err2:.2e} against the library's latent output projected in float64", flush=True)
+    assert err <= hp.TOL[dtype] and err2 <= hp.TOL[dtype]
+    assert np.abs(lse.cpu().numpy().astype(np.float64) - lse_ref).max() <= hp.LSE_TOL[dtype]

@@ -183,6 +183,8 @@ def test_absorbed_form_equals_explicit_up_projection(oracle):
         logits = scale * qh @ Kh.T
         logits[np.triu_indices(L, 1)] = -np.inf
         np.testing.assert_allclose(O_dense[0, :, h] @ WUV[h], softmax(logits, -1) @ Vh, atol=1e-10)
+        # the oracle's own up-projection (weights handed over output-dimension major) is that product
+        np.testing.assert_allclose(oracle.up_project(O_dense, WUV.transpose(0, 2, 1))[0, :, h], softmax(logits, -1) @ Vh, atol=1e-10)
         # LCA in head space: representatives built per Algorithm 1 from the oracle's c^rep and anchors
         Krep = np.concatenate([c["pool_rep"][0, h] @ WUK[h], KR[0, c["anchor"][0, h]]], -1)
         Vrep = c["pool_rep"][0, h] @ WUV[h]
