@@ -48,6 +48,29 @@ def test_cfg4_128k_fp16(oracle):
     _sampled_parity(oracle, inputs.configs()["cfg4"].with_(dtype="f16"), 40, dense_rows=6)
 
 
+def test_cfg4_128k_fused_up_projection(oracle):
+    """lca_prefill_attn_up at the 128K configuration: sampled rows against the oracle's attention over the emitted cache
+    followed by its float64 up-projection."""
+    import torch
+    from paper_2604_12452_amd import lca
+    wl = inputs.configs()["cfg4"]
+    run, Q, POOL, SEL = _sampled_parity(oracle, wl, 24)
+    rng = np.random.default_rng(404)
+    W = inputs.to_storage(rng.standard_normal((wl.H, 128, wl.d_pool)) / np.sqrt(wl.d_pool), "bf16")
+    O_up = torch.full((wl.B, wl.L, wl.H, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lca.prefill_attn_up(run.desc, run.Q, run.POOL, run.SEL, run.pool_rep, run.sel_rep, hp.to_dev(W, "bf16"), O_up, None, run.ws)
+    torch.cuda.synchronize()
+    assert bool(O_up.isfinite().all()), "some output row was not written"
+    rows = inputs.sample_rows(wl, 24)
+    od = hp.oracle_desc(oracle, wl)
+    O_lat = oracle.lca_attn_rows(od, rows, inputs.to_f64(Q[:, rows], "bf16"), inputs.to_f64(POOL, "bf16"), inputs.to_f64(SEL, "bf16"),
+                                 hp.from_dev(run.pool_rep, "bf16"), hp.from_dev(run.sel_rep, "bf16"))
+    want = oracle.up_project(O_lat, inputs.to_f64(W, "bf16"))
+    err = hp.vec_rel_err(hp.from_dev(O_up[:, rows.tolist()], "bf16"), want)
+    print(f"  fused up-projection at 128K: err {err:.2e}", flush=True)
+    assert err <= hp.TOL["bf16"]
+
+
 def test_cfg5_gqa_64k_fp16_prefill(oracle):
     _sampled_parity(oracle, inputs.configs()["cfg5"].with_(dtype="f16"), 32, dense_rows=4)
 
