@@ -175,3 +175,70 @@ def test_quantize_and_q8_decode_reject_bad_arguments():
     assert e.value.status == lca.ERR_UNSUPPORTED
     lca.quantize_cache(desc, None, buf, buf, buf, buf, buf, first_row=wl.m)      # nothing to do: valid
     torch.cuda.synchronize()
+
+
+def _random_decode_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        mode = int(rng.integers(0, 2))
+        if mode == MLA:
+            H, S = [(16, 1), (16, 4), (8, 8), (7, 1), (12, 3)][int(rng.integers(0, 5))]
+        else:
+            H, S = [(8, 2), (14, 2), (4, 4), (16, 1), (6, 2), (5, 1), (3, 3)][int(rng.integers(0, 7))]
+        L = int(rng.choice([rng.integers(1, 40), rng.integers(30, 200), rng.integers(150, 700), rng.integers(600, 2500)]))
+        g = int(rng.choice([1, 2, 4, 8, 16, 32]))
+        w = int(rng.choice([0, rng.integers(0, 30), rng.integers(20, 300)]))
+        if L > w and (L - w) % g == 0:
+            w += 1                      # keep at least the new token in the raw tail (k >= 1), as the decode convention has it
+        out.append((mode, H, S, L, g, w, int(rng.integers(0, 2)), ["bf16", "f16"][int(rng.integers(0, 2))], int(rng.integers(0, 2)),
+                    int(rng.integers(1, 5))))
+    return out
+
+
+@pytest.mark.parametrize("mode,H,S,L,g,w,ring,dtype,use_q8,B", _random_decode_cases(32, 4711))
+def test_decode_random_shapes(oracle, mode, H, S, L, g, w, ring, dtype, use_q8, B):
+    """Seeded random decode steps over both cache kinds: lengths from a single token to a few thousand (one tile, ragged
+    tiles, several workgroups per sequence or one), every group size, both widths and head ratios, rings that wrap."""
+    import torch
+    from oracle import q8
+    from paper_2604_12452_amd import lca
+    d_pool, d_sel = (512, 64) if mode == MLA else (128, 128)
+    wl = inputs.Workload("decode_rand", B=B, L=L, H=H, S=S, d_pool=d_pool, d_sel=d_sel, g=g, w=w, dtype=dtype, mode=mode, seed=900 + L + g,
+                         n_q=min(g, L), theta=10000.0 if mode == MLA else 500000.0)
+    print(f"[case] {wl} ring={ring} q8={use_q8}", flush=True)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense(alpha=False)
+    m, k, P = wl.m, wl.k, wl.kv_heads
+    tdt = lca.torch_dtype(run.desc)
+    m_cap, k_cap, k_start = (m + 3, k + 5, (k + 2) % (k + 5)) if ring else (m, k, 0)
+    layout = lca.CacheLayout(m_cap=m_cap, k_cap=k_cap, k_start=k_start)
+    pool_rep = torch.full((B, S, max(m_cap, 1), d_pool), float("nan"), dtype=tdt, device="cuda")
+    sel_rep = torch.full((B, S, max(m_cap, 1), d_sel), float("nan"), dtype=tdt, device="cuda")
+    if m:
+        pool_rep[:, :, :m], sel_rep[:, :, :m] = run.pool_rep, run.sel_rep
+    pool_tail = torch.full((B, P, k_cap, d_pool), float("nan"), dtype=tdt, device="cuda")
+    sel_tail = torch.full((B, P, k_cap, d_sel), float("nan"), dtype=tdt, device="cuda")
+    idx = (k_start + torch.arange(k, device="cuda")) % k_cap
+    if mode == MLA:
+        raw_pool, raw_sel = run.POOL[:, None, m * g:], run.SEL[:, None, m * g:]
+    else:
+        raw_pool, raw_sel = run.POOL[:, m * g:].permute(0, 2, 1, 3), run.SEL[:, m * g:].permute(0, 2, 1, 3)
+    pool_tail[:, :, idx], sel_tail[:, :, idx] = raw_pool, raw_sel
+    q = run.Q[:, L - 1].contiguous()
+    O = torch.full((B, H, d_pool), float("nan"), dtype=tdt, device="cuda")
+    if use_q8:
+        pq, sq, sc = _quantize_on_gpu(lca, torch, run.desc, layout, pool_rep, sel_rep)
+        lca.decode_attn_q8(run.desc, layout, q, pq, sq, sc, pool_tail, sel_tail, O, run.ws)
+        scn = sc.cpu().numpy().astype(np.float64)
+        pr = q8.dequantize_rows(pq.cpu().numpy()[:, :, :m], scn[:, :, :m, 0])
+        sr = q8.dequantize_rows(sq.cpu().numpy()[:, :, :m], scn[:, :, :m, 1])
+    else:
+        lca.decode_attn_cached(run.desc, layout, q, pool_rep, sel_rep, pool_tail, sel_tail, O, run.ws)
+        pr, sr = hp.from_dev(pool_rep[:, :, :m], dtype), hp.from_dev(sel_rep[:, :, :m], dtype)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attn(hp.oracle_desc(oracle, wl), hp.from_dev(q, dtype), pr, sr, hp.from_dev(raw_pool.contiguous(), dtype),
+                             hp.from_dev(raw_sel.contiguous(), dtype))
+    err = hp.vec_rel_err(hp.from_dev(O, dtype), ref)
+    print(f"  err {err:.2e}", flush=True)
+    assert err <= hp.TOL[dtype]
