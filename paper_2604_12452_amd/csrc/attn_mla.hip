@@ -764,14 +764,17 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         int nb, nh, nqb;
         kidx += n_slots;
         const bool has_next = item(kidx, nb, nh, nqb);
-        const int out_b = cur.b, out_h = cur.h, out_t0 = cur.t0, out_t_row = cur.t_row;
+        const int out_b = cur.b, out_h = cur.h, out_t0 = cur.t0;
         const float l_tot = st.l_run + __shfl_xor(st.l_run, 32, 64);
         const float inv = 1.f / l_tot;
         floatx16 up[UP ? DU / 32 : 1];
         if (has_next) {
             cur = make_blk(kp, nb, nh, nqb, wave, n);
-            issue_first_copies(cur, wave, lds0, voff_pool, voff_sel);
+            // The queries first: what their addresses are computed from comes back from scratch memory (spilled registers),
+            // and such a reload waits for every vector-memory operation issued before it -- behind the copies it would wait
+            // for the tiles to arrive from HBM before the first query load could even be issued.
             if (!UP) load_q(kp, cur, wave, lane, qf);
+            issue_first_copies(cur, wave, lds0, voff_pool, voff_sel);
         }
         if constexpr (UP) {
             // (the projection needs the registers the next item's queries would take: those are requested after it)
@@ -784,6 +787,11 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         static_assert(4 * 32 * ORS <= STAGE_BYTES, "output staging must fit in one tile stage");
         char *obuf = &stages[3][0] + wave * 32 * ORS;
         const int t_wfirst = out_t0 + wave * 32;
+        // The lane number is taken afresh for everything from here on.  Values derived from it before the loop are kept in
+        // spilled registers, and every reload from scratch memory waits for ALL vector-memory operations in flight: here
+        // the next item's queries and first tiles, just requested, and below the output stores.
+        const int lane_here = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        const int n_here = lane_here & 31, G_here = lane_here >> 5;
         // The stores go through a buffer descriptor of this wavefront's rows of this head (row r at r*H*1 KB): scalar
         // offsets instead of 64-bit address arithmetic per store, and rows past the end of the sequence fall outside
         // the descriptor's range and are dropped.
@@ -792,7 +800,7 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         const __amdgpu_buffer_rsrc_t o_rs = __builtin_amdgcn_make_buffer_rsrc(
             (void *)(kp.O + (((size_t)out_b * L + t_wfirst) * H + out_h) * DO), (short)0,
             rows_valid > 0 ? ((rows_valid - 1) * H * DO + DO) * 2 : 0, RSRC_WORD3);
-        const int o_voff = ((lane >> 4) * H * DO + (lane & 15) * 8) * 2;
+        const int o_voff = ((lane_here >> 4) * H * DO + (lane_here & 15) * 8) * 2;
 #pragma unroll
         for (int pass = 0; pass < DO / 128; ++pass) {
 #pragma unroll
@@ -806,24 +814,31 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
                         if (F16) o.hf[i] = (_Float16)x;
                         else o.h[i] = (__bf16)x;
                     }
-                    *reinterpret_cast<uint2 *>(obuf + n * ORS + (d4 * 32 + 8 * r4 + 4 * G) * 2) = o.u;
+                    *reinterpret_cast<uint2 *>(obuf + n_here * ORS + (d4 * 32 + 8 * r4 + 4 * G_here) * 2) = o.u;
                 }
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int r4 = 0; r4 < 8; ++r4) {                 // one wave-wide store covers four rows of 256 B
                 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
-                const int r = r4 * 4 + (lane >> 4);
-                const uintx4 v = *reinterpret_cast<const uintx4 *>(obuf + r * ORS + (lane & 15) * 16);
+                const int r = r4 * 4 + (lane_here >> 4);
+                const uintx4 v = *reinterpret_cast<const uintx4 *>(obuf + r * ORS + (lane_here & 15) * 16);
                 __builtin_amdgcn_raw_buffer_store_b128(v, o_rs, o_voff, (r4 * 4 * H * DO + pass * 128) * 2, 0);
             }
             __builtin_amdgcn_wave_barrier();
         }
-        if (kp.lse != nullptr && G == 0 && out_t_row < L)
-            kp.lse[((size_t)out_b * L + out_t_row) * H + out_h] = (st.m_ref + log2f(l_tot)) * 0.6931471805599453f;
+        if (kp.lse != nullptr) {
+            const int t_row_here = t_wfirst + n_here;
+            if (G_here == 0 && t_row_here < L)
+                kp.lse[((size_t)out_b * L + t_row_here) * H + out_h] = (st.m_ref + log2f(l_tot)) * 0.6931471805599453f;
+        }
         if (!has_next) break;
-        // the next item's queries have been on their way since before the output was written
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        q_to_fragments(qbuf, lane, qf);
+        // the next item's queries have been on their way since before the output was written; the wait leaves the output
+        // stores (and, when they were issued after the queries, the first tiles' copies) in flight: vector-memory operations
+        // complete in the order issued
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DO / 128) * 8 + (UP ? 0 : 3 * COPIES_PER_TILE)) : "memory");
+        // (the fresh lane number again: the eight LDS addresses q_to_fragments derives from it would otherwise be kept across
+        // the whole item, in spilled registers)
+        q_to_fragments(qbuf, lane_here, qf);
     }
 }
 
