@@ -28,7 +28,7 @@ def test_pair_count_closed_forms():
     L, w, g = 257, 40, 8
     brute = sum(max(0, (t + 1 - w) // g) + (t + 1 - max(0, (t + 1 - w) // g) * g) for t in range(L))
     assert bench.pair_count(L, w, g) == brute
-    # the 128K configuration: the pairs per head quoted in the design notes
+    # the 128K configuration: 663 M visible pairs per head, 23.09 TFLOP per launch, 159.5 MB condensed
     wl = inputs.configs()["cfg4"]
     assert abs(bench.pair_count(wl.L, wl.w, wl.g) - 663e6) < 1e6
     flops = 2.0 * (wl.d_qk + wl.d_v) * wl.B * wl.H * bench.pair_count(wl.L, wl.w, wl.g)
