@@ -25,7 +25,7 @@
  * "Sets": S condensed sets per sequence; query head h uses set h / (H / S).  In MLA mode all
  * sets read the same C^KV / K^R; in GQA mode set s reads KV head s.
  *
- * Readings of points the paper leaves open (listed in the repository's design notes):
+ * Readings taken where the paper leaves a point open:
  *   - every query row t sees what a decode step at that position would see: representatives of
  *     the groups lying wholly inside tokens [0, t+1-w), then raw tokens up to and including t
  *     (appendix A.2 notation: recent window R, distant history H, per query t);
