@@ -43,6 +43,12 @@ def test_cfg4_128k(oracle, g):
     _sampled_parity(oracle, inputs.configs()["cfg4"].with_(g=g), 40, dense_rows=6 if g == 16 else 0)
 
 
+def test_cfg4_128k_per_head_sets(oracle):
+    """The 128K configuration with one condensed set per query head (S = H), the other reading of "per head"."""
+    wl = inputs.configs()["cfg4"]
+    _sampled_parity(oracle, wl.with_(S=wl.H), 24)
+
+
 def test_cfg4_128k_fp16(oracle):
     """The 128K configuration with fp16 inputs, cache and output (the paper's implementation names both 16-bit types)."""
     _sampled_parity(oracle, inputs.configs()["cfg4"].with_(dtype="f16"), 40, dense_rows=6)
