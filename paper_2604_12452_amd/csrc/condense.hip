@@ -82,11 +82,14 @@ template <> struct Elt<float> {
 
 // ---------------------------------------------------------------------------------------------
 // Summary query: qbar[b,s,x] = mean over t in [L-n_q, L), h in set s of Q[b,t,h,x].
-// One workgroup of 16 wavefronts per (b, s, 64 chunks of 16 bytes): the wavefronts split the (t, h)
-// list, each lane keeps 8 independent 16-byte loads in flight, and the partial sums are merged in a
-// fixed order through LDS (deterministic).
+// One workgroup of 16 wavefronts per (b, s, 64 chunks of 16 bytes): wavefront v takes the (t, h) pairs
+// v, v+16, v+32, ... (row addresses are wave-uniform, kept in scalar registers and stepped without
+// divisions), each lane keeps up to 16 independent 16-byte loads in flight -- the 256 pairs of 16 queries x
+// 16 heads are one round trip to memory --, and the partial sums are merged in a fixed order through LDS
+// (deterministic), one output value per thread.
 // ---------------------------------------------------------------------------------------------
 constexpr int SQ_WAVES = 16;
+constexpr int SQ_DEPTH = 16;
 template <typename T>
 __global__ __launch_bounds__(SQ_WAVES *WAVE) void summary_query_kernel(const T *__restrict__ Q, float *__restrict__ qbar, int L, int H, int S,
                                                                        int d_qk, int n_q)
@@ -97,23 +100,27 @@ __global__ __launch_bounds__(SQ_WAVES *WAVE) void summary_query_kernel(const T *
     const int xblocks = (n_chunks + WAVE - 1) / WAVE;
     const int bs = blockIdx.x / xblocks, xb = blockIdx.x % xblocks;
     const int b = bs / S, s = bs % S, hps = H / S;
-    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    const int lane = threadIdx.x & (WAVE - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
     const int chunk = xb * WAVE + lane;
     const int n = n_q * hps;                       // (t, h) pairs, pair u -> t = L - n_q + u / hps, h = s*hps + u % hps
     float acc[EPC];
 #pragma unroll
     for (int e = 0; e < EPC; ++e) acc[e] = 0.f;
     if (chunk < n_chunks) {
-        for (int u0 = wave; u0 < n; u0 += SQ_WAVES * 8) {
-            uint4 v[8];
+        const int step_t = SQ_WAVES / hps, step_h = SQ_WAVES % hps;
+        int ut = wave / hps, uh = wave % hps;       // pair u = wave + 16 j  ->  (u / hps, u % hps), stepped with carry
+        const T *const base = Q + ((size_t)b * L + (L - n_q)) * H * d_qk + (size_t)s * hps * d_qk + chunk * EPC;
+        for (int u0 = wave; u0 < n; u0 += SQ_WAVES * SQ_DEPTH) {
+            uint4 v[SQ_DEPTH];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < SQ_DEPTH; ++i) {
                 const int u = u0 + i * SQ_WAVES;
-                v[i] = u < n ? *reinterpret_cast<const uint4 *>(Q + (((size_t)b * L + (L - n_q + u / hps)) * H + s * hps + u % hps) * d_qk + chunk * EPC)
-                             : make_uint4(0, 0, 0, 0);
+                v[i] = u < n ? *reinterpret_cast<const uint4 *>(base + ((size_t)ut * H + uh) * d_qk) : make_uint4(0, 0, 0, 0);
+                ut += step_t; uh += step_h;
+                if (uh >= hps) { uh -= hps; ++ut; }
             }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < SQ_DEPTH; ++i) {
                 float f[EPC];
                 Elt<T>::unpack(v[i], f);
 #pragma unroll
@@ -124,13 +131,13 @@ __global__ __launch_bounds__(SQ_WAVES *WAVE) void summary_query_kernel(const T *
 #pragma unroll
     for (int e = 0; e < EPC; ++e) part[wave][lane][e] = acc[e];
     __syncthreads();
-    if (wave == 0 && chunk < n_chunks) {
+    // thread x sums the 16 partial values of component x % EPC of chunk x / EPC (wavefront order: the same sum on every run)
+    const int ol = threadIdx.x / EPC, oe = threadIdx.x % EPC, ochunk = xb * WAVE + ol;
+    if (ol < WAVE && ochunk < n_chunks) {
+        float t = 0.f;
 #pragma unroll
-        for (int e = 0; e < EPC; ++e) {
-            float t = 0.f;
-            for (int wv = 0; wv < SQ_WAVES; ++wv) t += part[wv][lane][e];
-            qbar[(size_t)bs * d_qk + chunk * EPC + e] = t / (float)n;
-        }
+        for (int wv = 0; wv < SQ_WAVES; ++wv) t += part[wv][ol][oe];
+        qbar[(size_t)bs * d_qk + ochunk * EPC + oe] = t / (float)n;
     }
 }
 
