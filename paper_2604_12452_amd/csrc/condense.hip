@@ -160,8 +160,9 @@ __device__ __forceinline__ float wave_reduce_scatter(float (&v)[R], int lane)
         const bool hi = (lane & mask) != 0;
 #pragma unroll
         for (int i = 0; i < n / 2; ++i) {
-            const float send = hi ? v[i] : v[i + n / 2];
-            const float keep = hi ? v[i + n / 2] : v[i];
+            const float lo_half = v[i], hi_half = v[i + n / 2];      // (values first: a choice between two array elements
+            const float send = hi ? lo_half : hi_half;               // would become an indexed access to the array)
+            const float keep = hi ? hi_half : lo_half;
             v[i] = keep + __shfl_xor(send, mask, WAVE);
         }
     }
@@ -176,8 +177,8 @@ __device__ __forceinline__ float wave_reduce_scatter(float (&v)[R], int lane)
 //   sel part  : lane l owns row (l >> SH) and every (64/R)-th chunk of it, so its partial dot already
 //               sits with the lane that receives that row's score from the reduce-scatter
 // ---------------------------------------------------------------------------------------------
-template <typename T, int DP, int DS, int G, bool MLA>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8)))
+template <typename T, int DP, int DS, int G, bool MLA, bool HOLD>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(HOLD ? 2 : 3, 8)))
 void condense_reg_kernel(const T *__restrict__ POOL, const T *__restrict__ SEL, const float *__restrict__ qbar,
                          T *__restrict__ pool_rep, T *__restrict__ sel_rep, int32_t *__restrict__ anchor,
                          float *__restrict__ alpha_dbg, int B, int L, int S, int m, float scale)
@@ -206,6 +207,27 @@ void condense_reg_kernel(const T *__restrict__ POOL, const T *__restrict__ SEL, 
     const int pcol = (has_pool ? lane : 0) * EPC;
     const int my_row = lane >> SH, sub = lane & (LPR - 1);
 
+    // the loads of sub-block sb: R whole pool rows (a chunk per lane) and this lane's chunks of its own sel row
+    auto load_sub_block = [&](int sb, uint4 (&pdata)[R], uint4 (&sdata)[SPL]) {
+        const int row0 = j * G + sb * R;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            pdata[r] = has_pool ? *reinterpret_cast<const uint4 *>(pool_base + (size_t)(row0 + r) * P * DP + pcol) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < SPL; ++i) {
+            const int c = sub + i * LPR;
+            sdata[i] = c < NCS ? *reinterpret_cast<const uint4 *>(sel_base + (size_t)(row0 + my_row) * P * DS + c * EPC) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    // HOLD (several sets over one latent sequence, at most two sub-blocks): the group is loaded once and stays in
+    // registers for every set; otherwise a sub-block is loaded when its turn comes.
+    constexpr int NHELD = HOLD ? NSB : 1;
+    uint4 pheld[NHELD][R], sheld[NHELD][SPL];
+    if constexpr (HOLD) {
+#pragma unroll
+        for (int sb = 0; sb < NSB; ++sb) load_sub_block(sb, pheld[sb], sheld[sb]);
+    }
+
     const int s_begin = MLA ? 0 : p, s_end = MLA ? S : p + 1;
     for (int s = s_begin; s < s_end; ++s) {
         const float *qb = qbar + ((size_t)b * S + s) * DQK;
@@ -217,19 +239,7 @@ void condense_reg_kernel(const T *__restrict__ POOL, const T *__restrict__ SEL, 
         int best_row = 0;
         const size_t unit = ((size_t)b * S + s) * m + j;
 
-#pragma unroll 1
-        for (int sb = 0; sb < NSB; ++sb) {
-            const int row0 = j * G + sb * R;
-            // issue every load of the sub-block first
-            uint4 pdata[R], sdata[SPL];
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                pdata[r] = has_pool ? *reinterpret_cast<const uint4 *>(pool_base + (size_t)(row0 + r) * P * DP + pcol) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < SPL; ++i) {
-                const int c = sub + i * LPR;
-                sdata[i] = c < NCS ? *reinterpret_cast<const uint4 *>(sel_base + (size_t)(row0 + my_row) * P * DS + c * EPC) : make_uint4(0, 0, 0, 0);
-            }
+        auto sub_block = [&](int sb, const uint4 (&pdata)[R], const uint4 (&sdata)[SPL]) {
             // sel part of the score: this lane's chunks of its own row, summed over the row's lanes
             float ssum = 0.f;
 #pragma unroll
@@ -291,6 +301,17 @@ void condense_reg_kernel(const T *__restrict__ POOL, const T *__restrict__ SEL, 
                 for (int e = 0; e < EPC; ++e) acc[e] = fmaf(pr, f[e], acc[e]);
             }
             m_run = m_new;
+        };
+        if constexpr (HOLD) {
+#pragma unroll
+            for (int sb = 0; sb < NSB; ++sb) sub_block(sb, pheld[sb], sheld[sb]);
+        } else {
+#pragma unroll 1
+            for (int sb = 0; sb < NSB; ++sb) {
+                uint4 pdata[R], sdata[SPL];
+                load_sub_block(sb, pdata, sdata);            // every load of the sub-block is issued first
+                sub_block(sb, pdata, sdata);
+            }
         }
 
         const float inv_l = 1.f / l_run;
@@ -425,7 +446,14 @@ hipError_t run_reg(const CondenseArgs &a, hipStream_t st)
     const Dims &d = a.d;
     const long units = (long)d.B * (MLA ? 1 : d.S) * d.m;
     const int blocks = (int)((units + 3) / 4);
-    condense_reg_kernel<T, DP, DS, G, MLA><<<blocks, 256, 0, st>>>(
+    if constexpr (MLA && G <= 16) {
+        if (d.S > 1) {       // every set reads the same group: it is kept in registers across the sets
+            condense_reg_kernel<T, DP, DS, G, MLA, true><<<blocks, 256, 0, st>>>(
+                (const T *)a.POOL, (const T *)a.SEL, a.qbar, (T *)a.pool_rep, (T *)a.sel_rep, a.anchor, a.alpha_dbg, d.B, d.L, d.S, d.m, d.scale);
+            return hipGetLastError();
+        }
+    }
+    condense_reg_kernel<T, DP, DS, G, MLA, false><<<blocks, 256, 0, st>>>(
         (const T *)a.POOL, (const T *)a.SEL, a.qbar, (T *)a.pool_rep, (T *)a.sel_rep, a.anchor, a.alpha_dbg, d.B, d.L, d.S, d.m, d.scale);
     return hipGetLastError();
 }
