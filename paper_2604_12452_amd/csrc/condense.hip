@@ -199,7 +199,9 @@ void condense_reg_kernel(const T *__restrict__ POOL, const T *__restrict__ SEL, 
     const int P = MLA ? 1 : S;                  // KV sources per sequence
     const long n_units = (long)B * P * m;
     if (wave_id >= n_units) return;             // whole wave leaves together
-    const int j = (int)(wave_id % m), p = (int)((wave_id / m) % P), b = (int)(wave_id / ((long)m * P));
+    // the KV sources of a group are neighbours in the unit order: the P wavefronts that read the P interleaved parts of the
+    // same g token rows run at the same time, and the rows are fetched from memory as whole contiguous pieces
+    const int p = (int)(wave_id % P), j = (int)((wave_id / P) % m), b = (int)(wave_id / ((long)m * P));
 
     const T *pool_base = POOL + ((size_t)b * L * P + p) * DP;   // row i at + i * P * DP
     const T *sel_base = SEL + ((size_t)b * L * P + p) * DS;
