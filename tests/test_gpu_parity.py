@@ -81,6 +81,22 @@ def test_mla_mfma_small_all_rows(oracle, L, g, w, H, S, B, dtype):
     _full_parity(oracle, wl)
 
 
+@pytest.mark.parametrize("L,g,w,H,S,B,mode", [
+    (150, 16, 40, 24, 1, 1, inputs.MODE_MLA),      # 24 heads in one set: 384 (position, head) pairs, two rounds of loads per wavefront
+    (96, 8, 10, 40, 2, 2, inputs.MODE_MLA),        # 20 heads per set
+    (130, 16, 20, 32, 1, 1, inputs.MODE_MLA),      # more heads per set than wavefronts in the workgroup
+    (120, 16, 24, 36, 2, 1, inputs.MODE_GQA),      # 18 query heads per KV head
+])
+def test_condense_many_heads_per_set(oracle, L, g, w, H, S, B, mode):
+    """Condensation alone with more query heads per set than the 16 of the benchmark configurations: the summary query
+    walks its (position, head) list in steps of 16 pairs with a carry, which only such head counts exercise in full."""
+    d = (512, 64) if mode == inputs.MODE_MLA else (128, 128)
+    wl = inputs.Workload("many_heads", B=B, L=L, H=H, S=S, d_pool=d[0], d_sel=d[1], g=g, w=w, dtype="bf16", mode=mode, seed=900 + H)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense(alpha=True)
+    hp.check_condense(oracle, wl, run, inputs.to_f64(Q[:, wl.L - wl.nq:], wl.dtype), inputs.to_f64(POOL, wl.dtype), inputs.to_f64(SEL, wl.dtype))
+
+
 def _random_shapes(mode, n, seed):
     """Seeded draws of valid shapes for the MFMA kernels: lengths around the tile and block sizes, every group size,
     windows from none to longer than the sequence, several head ratios."""
