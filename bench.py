@@ -33,10 +33,10 @@ def pair_count(L: int, w: int, g: int, rows=None) -> int:
     return int((mt + t + 1 - mt * g).sum())
 
 
-def condense_bytes(wl) -> int:
-    """Algorithmic HBM bytes of one condensation: groups read once, representatives + anchors written."""
+def condense_bytes(wl, m: int) -> int:
+    """Algorithmic HBM bytes of one condensation over m groups: groups read once, representatives + anchors written."""
     row = (wl.d_pool + wl.d_sel) * 2
-    return wl.B * wl.kv_heads * wl.m * wl.g * row + wl.B * wl.S * wl.m * (row + 4) + wl.nq * wl.H * wl.d_qk * 2
+    return wl.B * wl.kv_heads * m * wl.g * row + wl.B * wl.S * m * (row + 4) + wl.nq * wl.H * wl.d_qk * 2
 
 
 def time_kernel(fn, iters: int, warmup: int, behind=None):
@@ -140,7 +140,7 @@ def decode_bench(wl, lca, hp, torch, tdt):
     B = 32
     wd = wl.with_(B=B, L=wl.L + 1)
     desc = hp.lca_desc(wd)
-    m, k = wd.m, wd.k
+    m, k = desc.m, desc.k
     mk = lambda *shape: torch.randn(shape, dtype=tdt, device="cuda")
     caches = [(mk(B, wd.S, m, wd.d_pool), mk(B, wd.S, m, wd.d_sel), mk(B, wd.kv_heads, k, wd.d_pool), mk(B, wd.kv_heads, k, wd.d_sel))
               for _ in range(N_ROT)]
@@ -210,7 +210,7 @@ def sweep_bench(wl, args, lca, hp, torch, inputs, tdt):
         fl = 2.0 * (w2.d_qk + w2.d_v) * w2.B * w2.H * pair_count(w2.L, w2.w, w2.g)
         label = dict(g=w2.g, w=w2.w, n_q=w2.nq, pool=names.get(d2.pool_reduce, "weighted"), sel=names.get(d2.sel_reduce, "maxsel"))
         rows.append({**label, "ms_condense": mc, "ms_attn": ma, "tokens_per_s": w2.B * w2.L / ((mc + ma) * 1e-3),
-                     "attn_TFLOPs": fl / (ma * 1e-3) / 1e12, "condense_GBps": condense_bytes(w2) / (mc * 1e-3) / 1e9,
+                     "attn_TFLOPs": fl / (ma * 1e-3) / 1e12, "condense_GBps": condense_bytes(w2, d2.m) / (mc * 1e-3) / 1e9,
                      "kv_cache_bytes_lca": cb, "kv_cache_saved_frac": 1.0 - cb / db})
         del pr, sr, an, ws2
     return rows
@@ -318,7 +318,7 @@ def main():
     pairs = pair_count(wl.L, wl.w, wl.g)
     flops = 2.0 * (wl.d_qk + wl.d_v) * wl.B * wl.H * pairs
     tflops = flops / (ms_attn * 1e-3) / 1e12
-    cbytes = condense_bytes(wl)
+    cbytes = condense_bytes(wl, d.m)
 
     extra = {
         "ms_condense": ms_cond, "ms_attn": ms_attn,
@@ -389,7 +389,7 @@ def main():
             db, cb = lca.cache_bytes(d2)
             fl = 2.0 * (w2.d_qk + w2.d_v) * w2.B * w2.H * pair_count(w2.L, w2.w, w2.g)
             extra[tag] = {"ms_condense": mc, "ms_attn": ma, "tokens_per_s": w2.B * w2.L / ((mc + ma) * 1e-3),
-                          "attn_TFLOPs": fl / (ma * 1e-3) / 1e12, "condense_GBps": condense_bytes(w2) / (mc * 1e-3) / 1e9,
+                          "attn_TFLOPs": fl / (ma * 1e-3) / 1e12, "condense_GBps": condense_bytes(w2, d2.m) / (mc * 1e-3) / 1e9,
                           "kv_cache_bytes_lca": cb, "kv_cache_saved_frac": 1.0 - cb / db}
             del pr, sr, an
 

@@ -86,6 +86,13 @@ typedef struct {
 lca_status lca_workspace_size(const lca_desc *desc, size_t *bytes);
 
 /*
+ * The partition of section 4.2 (Algorithm 1: groups, then local window plus remainder) for this descriptor:
+ * m = floor((L - w) / g) groups (0 when L <= w) and k = L - m*g raw tokens, so that m*g + k = L.  These are the
+ * row counts of every representative buffer ([B,S,m,.]) and raw tail ([B,P,k,.]) in the calls below.  Host only.
+ */
+lca_status lca_condensed_rows(const lca_desc *desc, int32_t *m, int32_t *k);
+
+/*
  * KV-cache footprint of one layer (section 4.3, decoding paragraph; appendix B): dense = one
  * (pool, sel) row per token and KV head; condensed = S*m representatives plus k raw tail rows per
  * KV head.  Host only.

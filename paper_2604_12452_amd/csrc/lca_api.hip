@@ -95,11 +95,12 @@ lca_status hip_status(hipError_t e, const char *what)
     return fail(LCA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// The two matrix-core kernels take their widths in a 16-bit type with a positive scale (their fixed-reference softmax
+// orders logits by the raw products); every other descriptor, a zero or negative scale included, runs the general kernel.
 lca_status run_attn(const lca::AttnArgs &a, hipStream_t st, const char *what)
 {
     if (lca::attn_mla_supported(a.d)) return hip_status(lca::launch_attn_mla(a, st), what);
     if (lca::attn_gqa64_supported(a.d)) return hip_status(lca::launch_attn_gqa64(a, st), what);
-    if (lca::attn_mfma_supported(a.d)) return hip_status(lca::launch_attn_mfma(a, st), what);
     return hip_status(lca::launch_attn_simple(a, st), what);
 }
 
@@ -126,6 +127,16 @@ lca_status lca_cache_bytes(const lca_desc *desc, size_t *dense_bytes, size_t *co
     const size_t row = (size_t)(d.d_pool + d.d_sel) * d.elt;
     *dense_bytes = (size_t)d.B * d.L * d.P * row;
     *condensed_bytes = (size_t)d.B * ((size_t)d.S * d.m + (size_t)d.P * d.k) * row;
+    return LCA_OK;
+}
+
+lca_status lca_condensed_rows(const lca_desc *desc, int32_t *m, int32_t *k)
+{
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    if (m == nullptr || k == nullptr) return fail(LCA_ERR_INVALID_ARG, "output pointer is NULL");
+    *m = d.m;
+    *k = d.k;
     return LCA_OK;
 }
 

@@ -74,8 +74,6 @@ size_t attn_mla_up_workspace_bytes(const Dims &d);
 hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st);
 bool attn_gqa64_supported(const Dims &d);
 hipError_t launch_attn_gqa64(const AttnArgs &a, hipStream_t st);
-bool attn_mfma_supported(const Dims &d);
-hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t st);
 bool decode_supported(const Dims &d);
 int decode_splits(const Dims &d);
 size_t decode_workspace_bytes(const Dims &d);

@@ -56,14 +56,6 @@ class Workload:
         return self.d_pool
 
     @property
-    def m(self) -> int:
-        return (self.L - self.w) // self.g if self.L > self.w else 0
-
-    @property
-    def k(self) -> int:
-        return self.L - self.m * self.g
-
-    @property
     def nq(self) -> int:
         return self.n_q if self.n_q > 0 else self.g
 

@@ -12,14 +12,14 @@ import os
 from dataclasses import dataclass
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("LCA_LIB_PATH", os.path.join(_PKG, "liblca.so"))   # override: another build of the same library
+LIB_PATH = os.path.join(_PKG, "liblca.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 MODE_MLA, MODE_GQA = 0, 1
 BF16, F32, F16 = 0, 1, 2
 REDUCE_DEFAULT, REDUCE_WEIGHTED, REDUCE_MEAN, REDUCE_MAXSEL, REDUCE_MAXPOOL = range(5)
 
-EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condense", "lca_prefill_attn", "dense_mla_attn",
+EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condensed_rows", "lca_condense", "lca_prefill_attn", "dense_mla_attn",
            "lca_decode_attn", "lca_decode_attn_cached", "lca_cache_update", "lca_deviation_stats", "lca_quantize_cache",
            "lca_decode_attn_q8", "lca_prefill_attn_up", "lca_last_error")
 
@@ -75,11 +75,13 @@ class Desc:
 
     @property
     def m(self) -> int:
-        return (self.L - self.w) // self.g if self.L > self.w else 0
+        """Number of groups / representatives per set, as the library derives it (lca_condensed_rows)."""
+        return condensed_rows(self)[0]
 
     @property
     def k(self) -> int:
-        return self.L - self.m * self.g
+        """Number of raw tail tokens, as the library derives it (lca_condensed_rows)."""
+        return condensed_rows(self)[1]
 
     @property
     def kv_heads(self) -> int:
@@ -116,6 +118,8 @@ def _ptr(t):
         return ctypes.c_void_p(t)
     if not t.is_contiguous():
         raise ValueError("liblca needs contiguous tensors")
+    if not t.is_cuda:
+        raise ValueError(f"a tensor of shape {tuple(t.shape)} is not a device tensor: liblca takes device pointers")
     return ctypes.c_void_p(t.data_ptr())
 
 
@@ -137,11 +141,58 @@ def _check(status: int):
         raise LcaError(status, load().lca_last_error().decode())
 
 
+# The library receives bare pointers and cannot see how large a buffer is, so the binding compares every tensor with the
+# size and element type the header documents for it before anything is launched: a kernel reading or writing past a
+# buffer is a GPU memory fault, not an exception.  Only sizes and types are compared (marshalling), no values.
+_ELT_NAMES = {BF16: ("torch.bfloat16", "torch.int16", "torch.uint16"), F32: ("torch.float32",), F16: ("torch.float16",)}
+_KIND_NAMES = {"i32": ("torch.int32",), "f32": ("torch.float32",), "u8": ("torch.uint8",)}
+
+
+def _fit(desc: Desc, t, name: str, elems: int, kind: str = "elt", optional: bool = False):
+    """Raise ValueError unless tensor `t` has the element type `kind` stands for and holds at least `elems` elements."""
+    if t is None:
+        if optional or elems == 0:
+            return
+        raise ValueError(f"{name} is required")
+    if isinstance(t, int):          # a raw device address: the caller vouches for it
+        return
+    names = _ELT_NAMES[desc.dtype] if kind == "elt" else _KIND_NAMES[kind]
+    if str(t.dtype) not in names:
+        raise ValueError(f"{name} has dtype {t.dtype}, expected {' / '.join(names)}")
+    if t.numel() < elems:
+        raise ValueError(f"{name} holds {t.numel()} elements, the descriptor needs {elems}")
+
+
+def _fit_inputs(desc: Desc, Q, POOL, SEL, L=None):
+    L = desc.L if L is None else L
+    _fit(desc, Q, "Q", desc.B * L * desc.H * desc.d_qk)
+    _fit(desc, POOL, "POOL", desc.B * L * desc.kv_heads * desc.d_pool)
+    _fit(desc, SEL, "SEL", desc.B * L * desc.kv_heads * desc.d_sel)
+
+
+def _fit_reps(desc: Desc, pool_rep, sel_rep, rows: int):
+    _fit(desc, pool_rep, "pool_rep", desc.B * desc.S * rows * desc.d_pool)
+    _fit(desc, sel_rep, "sel_rep", desc.B * desc.S * rows * desc.d_sel)
+
+
+def _fit_tails(desc: Desc, pool_tail, sel_tail, rows: int):
+    _fit(desc, pool_tail, "pool_tail", desc.B * desc.kv_heads * rows * desc.d_pool)
+    _fit(desc, sel_tail, "sel_tail", desc.B * desc.kv_heads * rows * desc.d_sel)
+
+
 def workspace_size(desc: Desc) -> int:
     n = ctypes.c_size_t(0)
     cd = desc.c()
     _check(load().lca_workspace_size(ctypes.byref(cd), ctypes.byref(n)))
     return int(n.value)
+
+
+def condensed_rows(desc: Desc):
+    """(m, k) of section 4.2's partition for this descriptor, from the library."""
+    m, k = ctypes.c_int32(0), ctypes.c_int32(0)
+    cd = desc.c()
+    _check(load().lca_condensed_rows(ctypes.byref(cd), ctypes.byref(m), ctypes.byref(k)))
+    return int(m.value), int(k.value)
 
 
 def cache_bytes(desc: Desc):
@@ -153,6 +204,11 @@ def cache_bytes(desc: Desc):
 
 def condense(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, anchor_idx, alpha_dbg, workspace, stream=None):
     cd = desc.c()
+    m, _ = condensed_rows(desc)
+    _fit_inputs(desc, Q, POOL, SEL)
+    _fit_reps(desc, pool_rep, sel_rep, m)
+    _fit(desc, anchor_idx, "anchor_idx", desc.B * desc.S * m, "i32")
+    _fit(desc, alpha_dbg, "alpha_dbg", desc.B * desc.S * m * desc.g, "f32", optional=True)
     _check(load().lca_condense(ctypes.byref(cd), _ptr(Q), _ptr(POOL), _ptr(SEL), _ptr(pool_rep), _ptr(sel_rep),
                                _ptr(anchor_idx), _ptr(alpha_dbg), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)),
                                _stream(stream)))
@@ -160,6 +216,10 @@ def condense(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, anchor_idx, alpha_dbg,
 
 def prefill_attn(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, O, lse, workspace, stream=None):
     cd = desc.c()
+    _fit_inputs(desc, Q, POOL, SEL)
+    _fit_reps(desc, pool_rep, sel_rep, condensed_rows(desc)[0])
+    _fit(desc, O, "O", desc.B * desc.L * desc.H * desc.d_pool)
+    _fit(desc, lse, "lse", desc.B * desc.L * desc.H, "f32", optional=True)
     _check(load().lca_prefill_attn(ctypes.byref(cd), _ptr(Q), _ptr(POOL), _ptr(SEL), _ptr(pool_rep), _ptr(sel_rep),
                                    _ptr(O), _ptr(lse), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)),
                                    _stream(stream)))
@@ -167,18 +227,39 @@ def prefill_attn(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, O, lse, workspace,
 
 def prefill_attn_up(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, W_up, O_up, lse, workspace, stream=None):
     cd = desc.c()
+    _fit_inputs(desc, Q, POOL, SEL)
+    _fit_reps(desc, pool_rep, sel_rep, condensed_rows(desc)[0])
+    _fit(desc, W_up, "W_up", desc.H * 128 * desc.d_pool)
+    _fit(desc, O_up, "O_up", desc.B * desc.L * desc.H * 128)
+    _fit(desc, lse, "lse", desc.B * desc.L * desc.H, "f32", optional=True)
     _check(load().lca_prefill_attn_up(ctypes.byref(cd), _ptr(Q), _ptr(POOL), _ptr(SEL), _ptr(pool_rep), _ptr(sel_rep), _ptr(W_up),
                                       _ptr(O_up), _ptr(lse), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
 
 
 def dense_attn(desc: Desc, Q, POOL, SEL, O, lse, workspace, stream=None):
     cd = desc.c()
+    _fit_inputs(desc, Q, POOL, SEL)
+    _fit(desc, O, "O", desc.B * desc.L * desc.H * desc.d_pool)
+    _fit(desc, lse, "lse", desc.B * desc.L * desc.H, "f32", optional=True)
     _check(load().dense_mla_attn(ctypes.byref(cd), _ptr(Q), _ptr(POOL), _ptr(SEL), _ptr(O), _ptr(lse), _ptr(workspace),
                                  ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
 
 
+def _fit_decode(desc: Desc, layout, q, pool_rep, sel_rep, pool_tail, sel_tail, O, rep_kind="elt", scales=None):
+    m, k = condensed_rows(desc)
+    m_cap, k_cap = (layout.m_cap, layout.k_cap) if layout is not None else (m, k)
+    _fit(desc, q, "q", desc.B * desc.H * desc.d_qk)
+    _fit(desc, pool_rep, "pool_rep", desc.B * desc.S * m_cap * desc.d_pool if m > 0 else 0, rep_kind)
+    _fit(desc, sel_rep, "sel_rep", desc.B * desc.S * m_cap * desc.d_sel if m > 0 else 0, rep_kind)
+    if rep_kind == "u8":
+        _fit(desc, scales, "scales", desc.B * desc.S * m_cap * 2 if m > 0 else 0, "f32")
+    _fit_tails(desc, pool_tail, sel_tail, k_cap)
+    _fit(desc, O, "O", desc.B * desc.H * desc.d_pool)
+
+
 def decode_attn(desc: Desc, q, pool_rep, sel_rep, pool_tail, sel_tail, O, workspace, stream=None):
     cd = desc.c()
+    _fit_decode(desc, None, q, pool_rep, sel_rep, pool_tail, sel_tail, O)
     _check(load().lca_decode_attn(ctypes.byref(cd), _ptr(q), _ptr(pool_rep), _ptr(sel_rep), _ptr(pool_tail),
                                   _ptr(sel_tail), _ptr(O), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)),
                                   _stream(stream)))
@@ -186,12 +267,17 @@ def decode_attn(desc: Desc, q, pool_rep, sel_rep, pool_tail, sel_tail, O, worksp
 
 def decode_attn_cached(desc: Desc, layout: CacheLayout, q, pool_rep, sel_rep, pool_tail, sel_tail, O, workspace, stream=None):
     cd, cl = desc.c(), layout.c()
+    _fit_decode(desc, layout, q, pool_rep, sel_rep, pool_tail, sel_tail, O)
     _check(load().lca_decode_attn_cached(ctypes.byref(cd), ctypes.byref(cl), _ptr(q), _ptr(pool_rep), _ptr(sel_rep), _ptr(pool_tail),
                                          _ptr(sel_tail), _ptr(O), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
 
 
 def cache_update(desc: Desc, layout: CacheLayout, q_recent, pool_tail, sel_tail, pool_rep, sel_rep, anchor_idx, workspace, stream=None):
     cd, cl = desc.c(), layout.c()
+    _fit(desc, q_recent, "q_recent", desc.B * (desc.n_q or desc.g) * desc.H * desc.d_qk)
+    _fit_tails(desc, pool_tail, sel_tail, layout.k_cap)
+    _fit_reps(desc, pool_rep, sel_rep, layout.m_cap)
+    _fit(desc, anchor_idx, "anchor_idx", desc.B * desc.S * layout.m_cap, "i32", optional=True)
     _check(load().lca_cache_update(ctypes.byref(cd), ctypes.byref(cl), _ptr(q_recent), _ptr(pool_tail), _ptr(sel_tail), _ptr(pool_rep),
                                    _ptr(sel_rep), _ptr(anchor_idx), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
 
@@ -199,6 +285,13 @@ def cache_update(desc: Desc, layout: CacheLayout, q_recent, pool_tail, sel_tail,
 def quantize_cache(desc: Desc, layout, pool_rep, sel_rep, pool_q8, sel_q8, scales, first_row=0, stream=None):
     cd = desc.c()
     cl = layout.c() if layout is not None else None
+    m, _ = condensed_rows(desc)
+    rows = layout.m_cap if layout is not None else m
+    if 0 <= first_row < m:          # (otherwise the library rejects first_row or has nothing to do, and reads nothing)
+        _fit_reps(desc, pool_rep, sel_rep, rows)
+        _fit(desc, pool_q8, "pool_q8", desc.B * desc.S * rows * desc.d_pool, "u8")
+        _fit(desc, sel_q8, "sel_q8", desc.B * desc.S * rows * desc.d_sel, "u8")
+        _fit(desc, scales, "scales", desc.B * desc.S * rows * 2, "f32")
     _check(load().lca_quantize_cache(ctypes.byref(cd), ctypes.byref(cl) if cl is not None else None, ctypes.c_int32(first_row), _ptr(pool_rep), _ptr(sel_rep),
                                      _ptr(pool_q8), _ptr(sel_q8), _ptr(scales), _stream(stream)))
 
@@ -206,6 +299,7 @@ def quantize_cache(desc: Desc, layout, pool_rep, sel_rep, pool_q8, sel_q8, scale
 def decode_attn_q8(desc: Desc, layout, q, pool_q8, sel_q8, scales, pool_tail, sel_tail, O, workspace, stream=None):
     cd = desc.c()
     cl = layout.c() if layout is not None else None
+    _fit_decode(desc, layout, q, pool_q8, sel_q8, pool_tail, sel_tail, O, rep_kind="u8", scales=scales)
     _check(load().lca_decode_attn_q8(ctypes.byref(cd), ctypes.byref(cl) if cl is not None else None, _ptr(q), _ptr(pool_q8), _ptr(sel_q8),
                                      _ptr(scales), _ptr(pool_tail), _ptr(sel_tail), _ptr(O), _ptr(workspace),
                                      ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
@@ -213,6 +307,10 @@ def decode_attn_q8(desc: Desc, layout, q, pool_q8, sel_q8, scales, pool_tail, se
 
 def deviation_stats(desc: Desc, POOL, SEL, pool_rep, sel_rep, stats, workspace, stream=None):
     cd = desc.c()
+    _fit(desc, POOL, "POOL", desc.B * desc.L * desc.kv_heads * desc.d_pool)
+    _fit(desc, SEL, "SEL", desc.B * desc.L * desc.kv_heads * desc.d_sel)
+    _fit_reps(desc, pool_rep, sel_rep, condensed_rows(desc)[0])
+    _fit(desc, stats, "stats", desc.B * desc.S * 6, "f32")
     _check(load().lca_deviation_stats(ctypes.byref(cd), _ptr(POOL), _ptr(SEL), _ptr(pool_rep), _ptr(sel_rep), _ptr(stats), _ptr(workspace),
                                       ctypes.c_size_t(_nbytes(workspace)), _stream(stream)))
 

@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu through the GPU runner)")
 
 
+def pytest_terminal_summary(terminalreporter):
+    from tests import helpers
+    for key in sorted(helpers.SEEN, key=str):
+        terminalreporter.write_line(f"[largest seen] {key}: {helpers.SEEN[key]:.3e}")
+
+
 @pytest.fixture(scope="session")
 def oracle():
     import oracle as o

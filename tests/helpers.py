@@ -15,7 +15,21 @@ from paper_2604_12452_amd import inputs
 # line with the 8x finer type; measured errors are around 5e-4).
 TOL = {"bf16": 1e-2, "f32": 1e-4, "f16": 2e-3}
 LSE_TOL = {"bf16": 1e-2, "f32": 1e-4, "f16": 1e-2}
+# End to end against an oracle whose cache is never rounded to the storage type.  The stored representative differs from
+# the float64 one by up to half a unit in the last place of every component (2^-9 relative in bf16, 2^-12 in fp16), which
+# reaches the output twice: as the value, and through the logits scale * <q, c_rep>, whose perturbation grows with the
+# scale (at scale 3 it moves probabilities by about one per cent in bf16).  Largest values measured over all cases:
+# bf16 1.76e-2 (the scale-3 cases; 7.8e-3 otherwise at the narrow widths), fp16 2.4e-3, fp32 5e-6.  Gated at twice TOL.
+E4_TOL = {"bf16": 2e-2, "f32": 1e-4, "f16": 4e-3}
 ANCHOR_MARGIN = 1e-3   # anchors must match bit-exactly where the oracle's top-two score gap exceeds this
+
+# Largest value seen of the end-to-end comparison against the oracle that never rounds its cache, per element type and
+# width class; conftest.py prints it at the end of a run.
+SEEN = {}
+
+
+def note(key, value):
+    SEEN[key] = max(SEEN.get(key, 0.0), float(value))
 
 
 def vec_rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
@@ -47,10 +61,20 @@ def check_condense(o, wl, run: GpuRun, Qf_tail, POOLf, SELf, tol=None):
         return ref, np.zeros((wl.B, wl.S, 0), dtype=bool)
     anchor = run.anchor.cpu().numpy()
     differ = anchor != ref["anchor"]
-    # bit-exact wherever the decision is not a near-tie; a near-tie may pick either of the top two
+    # bit-exact wherever the decision is not a near-tie ...
     assert not (differ & (ref["margin"] > ANCHOR_MARGIN)).any(), "anchor mismatch above the score margin"
+    # ... and on exact ties (equal scores in float64: equal rows, or a zero summary query), where the lowest index wins (Eq. 8)
+    assert not (differ & (ref["margin"] == 0.0)).any(), "an exact tie did not go to the lowest index"
     j = np.arange(od.m)[None, None, :]
     assert ((anchor >= j * wl.g) & (anchor < (j + 1) * wl.g)).all(), "anchor outside its group"
+    # a near-tie may pick another token only if its score is within the margin of the maximum: with alpha = softmax(s),
+    # s_max - s[gpu anchor] = ln(alpha_max / alpha[gpu anchor]), taken from the oracle's weights
+    if differ.any():
+        al = ref["alpha"]
+        a_gpu = np.take_along_axis(al, anchor.astype(np.int64), axis=-1)
+        a_max = np.take_along_axis(al, ref["anchor"].astype(np.int64), axis=-1)
+        gap = np.log(a_max[differ]) - np.log(a_gpu[differ])
+        assert (gap <= ANCHOR_MARGIN).all(), f"a GPU anchor scores {gap.max():.3e} below the group's maximum (allowed {ANCHOR_MARGIN})"
     # the selected component is copied, never recomputed: bit-exact rows of SEL at the GPU's anchors
     sel_gpu = from_dev(run.sel_rep, wl.dtype)
     for b in range(wl.B):
@@ -90,12 +114,12 @@ def check_prefill(o, wl, run: GpuRun, rows, Qf_rows, POOLf, SELf, ref_cond, diff
     O3 = o.lca_attn_rows(od, rows, Qf_rows, POOLf, SELf, pool3, sel3)
     e3 = vec_rel_err(O_gpu, O3)
     assert e3 <= tol, f"stage 3 (end to end) rel err {e3:.3e} > {tol}"
-    if wl.d_pool >= 128:
-        # Against an oracle that never rounds its cache the two 16-bit stores (cache, output; unit roundoff
-        # 2^-8 each) alone can reach 0.78 % of a component, so this looser comparison is gated at 2x the bar.
-        O4 = o.lca_attn_rows(od, rows, Qf_rows, POOLf, SELf, ref_cond["pool_rep"], sel3)
-        e4 = vec_rel_err(O_gpu, O4)
-        assert e4 <= 2 * tol, f"stage 3 against the unrounded fp64 cache: rel err {e4:.3e} > {2 * tol}"
+    # The same against an oracle that never rounds its cache (all-float64 end to end).
+    O4 = o.lca_attn_rows(od, rows, Qf_rows, POOLf, SELf, ref_cond["pool_rep"], sel3)
+    e4 = vec_rel_err(O_gpu, O4)
+    note(("e4", wl.dtype, "layer widths" if wl.d_pool >= 128 else "narrow", "scale > 1" if wl.scale > 1 else "scale <= 1"), e4)
+    print(f"  end to end against the unrounded float64 cache: rel err {e4:.3e}", flush=True)
+    assert e4 <= E4_TOL[wl.dtype], f"stage 3 against the unrounded fp64 cache: rel err {e4:.3e} > {E4_TOL[wl.dtype]}"
     return e2, e3
 
 

@@ -27,7 +27,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared()
-    assert set(names) == set(lca.EXPORTS) and len(names) == 13
+    assert set(names) == set(lca.EXPORTS) and len(names) == 14
     for n in names:
         assert hasattr(lib, n)
 
@@ -47,6 +47,62 @@ def test_workspace_and_cache_bytes_are_host_only(lib):
     assert lca.cache_bytes(gqa) == (268435456, 20709376)
     assert lca.workspace_size(_desc(dtype=lca.F16)) == lca.workspace_size(_desc())      # both 16-bit types are accepted
     assert lca.workspace_size(lca.Desc(B=32, L=65537, H=32, S=8, d_pool=128, d_sel=128, g=16, w=1024, mode=lca.MODE_GQA)) > 0
+
+
+def test_condensed_rows_follow_the_partition_of_section_4_2(lib):
+    """m = floor((L - w) / g) groups, k = w + (L - w) mod g raw tokens, every token accounted for (m g + k = L)."""
+    for L, w, g in [(131072, 1024, 16), (131072, 1024, 32), (1024, 128, 16), (1000, 100, 16), (77, 9, 4), (100, 200, 16), (40, 40, 4), (5, 0, 8),
+                    (65537, 1024, 16)]:
+        d = _desc(L=L, w=w, g=g)
+        m, k = lca.condensed_rows(d)
+        assert (m, k) == (d.m, d.k)
+        assert m * g + k == L and m >= 0
+        if L > w:
+            assert k == w + (L - w) % g and m == (L - w - (L - w) % g) // g
+        else:
+            assert (m, k) == (0, L)
+    assert lca.condensed_rows(_desc(L=65537)) == (4032, 1025)
+    cd = _desc().c()
+    assert lib.lca_condensed_rows(ctypes.byref(cd), None, None) == lca.ERR_INVALID_ARG
+
+
+def test_binding_rejects_tensors_that_do_not_fit_the_descriptor(lib):
+    """The binding compares every tensor with the size and element type the header documents before the library is
+    called: a mismatch raises ValueError and nothing is launched (CPU tensors here; a tensor of the right size and type
+    that is not on the device is rejected as well)."""
+    import torch
+    d = lca.Desc(B=1, L=64, H=2, S=1, d_pool=512, d_sel=64, g=4, w=8)
+    m = d.m
+    bf = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16)
+    Q, POOL, SEL = bf(1, 64, 2, 576), bf(1, 64, 512), bf(1, 64, 64)
+    pr, sr, an = bf(1, 1, m, 512), bf(1, 1, m, 64), torch.zeros((1, 1, m), dtype=torch.int32)
+    O, ws = bf(1, 64, 2, 512), torch.zeros(1 << 16, dtype=torch.uint8)
+    bad = [
+        ("Q holds", lambda: lca.condense(d, Q[:, :63].contiguous(), POOL, SEL, pr, sr, an, None, ws)),
+        ("POOL has dtype", lambda: lca.condense(d, Q, POOL.float(), SEL, pr, sr, an, None, ws)),
+        ("SEL holds", lambda: lca.condense(d, Q, POOL, SEL[:, :, :32].contiguous(), pr, sr, an, None, ws)),
+        ("pool_rep holds", lambda: lca.condense(d, Q, POOL, SEL, pr[:, :, :m - 1].contiguous(), sr, an, None, ws)),
+        ("anchor_idx has dtype", lambda: lca.condense(d, Q, POOL, SEL, pr, sr, an.long(), None, ws)),
+        ("alpha_dbg holds", lambda: lca.condense(d, Q, POOL, SEL, pr, sr, an, torch.zeros(m * 4 - 1), ws)),
+        ("O holds", lambda: lca.prefill_attn(d, Q, POOL, SEL, pr, sr, O[:, :, :1].contiguous(), None, ws)),
+        ("lse has dtype", lambda: lca.prefill_attn(d, Q, POOL, SEL, pr, sr, O, torch.zeros((1, 64, 2), dtype=torch.float64), ws)),
+        ("O is required", lambda: lca.dense_attn(d, Q, POOL, SEL, None, None, ws)),
+        ("sel_rep holds", lambda: lca.prefill_attn(d, Q, POOL, SEL, pr, sr[:, :, 1:].contiguous(), O, None, ws)),
+        ("pool_tail holds", lambda: lca.decode_attn(lca.Desc(B=1, L=64, H=16, S=1, d_pool=512, d_sel=64, g=4, w=8), bf(1, 16, 576), pr, sr,
+                                                    bf(1, 1, d.k - 1, 512), bf(1, 1, d.k, 64), bf(1, 16, 512), ws)),
+        ("pool_rep holds", lambda: lca.decode_attn_cached(lca.Desc(B=1, L=64, H=16, S=1, d_pool=512, d_sel=64, g=4, w=8),
+                                                          lca.CacheLayout(m_cap=m + 4, k_cap=d.k + 4), bf(1, 16, 576), pr, sr,
+                                                          bf(1, 1, d.k + 4, 512), bf(1, 1, d.k + 4, 64), bf(1, 16, 512), ws)),
+        ("q_recent holds", lambda: lca.cache_update(d, lca.CacheLayout(m_cap=m, k_cap=12), bf(1, 3, 2, 576), bf(1, 1, 12, 512), bf(1, 1, 12, 64),
+                                                    pr, sr, an, ws)),
+        ("pool_q8 has dtype", lambda: lca.quantize_cache(d, None, pr, sr, pr, sr, torch.zeros((1, 1, m, 2)))),
+        ("stats holds", lambda: lca.deviation_stats(d, POOL, SEL, pr, sr, torch.zeros(5), ws)),
+        ("is not a device tensor", lambda: lca.condense(d, Q, POOL, SEL, pr, sr, an, None, ws)),
+    ]
+    for needle, call in bad:
+        with pytest.raises(ValueError) as e:
+            call()
+        assert needle in str(e.value), (needle, str(e.value))
 
 
 @pytest.mark.parametrize("kw", [dict(B=0), dict(L=0), dict(H=15, S=2), dict(g=0), dict(g=65), dict(w=-1), dict(n_q=-1),

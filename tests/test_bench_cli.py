@@ -33,6 +33,6 @@ def test_pair_count_closed_forms():
     assert abs(bench.pair_count(wl.L, wl.w, wl.g) - 663e6) < 1e6
     flops = 2.0 * (wl.d_qk + wl.d_v) * wl.B * wl.H * bench.pair_count(wl.L, wl.w, wl.g)
     assert abs(flops - 23.09e12) < 0.01e12
-    assert abs(bench.condense_bytes(wl) - 159.5e6) < 0.3e6
+    assert abs(bench.condense_bytes(wl, 8128) - 159.5e6) < 0.3e6      # m = (131072 - 1024) / 16 groups
     rows = np.array([0, 100, 256], dtype=np.int64)
     assert bench.pair_count(L, w, g, rows) == sum(max(0, (t + 1 - w) // g) + (t + 1 - max(0, (t + 1 - w) // g) * g) for t in rows)

@@ -84,7 +84,12 @@ def _update_and_check(oracle, cache, L, q_recent_store, m_before):
     anchor = cache.anchor[:, :, m - 1].cpu().numpy()
     differ = anchor - (m - 1) * wl.g != ref["anchor"]
     assert not (differ & (ref["margin"] > hp.ANCHOR_MARGIN)).any(), "anchor mismatch above the score margin"
+    assert not (differ & (ref["margin"] == 0.0)).any(), "an exact tie did not go to the lowest index"
     assert ((anchor >= (m - 1) * wl.g) & (anchor < m * wl.g)).all()
+    if differ.any():      # a near-tie may take another token only if it scores within the margin of the maximum
+        a_gpu = np.take_along_axis(ref["alpha"], (anchor - (m - 1) * wl.g)[..., None].astype(np.int64), axis=-1)[..., 0]
+        gap = np.log(ref["alpha"].max(axis=-1)[differ]) - np.log(a_gpu[differ])
+        assert (gap <= hp.ANCHOR_MARGIN).all(), f"a GPU anchor scores {gap.max():.3e} below the maximum"
     for b in range(wl.B):
         for s in range(wl.S):                                      # the selected component is a bit-exact copy of the anchor's row
             p = 0 if wl.mode == inputs.MODE_MLA else s
@@ -141,6 +146,39 @@ def test_cache_update_matches_oracle(oracle, mode, d_pool, d_sel, H, S, dtype, g
     q_recent = _storage(rng, (B, g, H, wl.d_qk), dtype, sigma=2.0)
     err = _update_and_check(oracle, cache, L, q_recent, m_before)
     print(f"  pooled err {err:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("mode,d_pool,d_sel,H,S,dtype", SHAPES)
+@pytest.mark.parametrize("g", [4, 16, 32])
+def test_cache_update_exact_tie_takes_the_lowest_index(oracle, mode, d_pool, d_sel, H, S, dtype, g):
+    """The top-scoring token among the g oldest ring rows (for set 0) is copied over another of them: two equal rows hold the
+    largest score exactly, and the update must name the older one (Eq. 8, lowest index on ties); the ring wraps inside the g rows."""
+    B, w = 3, 20
+    k_cap = w + g + 3
+    k_start = k_cap - g // 2
+    L = w + 2 * g
+    wl = inputs.Workload("update_tie", B=B, L=L, H=H, S=S, d_pool=d_pool, d_sel=d_sel, g=g, w=w, dtype=dtype, mode=mode, seed=0,
+                         scale=1.0 / np.sqrt(d_pool + d_sel if mode == inputs.MODE_MLA else d_sel))
+    print(f"[case] {wl}", flush=True)
+    rng = np.random.default_rng(2000 + g)
+    cache = Cache(wl, m_cap=3, k_cap=k_cap, k_start=k_start, rng=rng)
+    cache.push(w + g)
+    q_recent = _storage(rng, (B, g, H, wl.d_qk), dtype, sigma=2.0)
+    od = hp.oracle_desc(oracle, wl)
+    pool_old, sel_old = cache.tail_rows(0, g)
+    first = oracle.cache_update(od, inputs.to_f64(q_recent, dtype), pool_old, sel_old)
+    expect = np.zeros(B, dtype=np.int64)
+    for b in range(B):
+        top = int(first["anchor"][b, 0])
+        other = (top + 1 + b) % g
+        for T in (cache.pool_tail, cache.sel_tail):
+            T[b, :, (k_start + other) % k_cap] = T[b, :, (k_start + top) % k_cap]
+        expect[b] = min(top, other)
+    pool_old, sel_old = cache.tail_rows(0, g)
+    ref = oracle.cache_update(od, inputs.to_f64(q_recent, dtype), pool_old, sel_old)
+    assert (ref["margin"][:, 0] == 0.0).all() and np.array_equal(ref["anchor"][:, 0], expect)
+    _update_and_check(oracle, cache, L, q_recent, 1)
+    assert np.array_equal(cache.anchor[:, 0, 1].cpu().numpy() - g, expect)
 
 
 @pytest.mark.parametrize("mode,d_pool,d_sel,H,S,dtype", SHAPES)

@@ -105,7 +105,7 @@ def test_cfg5_gqa_64k_prefill_and_decode(oracle):
     ws = lca.alloc_workspace(desc)
     pool_rep, sel_rep, anchor, _ = lca.alloc_condensed(desc)
     lca.condense(desc, Qd, Vd, Kd, pool_rep, sel_rep, anchor, None, ws)
-    m, k, g = wd.m, wd.k, wd.g
+    m, k, g = desc.m, desc.k, wd.g
     assert (m, k) == (4032, 1025)
     pool_tail = Vd[:, m * g:].permute(0, 2, 1, 3).contiguous()
     sel_tail = Kd[:, m * g:].permute(0, 2, 1, 3).contiguous()

@@ -19,7 +19,7 @@ def test_prefill_and_decode_replay_in_a_graph(mode, d_pool, d_sel, H, S):
     Q, POOL, SEL = inputs.gen_all(wl)
     run = hp.GpuRun(wl, Q, POOL, SEL)
     d = run.desc
-    m, g = wl.m, wl.g
+    m, g = d.m, wl.g
     pool_rep, sel_rep, anchor, _ = lca.alloc_condensed(d)
     O = torch.empty((wl.B, wl.L, wl.H, wl.d_pool), dtype=torch.bfloat16, device="cuda")
     Od = torch.empty((wl.B, wl.H, wl.d_pool), dtype=torch.bfloat16, device="cuda")

@@ -50,7 +50,7 @@ def test_generic_kernels_small_shapes(oracle, dtype, mode, L, g, w, H, S):
 @pytest.mark.parametrize("L,w,g", [(40, 64, 4), (10, 8, 4), (1, 1, 1), (5, 0, 8)])
 def test_no_groups_falls_back_to_dense(oracle, L, w, g):
     wl = _wl("short", L=L, w=w, g=min(g, 8), n_q=1)
-    assert wl.m == 0
+    assert hp.lca_desc(wl).m == 0
     run = _full_parity(oracle, wl)
     assert np.array_equal(hp.from_dev(run.O, wl.dtype), hp.from_dev(run.O_dense, wl.dtype))
 
@@ -220,7 +220,7 @@ def test_decode_step(oracle, mode, d_pool, d_sel, H, S, dtype, L, g, w):
     Q, POOL, SEL = inputs.gen_all(wl)
     run = hp.GpuRun(wl, Q, POOL, SEL).condense(alpha=False)
     # the cache after L tokens, the newest of which is the one being decoded
-    m, k = wl.m, wl.k
+    m, k = run.desc.m, run.desc.k
     if mode == inputs.MODE_MLA:
         pool_tail = run.POOL[:, None, m * g:].contiguous()
         sel_tail = run.SEL[:, None, m * g:].contiguous()
@@ -439,3 +439,149 @@ def test_mla_prefill_with_fused_up_projection(oracle, dtype, L, g, w, H, S, B):
     print(f"  fused up-projection: err {err:.2e} against the oracle, {err2:.2e} against the library's latent output projected in float64", flush=True)
     assert err <= hp.TOL[dtype] and err2 <= hp.TOL[dtype]
     assert np.abs(lse.cpu().numpy().astype(np.float64) - lse_ref).max() <= hp.LSE_TOL[dtype]
+
+
+# ---- the 1/sqrt(d) factor of Eq. 6 and Eq. 10: desc.scale through every kernel ---------------------------------
+_SCALE_KERNELS = {
+    # name: (mode, d_pool, d_sel, dtype, H, S)
+    "mla_mfma_bf16": (inputs.MODE_MLA, 512, 64, "bf16", 4, 2),
+    "mla_mfma_f16": (inputs.MODE_MLA, 512, 64, "f16", 2, 1),
+    "gqa_mfma_bf16": (inputs.MODE_GQA, 128, 128, "bf16", 8, 2),
+    "gqa_mfma_f16": (inputs.MODE_GQA, 128, 128, "f16", 4, 2),
+    "cfg1_widths_f32": (inputs.MODE_MLA, 128, 32, "f32", 4, 1),
+    "generic_f32_mla": (inputs.MODE_MLA, 24, 16, "f32", 4, 2),
+    "generic_bf16_gqa": (inputs.MODE_GQA, 24, 16, "bf16", 4, 2),
+}
+
+
+@pytest.mark.parametrize("which", ["rsqrt_d", "odd", "large"])
+@pytest.mark.parametrize("kernel", sorted(_SCALE_KERNELS))
+def test_scale_enters_scores_and_logits(oracle, kernel, which):
+    """desc.scale != 1 through condensation (Eq. 6: s_i = scale <qbar, k_i>), LCA prefill and the dense baseline (Eq. 10,
+    Eq. 5: logits scale <q, k>), at both matrix-core widths in both 16-bit types and in the general kernels.  'rsqrt_d'
+    is the paper's 1/sqrt(d) with unit-variance queries, 'odd' is 0.37 with the benchmark's query distribution, 'large'
+    is 3.0 (sharper softmax than any benchmark input).  A scale applied twice, or left out of either place, moves the
+    weights and the outputs far beyond the tolerance."""
+    mode, d_pool, d_sel, dtype, H, S = _SCALE_KERNELS[kernel]
+    d_qk = d_pool + d_sel if mode == inputs.MODE_MLA else d_sel
+    scale, qv = {"rsqrt_d": (1.0 / math.sqrt(d_qk), 1), "odd": (0.37, 0), "large": (3.0, 0)}[which]
+    wl = inputs.Workload("scale", B=2, L=300, H=H, S=S, d_pool=d_pool, d_sel=d_sel, g=8, w=40, dtype=dtype, mode=mode, seed=61,
+                         q_var_dim=qv, scale=scale, theta=500000.0 if mode == inputs.MODE_GQA else 10000.0)
+    run = _full_parity(oracle, wl)
+    assert abs(run.desc.scale - scale) < 1e-7
+
+
+@pytest.mark.parametrize("scale", [0.0, -0.5])
+@pytest.mark.parametrize("mode,d_pool,d_sel,dtype", [(inputs.MODE_MLA, 512, 64, "bf16"), (inputs.MODE_GQA, 128, 128, "bf16"),
+                                                      (inputs.MODE_MLA, 512, 64, "f16"), (inputs.MODE_MLA, 24, 16, "f32")])
+def test_zero_and_negative_scale(oracle, scale, mode, d_pool, d_sel, dtype):
+    """A zero scale makes every weight uniform (plain averages, lowest index as anchor) and a negative one turns the order of the
+    scores around; the matrix-core kernels only take positive scales, so these descriptors run the general attention kernel."""
+    wl = inputs.Workload("scale_le0", B=1, L=200, H=4, S=2, d_pool=d_pool, d_sel=d_sel, g=8, w=24, dtype=dtype, mode=mode, seed=62,
+                         scale=scale, theta=500000.0 if mode == inputs.MODE_GQA else 10000.0)
+    run = _full_parity(oracle, wl)
+    if scale == 0.0:
+        m = run.desc.m
+        assert np.array_equal(run.anchor.cpu().numpy(), np.broadcast_to(np.arange(m) * wl.g, (wl.B, wl.S, m)))
+
+
+# ---- exact ties: equal rows inside a group (Eq. 8: the lowest index wins) ---------------------------------------------
+@pytest.mark.parametrize("g", [2, 3, 4, 8, 16, 32, 64])
+@pytest.mark.parametrize("mode,d_pool,d_sel,dtype,S", [
+    (inputs.MODE_MLA, 512, 64, "bf16", 1), (inputs.MODE_MLA, 512, 64, "bf16", 4), (inputs.MODE_MLA, 512, 64, "f16", 2),
+    (inputs.MODE_GQA, 128, 128, "bf16", 2), (inputs.MODE_GQA, 128, 128, "f16", 1), (inputs.MODE_MLA, 128, 32, "f32", 2),
+    (inputs.MODE_MLA, 24, 16, "f32", 2), (inputs.MODE_GQA, 24, 16, "bf16", 2)])
+def test_exact_ties_take_the_lowest_index(oracle, g, mode, d_pool, d_sel, dtype, S):
+    """In two groups out of three the top-scoring token (of set / KV head 0) is copied over another token of its group, earlier or
+    later, so that two tokens hold the group's largest score exactly.  The oracle's margin is then exactly zero there and
+    both sides must name the lower of the two positions."""
+    wl = inputs.Workload("ties", B=2, L=40 + 12 * g, H=4, S=S, d_pool=d_pool, d_sel=d_sel, g=g, w=40, dtype=dtype, mode=mode, seed=300 + g,
+                         theta=500000.0 if mode == inputs.MODE_GQA else 10000.0)
+    print(f"[case] {wl}", flush=True)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    Qf, POOLf, SELf = (inputs.to_f64(x, wl.dtype) for x in (Q, POOL, SEL))
+    od = hp.oracle_desc(oracle, wl)
+    qbar = oracle.summary_query(od, Qf[:, wl.L - wl.nq:])
+    first = oracle.condense(od, qbar, POOLf, SELf)
+    planted = np.zeros((wl.B, od.m), dtype=bool)
+    expect = np.zeros((wl.B, od.m), dtype=np.int64)
+    for b in range(wl.B):
+        for j in range(od.m):
+            if j % 3 == 2:
+                continue
+            top = int(first["anchor"][b, 0, j])
+            r = top - j * g
+            other = j * g + ((r + 1 + (j * 7) % (g - 1)) % g)          # another position of the group, before or after the top one
+            assert other != top
+            for X in (POOL, SEL):
+                X[b, other] = X[b, top]                                 # MLA: the token's rows; GQA: all KV heads' rows of the token
+            planted[b, j], expect[b, j] = True, min(top, other)
+    POOLf, SELf = inputs.to_f64(POOL, wl.dtype), inputs.to_f64(SEL, wl.dtype)
+    ref = oracle.condense(od, qbar, POOLf, SELf)
+    assert (ref["margin"][:, 0][planted] == 0.0).all() and np.array_equal(ref["anchor"][:, 0][planted], expect[planted])
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense()
+    ref2, differ = hp.check_condense(oracle, wl, run, Qf[:, wl.L - wl.nq:], POOLf, SELf)
+    got = run.anchor.cpu().numpy()
+    assert np.array_equal(got[:, 0][planted], expect[planted]), "a tie between equal rows did not go to the lowest index"
+    ties = ref2["margin"] == 0.0
+    assert np.array_equal(got[ties], ref2["anchor"][ties])
+    print(f"  {int(planted.sum())} planted ties, {int(ties.sum())} exact ties over all sets", flush=True)
+
+
+# ---- the number of summary queries (Table 8: 8, 16, 32 at g = 16) ----------------------------------------------------
+@pytest.mark.parametrize("n_q", [1, 8, 32, 50])
+@pytest.mark.parametrize("mode,d_pool,d_sel,dtype,H,S", [
+    (inputs.MODE_MLA, 512, 64, "bf16", 16, 1), (inputs.MODE_MLA, 512, 64, "f16", 4, 2), (inputs.MODE_GQA, 128, 128, "bf16", 8, 2),
+    (inputs.MODE_MLA, 128, 32, "f32", 4, 1), (inputs.MODE_GQA, 24, 16, "bf16", 4, 4)])
+def test_number_of_summary_queries_differs_from_group_size(oracle, n_q, mode, d_pool, d_sel, dtype, H, S):
+    """n_q != g with groups present: the summary query averages the last n_q positions whatever the group size is, and
+    everything downstream (weights, anchors, representatives, attention over them) follows it."""
+    wl = inputs.Workload("n_q", B=2, L=360, H=H, S=S, d_pool=d_pool, d_sel=d_sel, g=16, w=70, n_q=n_q, dtype=dtype, mode=mode, seed=400 + n_q,
+                         theta=500000.0 if mode == inputs.MODE_GQA else 10000.0)
+    _full_parity(oracle, wl, dense=False)
+
+
+# ---- representatives counted g times (the normaliser of appendix A.2): rep_logit_bias = ln g -----------------------------
+@pytest.mark.parametrize("mode,d_pool,d_sel,dtype,H,S,g", [
+    (inputs.MODE_GQA, 128, 128, "bf16", 8, 2, 16), (inputs.MODE_GQA, 128, 128, "f16", 4, 1, 8), (inputs.MODE_GQA, 128, 128, "bf16", 6, 2, 4),
+    (inputs.MODE_MLA, 512, 64, "f16", 2, 1, 16), (inputs.MODE_MLA, 24, 16, "f32", 4, 2, 4), (inputs.MODE_GQA, 24, 16, "bf16", 4, 2, 8)])
+def test_multiplicity_bias_all_kernels(oracle, mode, d_pool, d_sel, dtype, H, S, g):
+    wl = inputs.Workload("bias", B=2, L=400, H=H, S=S, d_pool=d_pool, d_sel=d_sel, g=g, w=32, dtype=dtype, mode=mode, seed=500 + g,
+                         theta=500000.0 if mode == inputs.MODE_GQA else 10000.0)
+    _full_parity(oracle, wl, bias=math.log(float(g)), dense=False)
+
+
+@pytest.mark.parametrize("mode,d_pool,d_sel,H,S,dtype", [
+    (inputs.MODE_GQA, 128, 128, 8, 2, "bf16"), (inputs.MODE_MLA, 512, 64, 16, 1, "bf16"), (inputs.MODE_MLA, 512, 64, 8, 8, "f16"),
+    (inputs.MODE_MLA, 128, 32, 4, 1, "f32")])
+def test_decode_step_with_multiplicity_bias_and_scale(oracle, mode, d_pool, d_sel, H, S, dtype):
+    """One decode step with rep_logit_bias = ln g and a scale other than 1 against the oracle's decode step (which equals
+    the last prefill row by its own pin)."""
+    import torch
+    from paper_2604_12452_amd import lca
+    B, L, g, w = 3, 500, 16, 60
+    wl = inputs.Workload("decode_bias", B=B, L=L, H=H, S=S, d_pool=d_pool, d_sel=d_sel, g=g, w=w, dtype=dtype, mode=mode, seed=77, scale=0.6,
+                         theta=500000.0 if mode == inputs.MODE_GQA else 10000.0)
+    print(f"[case] {wl}", flush=True)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    bias = math.log(float(g))
+    run = hp.GpuRun(wl, Q, POOL, SEL, rep_logit_bias=bias).condense(alpha=False)
+    m = run.desc.m
+    if mode == inputs.MODE_MLA:
+        pool_tail, sel_tail = run.POOL[:, None, m * g:].contiguous(), run.SEL[:, None, m * g:].contiguous()
+    else:
+        pool_tail, sel_tail = run.POOL[:, m * g:].permute(0, 2, 1, 3).contiguous(), run.SEL[:, m * g:].permute(0, 2, 1, 3).contiguous()
+    q = run.Q[:, L - 1].contiguous()
+    O = torch.full((B, H, d_pool), float("nan"), dtype=lca.torch_dtype(run.desc), device="cuda")
+    lca.decode_attn(run.desc, q, run.pool_rep, run.sel_rep, pool_tail, sel_tail, O, run.ws)
+    torch.cuda.synchronize()
+    od = hp.oracle_desc(oracle, wl, rep_logit_bias=bias)
+    ref = oracle.decode_attn(od, hp.from_dev(q, dtype), hp.from_dev(run.pool_rep, dtype), hp.from_dev(run.sel_rep, dtype),
+                             hp.from_dev(pool_tail, dtype), hp.from_dev(sel_tail, dtype))
+    nobias = oracle.decode_attn(hp.oracle_desc(oracle, wl), hp.from_dev(q, dtype), hp.from_dev(run.pool_rep, dtype),
+                                hp.from_dev(run.sel_rep, dtype), hp.from_dev(pool_tail, dtype), hp.from_dev(sel_tail, dtype))
+    got = hp.from_dev(O, dtype)
+    err = hp.vec_rel_err(got, ref)
+    print(f"  decode err {err:.2e} (the same step without the bias differs by {hp.vec_rel_err(nobias, ref):.2e})", flush=True)
+    assert err <= hp.TOL[dtype]
+    assert hp.vec_rel_err(nobias, ref) > 10 * hp.TOL[dtype], "the bias must matter on this input, or the case proves nothing"
