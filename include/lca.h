@@ -115,6 +115,22 @@ lca_status lca_condense(const lca_desc *desc, const void *Q, const void *POOL, c
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * lca_condense for callers that can neither allocate device memory nor hand over a workspace: code under HIP graph
+ * capture, serving loops with a fixed memory plan, harnesses that forbid hipMalloc.  Same inputs, outputs and results
+ * as lca_condense; the summary queries (B * S * d_qk floats, the only scratch memory that call uses) live in a device
+ * array built into the library instead of the caller's workspace.  The call allocates nothing and frees nothing.
+ *   - Limit: B * S * d_qk * 4 bytes (rounded up to 256) must not exceed 256 KiB, e.g. B * S <= 113 at d_qk = 576;
+ *     beyond it the call returns LCA_ERR_WORKSPACE and launches nothing.
+ *   - Every GPU the library runs on holds its own copy of the array for the life of the process; its address on the
+ *     current device is looked up on the first call made with that device current (make that call outside a capture).
+ *   - All calls on one GPU share the array, which keeps the previous call's contents; nothing in it has to start at
+ *     zero.  Two calls whose kernels overlap on one GPU (different streams, no ordering between them) race on it:
+ *     order them, or use lca_condense with separate workspaces.
+ */
+lca_status lca_condense_noalloc(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL,
+                                void *pool_rep, void *sel_rep, int32_t *anchor_idx, float *alpha_dbg, void *stream);
+
+/*
  * Prefill attention over the condensed context (section 4.3, Eq. 10; Algorithm 1, last steps;
  * appendix A.2 notation for a query at position t).  Row t of head h (set s) attends
  *   representatives j < m_t,  m_t = max(0, floor((t + 1 - w) / g)),  and raw tokens m_t*g <= i <= t,

@@ -3,6 +3,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "lca_internal.h"
 
@@ -104,6 +105,32 @@ lca_status run_attn(const lca::AttnArgs &a, hipStream_t st, const char *what)
     return hip_status(lca::launch_attn_simple(a, st), what);
 }
 
+// ---- lca_condense_noalloc: the summary query lives in a device array of the library's own ----
+// One copy of the array exists on every GPU the library runs on, at an address of that GPU's own; in host code the
+// array's name is only a handle for hipGetSymbolAddress, never a pointer to pass on.
+constexpr size_t STATIC_SCRATCH_BYTES = 256 * 1024;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up once per device).
+lca_status static_scratch(void **out)
+{
+    int dev = -1;
+    LCA_TRY(hip_status(hipGetDevice(&dev), "hipGetDevice"));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(LCA_ERR_UNSUPPORTED, "device ordinal %d is beyond the %d this library keeps scratch addresses for", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        LCA_TRY(hip_status(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)"));
+        if (p == nullptr) return fail(LCA_ERR_HIP, "hipGetSymbolAddress(scratch) returned a NULL address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LCA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -157,6 +184,30 @@ lca_status lca_condense(const lca_desc *desc, const void *Q, const void *POOL, c
     a.d = d; a.Q = Q; a.POOL = POOL; a.SEL = SEL; a.pool_rep = pool_rep; a.sel_rep = sel_rep;
     a.anchor = anchor_idx; a.alpha_dbg = alpha_dbg; a.qbar = static_cast<float *>(workspace);
     return hip_status(lca::launch_condense(a, static_cast<hipStream_t>(stream)), "lca_condense");
+}
+
+lca_status lca_condense_noalloc(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL, void *pool_rep, void *sel_rep,
+                                int32_t *anchor_idx, float *alpha_dbg, void *stream)
+{
+    lca::Dims d;
+    LCA_TRY(make_dims(desc, d));
+    if (d.n_q > d.L) return fail(LCA_ERR_INVALID_ARG, "n_q (%d) must be in [1, L]", d.n_q);
+    LCA_TRY(check_ptr(Q, "Q"));
+    LCA_TRY(check_ptr(POOL, "POOL"));
+    LCA_TRY(check_ptr(SEL, "SEL"));
+    LCA_TRY(check_ptr(pool_rep, "pool_rep", d.m > 0));
+    LCA_TRY(check_ptr(sel_rep, "sel_rep", d.m > 0));
+    if (d.m > 0 && anchor_idx == nullptr) return fail(LCA_ERR_INVALID_ARG, "anchor_idx is NULL");
+    if (qbar_bytes(d) > STATIC_SCRATCH_BYTES)
+        return fail(LCA_ERR_WORKSPACE, "lca_condense_noalloc: the summary queries of this descriptor need %zu bytes (B * S * d_qk floats), the "
+                                       "built-in scratch holds %zu; use lca_condense with a workspace of the caller's", qbar_bytes(d), STATIC_SCRATCH_BYTES);
+    void *qbar = nullptr;
+    LCA_TRY(static_scratch(&qbar));
+    lca::CondenseArgs a;
+    a.d = d; a.Q = Q; a.POOL = POOL; a.SEL = SEL; a.pool_rep = pool_rep; a.sel_rep = sel_rep;
+    a.anchor = anchor_idx; a.alpha_dbg = alpha_dbg; a.qbar = static_cast<float *>(qbar);
+    // (nothing in the scratch has to start at zero: the first kernel writes every summary query before the second reads it)
+    return hip_status(lca::launch_condense(a, static_cast<hipStream_t>(stream)), "lca_condense_noalloc");
 }
 
 lca_status lca_prefill_attn(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL, const void *pool_rep,

@@ -19,7 +19,7 @@ MODE_MLA, MODE_GQA = 0, 1
 BF16, F32, F16 = 0, 1, 2
 REDUCE_DEFAULT, REDUCE_WEIGHTED, REDUCE_MEAN, REDUCE_MAXSEL, REDUCE_MAXPOOL = range(5)
 
-EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condensed_rows", "lca_condense", "lca_prefill_attn", "dense_mla_attn",
+EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condensed_rows", "lca_condense", "lca_condense_noalloc", "lca_prefill_attn", "dense_mla_attn",
            "lca_decode_attn", "lca_decode_attn_cached", "lca_cache_update", "lca_deviation_stats", "lca_quantize_cache",
            "lca_decode_attn_q8", "lca_prefill_attn_up", "lca_last_error")
 
@@ -212,6 +212,17 @@ def condense(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, anchor_idx, alpha_dbg,
     _check(load().lca_condense(ctypes.byref(cd), _ptr(Q), _ptr(POOL), _ptr(SEL), _ptr(pool_rep), _ptr(sel_rep),
                                _ptr(anchor_idx), _ptr(alpha_dbg), _ptr(workspace), ctypes.c_size_t(_nbytes(workspace)),
                                _stream(stream)))
+
+
+def condense_noalloc(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, anchor_idx, alpha_dbg, stream=None):
+    cd = desc.c()
+    m, _ = condensed_rows(desc)
+    _fit_inputs(desc, Q, POOL, SEL)
+    _fit_reps(desc, pool_rep, sel_rep, m)
+    _fit(desc, anchor_idx, "anchor_idx", desc.B * desc.S * m, "i32")
+    _fit(desc, alpha_dbg, "alpha_dbg", desc.B * desc.S * m * desc.g, "f32", optional=True)
+    _check(load().lca_condense_noalloc(ctypes.byref(cd), _ptr(Q), _ptr(POOL), _ptr(SEL), _ptr(pool_rep), _ptr(sel_rep),
+                                       _ptr(anchor_idx), _ptr(alpha_dbg), _stream(stream)))
 
 
 def prefill_attn(desc: Desc, Q, POOL, SEL, pool_rep, sel_rep, O, lse, workspace, stream=None):

@@ -27,7 +27,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared()
-    assert set(names) == set(lca.EXPORTS) and len(names) == 14
+    assert set(names) == set(lca.EXPORTS) and len(names) == 15
     for n in names:
         assert hasattr(lib, n)
 

@@ -1,0 +1,101 @@
+"""lca_condense_noalloc (the entry point for callers that cannot allocate: its summary queries live in a device array
+built into the library) against lca_condense, through the C ABI: identical bits on two calls in a row, the second on a
+smaller input, and a clear error beyond the built-in scratch's size."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from paper_2604_12452_amd import inputs
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+
+def _both(wl):
+    """(outputs of lca_condense, outputs of lca_condense_noalloc) on the same device inputs, called through ctypes."""
+    import torch
+    from paper_2604_12452_amd import lca
+    lib = lca.load()
+    print(f"[case] {wl}", flush=True)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    run = hp.GpuRun(wl, Q, POOL, SEL)
+    d = run.desc
+    cd = d.c()
+    vp = ctypes.c_void_p
+    st = vp(torch.cuda.current_stream().cuda_stream)
+    outs = []
+    for which in ("lca_condense", "lca_condense_noalloc"):
+        pool_rep, sel_rep, anchor, alpha = lca.alloc_condensed(d, alpha=True)
+        for t in (pool_rep, sel_rep, alpha):
+            t.fill_(float("nan"))
+        anchor.fill_(-1)
+        torch.cuda.synchronize()
+        common = (ctypes.byref(cd), vp(run.Q.data_ptr()), vp(run.POOL.data_ptr()), vp(run.SEL.data_ptr()), vp(pool_rep.data_ptr()),
+                  vp(sel_rep.data_ptr()), vp(anchor.data_ptr()), vp(alpha.data_ptr()))
+        if which == "lca_condense":
+            rc = lib.lca_condense(*common, vp(run.ws.data_ptr()), ctypes.c_size_t(run.ws.numel()), st)
+        else:
+            rc = lib.lca_condense_noalloc(*common, st)
+        assert rc == lca.OK, lib.lca_last_error()
+        torch.cuda.synchronize()
+        outs.append((pool_rep, sel_rep, anchor, alpha))
+    return run, outs
+
+
+def _same_bits(a, b):
+    import torch
+    for x, y in zip(a, b):
+        assert x.shape == y.shape
+        if x.numel():
+            assert torch.equal(x.contiguous().view(torch.uint8), y.contiguous().view(torch.uint8))
+
+
+def test_noalloc_matches_condense_twice_second_call_smaller(oracle):
+    big = inputs.Workload("noalloc_big", B=2, L=1500, H=8, S=4, d_pool=512, d_sel=64, g=16, w=100, dtype="bf16", seed=801)
+    small = inputs.Workload("noalloc_small", B=1, L=300, H=2, S=1, d_pool=512, d_sel=64, g=8, w=20, dtype="bf16", seed=802)
+    for wl in (big, small):          # the second call finds the first call's summary queries in the scratch
+        run, (ref, got) = _both(wl)
+        _same_bits(ref, got)
+        # and the result is the method's: the oracle's check of stage 1 on the no-allocation call's outputs
+        run.pool_rep, run.sel_rep, run.anchor, run.alpha = got
+        Qf = inputs.to_f64(inputs.gen_all(wl)[0][:, wl.L - wl.nq:], wl.dtype)
+        POOLf, SELf = hp.from_dev(run.POOL, wl.dtype), hp.from_dev(run.SEL, wl.dtype)
+        hp.check_condense(oracle, wl, run, Qf, POOLf, SELf)
+
+
+def test_noalloc_gqa_and_fp32_shapes(oracle):
+    for wl in (inputs.Workload("noalloc_gqa", B=2, L=700, H=8, S=2, d_pool=128, d_sel=128, g=16, w=64, dtype="f16", mode=inputs.MODE_GQA, seed=803,
+                               theta=500000.0),
+               inputs.Workload("noalloc_f32", B=1, L=333, H=4, S=2, d_pool=24, d_sel=16, g=4, w=10, dtype="f32", seed=804),
+               inputs.Workload("noalloc_nogroups", B=1, L=40, H=2, S=1, d_pool=512, d_sel=64, g=16, w=64, dtype="bf16", seed=805)):
+        _, (ref, got) = _both(wl)
+        _same_bits(ref, got)
+
+
+def test_noalloc_rejects_what_its_scratch_cannot_hold():
+    import torch
+    from paper_2604_12452_amd import lca
+    lib = lca.load()
+    # B * S * d_qk * 4 bytes = 8 * 16 * 576 * 4 = 294 912 > 256 KiB
+    d = lca.Desc(B=8, L=64, H=16, S=16, d_pool=512, d_sel=64, g=4, w=8)
+    buf = torch.zeros(1 << 24, dtype=torch.bfloat16, device="cuda")
+    idx = torch.full((1 << 16,), -3, dtype=torch.int32, device="cuda")
+    cd = d.c()
+    vp = ctypes.c_void_p
+    rc = lib.lca_condense_noalloc(ctypes.byref(cd), vp(buf.data_ptr()), vp(buf.data_ptr()), vp(buf.data_ptr()), vp(buf.data_ptr()),
+                                  vp(buf.data_ptr()), vp(idx.data_ptr()), vp(0), vp(torch.cuda.current_stream().cuda_stream))
+    assert rc == lca.ERR_WORKSPACE
+    msg = lib.lca_last_error().decode()
+    assert "294912" in msg and "262144" in msg, msg
+    torch.cuda.synchronize()
+    assert bool((idx == -3).all()) and bool((buf == 0).all())        # nothing was launched
+    # the largest descriptor that fits: B * S = 113 sets of 576 floats
+    ok = lca.Desc(B=113, L=64, H=1, S=1, d_pool=512, d_sel=64, g=4, w=8)
+    cd = ok.c()
+    MB = 1 << 20           # Q 8.3 MB, POOL 7.4 MB, SEL 0.9 MB, pool_rep 1.6 MB, sel_rep 0.2 MB: disjoint pieces of the 32 MB buffer
+    base = buf.data_ptr()
+    rc = lib.lca_condense_noalloc(ctypes.byref(cd), vp(base), vp(base + 10 * MB), vp(base + 20 * MB), vp(base + 24 * MB),
+                                  vp(base + 28 * MB), vp(idx.data_ptr()), vp(0), vp(torch.cuda.current_stream().cuda_stream))
+    assert rc == lca.OK, lib.lca_last_error()
+    torch.cuda.synchronize()
