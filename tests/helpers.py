@@ -19,8 +19,10 @@ LSE_TOL = {"bf16": 1e-2, "f32": 1e-4, "f16": 1e-2}
 # the float64 one by up to half a unit in the last place of every component (2^-9 relative in bf16, 2^-12 in fp16), which
 # reaches the output twice: as the value, and through the logits scale * <q, c_rep>, whose perturbation grows with the
 # scale (at scale 3 it moves probabilities by about one per cent in bf16).  Largest values measured over all cases:
-# bf16 1.76e-2 (the scale-3 cases; 7.8e-3 otherwise at the narrow widths), fp16 2.4e-3, fp32 5e-6.  Gated at twice TOL.
-E4_TOL = {"bf16": 2e-2, "f32": 1e-4, "f16": 4e-3}
+# scale <= 1 (every benchmark configuration): bf16 8.96e-3, fp16 1.72e-3, fp32 2.5e-6 -- held to TOL itself;
+# scale 3: bf16 1.76e-2, fp16 2.37e-3, fp32 5.2e-6 -- held to twice TOL.
+def e4_tol(wl):
+    return TOL[wl.dtype] * (1.0 if wl.scale <= 1.0 else 2.0)
 ANCHOR_MARGIN = 1e-3   # anchors must match bit-exactly where the oracle's top-two score gap exceeds this
 
 # Largest value seen of the end-to-end comparison against the oracle that never rounds its cache, per element type and
@@ -119,7 +121,7 @@ def check_prefill(o, wl, run: GpuRun, rows, Qf_rows, POOLf, SELf, ref_cond, diff
     e4 = vec_rel_err(O_gpu, O4)
     note(("e4", wl.dtype, "layer widths" if wl.d_pool >= 128 else "narrow", "scale > 1" if wl.scale > 1 else "scale <= 1"), e4)
     print(f"  end to end against the unrounded float64 cache: rel err {e4:.3e}", flush=True)
-    assert e4 <= E4_TOL[wl.dtype], f"stage 3 against the unrounded fp64 cache: rel err {e4:.3e} > {E4_TOL[wl.dtype]}"
+    assert e4 <= e4_tol(wl), f"stage 3 against the unrounded fp64 cache: rel err {e4:.3e} > {e4_tol(wl)}"
     return e2, e3
 
 
