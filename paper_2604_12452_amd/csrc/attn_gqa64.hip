@@ -68,7 +68,7 @@ constexpr int BMW = 64;                 // query rows per wavefront
 constexpr int NKS = D / 16;             // 8 k-steps of S^T
 constexpr int NDV = D / 32;             // 4 value tiles
 constexpr int COPIES = 2 * BN / NW / 4; // direct-to-LDS loads per wavefront and tile: 16 rows of K and of V, 4 rows each
-constexpr int GRID = 256;               // workgroups of the persistent kernel = CUs of the chip
+constexpr int GRID = 256;               // most workgroups the persistent kernel is launched with (one per CU of the chip)
 constexpr int RING = 4;                 // fragments in flight per operand
 constexpr float NEG_BIG = -1.0e30f;
 constexpr float L_LIMIT = 0x1p90f;      // a row sum beyond this (or not finite) makes the workgroup repeat the item from exact maxima
@@ -766,7 +766,8 @@ hipError_t launch_attn_gqa64(const AttnArgs &a, hipStream_t st)
     kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
     // persistent grid: one workgroup per CU (a workgroup takes 128 KB of LDS and most of the registers)
     const long items = (long)kp.n_qb * kp.n_units;
-    long grid = items < GRID ? items : GRID;
+    const long cus = persistent_grid();     // <= GRID
+    long grid = items < cus ? items : cus;
     grid = (grid + 7) / 8 * 8;
     if (d.dtype == LCA_F16)
         attn_gqa64_kernel<true><<<(unsigned)grid, 64 * NW, 0, st>>>(kp);

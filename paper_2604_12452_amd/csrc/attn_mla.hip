@@ -72,7 +72,6 @@ constexpr int NDV = DV / 32;            // 16 value tiles
 #endif
 constexpr int CHAIN_DEPTH = LCA_CHAIN_DEPTH;   // key fragments in flight ahead of the S^T chain
 constexpr int DU = 128;                  // UP variant: width of a head's value after the up-projection
-constexpr int MLA_GRID = 256;            // workgroups of the persistent kernel = CUs of the chip
 constexpr float NEG_BIG = -1.0e30f;     // stands for -inf in running maxima (keeps exp2 arguments finite)
 constexpr float L_LIMIT = 0x1p90f;      // a row sum beyond this (or not finite) makes the workgroup repeat the item from exact maxima
 // fp16 ends at 65504: the fp16 kernels keep the largest exponential of each row (one v_max3 per pair) and repeat the item
@@ -865,7 +864,8 @@ hipError_t launch_attn_mla(const AttnArgs &a, hipStream_t st)
     kp.bias_log2 = d.rep_logit_bias * 1.4426950408889634f;
     // persistent grid: one workgroup per CU (a workgroup takes all of a CU's LDS and registers)
     const long items = (((long)kp.n_qb * d.B + 15) / 16) * 16 * d.H;
-    long grid = items < MLA_GRID ? items : MLA_GRID;
+    const long cus = persistent_grid();
+    long grid = items < cus ? items : cus;
     grid = (grid + 7) / 8 * 8;
     kp.W_up = nullptr;
     if (a.W_up != nullptr) {

@@ -65,6 +65,9 @@ struct UpdateArgs {
     int m_cap, k_cap, k_start;
 };
 
+// Workgroups of a persistent one-per-CU kernel on the current device (its CU count, a multiple of 8 in [8, 256]).
+int persistent_grid();
+
 // Launchers return hipSuccess or the launch error. They assume validated arguments.
 hipError_t launch_condense(const CondenseArgs &a, hipStream_t st);
 hipError_t launch_summary_query(const Dims &d, const void *Q, int L, float *qbar, hipStream_t st);

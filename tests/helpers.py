@@ -18,11 +18,13 @@ LSE_TOL = {"bf16": 1e-2, "f32": 1e-4, "f16": 1e-2}
 # End to end against an oracle whose cache is never rounded to the storage type.  The stored representative differs from
 # the float64 one by up to half a unit in the last place of every component (2^-9 relative in bf16, 2^-12 in fp16), which
 # reaches the output twice: as the value, and through the logits scale * <q, c_rep>, whose perturbation grows with the
-# scale (at scale 3 it moves probabilities by about one per cent in bf16).  Largest values measured over all cases:
-# scale <= 1 (every benchmark configuration): bf16 8.96e-3, fp16 1.72e-3, fp32 2.5e-6 -- held to TOL itself;
-# scale 3: bf16 1.76e-2, fp16 2.37e-3, fp32 5.2e-6 -- held to twice TOL.
+# size of the logits (at scale 3, or with latents thirty times larger, it moves probabilities by about one per cent in
+# bf16).  Largest values measured over all cases:
+# logits of the benchmark configurations' size (scale <= 1, AR(1) rho <= 0.9): bf16 8.96e-3, fp16 1.72e-3, fp32 2.5e-6
+#   -- held to TOL itself;
+# larger logits (scale 3: bf16 1.76e-2, fp16 2.37e-3, fp32 5.2e-6; rho = 0.9999 latents: bf16 1.50e-2) -- held to twice TOL.
 def e4_tol(wl):
-    return TOL[wl.dtype] * (1.0 if wl.scale <= 1.0 else 2.0)
+    return TOL[wl.dtype] * (1.0 if wl.scale <= 1.0 and wl.rho <= 0.9 else 2.0)
 ANCHOR_MARGIN = 1e-3   # anchors must match bit-exactly where the oracle's top-two score gap exceeds this
 
 # Largest value seen of the end-to-end comparison against the oracle that never rounds its cache, per element type and
@@ -119,7 +121,7 @@ def check_prefill(o, wl, run: GpuRun, rows, Qf_rows, POOLf, SELf, ref_cond, diff
     # The same against an oracle that never rounds its cache (all-float64 end to end).
     O4 = o.lca_attn_rows(od, rows, Qf_rows, POOLf, SELf, ref_cond["pool_rep"], sel3)
     e4 = vec_rel_err(O_gpu, O4)
-    note(("e4", wl.dtype, "layer widths" if wl.d_pool >= 128 else "narrow", "scale > 1" if wl.scale > 1 else "scale <= 1"), e4)
+    note(("e4", wl.dtype, "layer widths" if wl.d_pool >= 128 else "narrow", "large logits" if wl.scale > 1 or wl.rho > 0.9 else "benchmark-sized logits"), e4)
     print(f"  end to end against the unrounded float64 cache: rel err {e4:.3e}", flush=True)
     assert e4 <= e4_tol(wl), f"stage 3 against the unrounded fp64 cache: rel err {e4:.3e} > {e4_tol(wl)}"
     return e2, e3

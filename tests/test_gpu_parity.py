@@ -145,6 +145,15 @@ def test_mla_mfma_multiplicity_bias(oracle):
     _full_parity(oracle, wl, bias=math.log(16.0), dense=False)
 
 
+@pytest.mark.parametrize("mode,d_pool,d_sel,S", [(inputs.MODE_MLA, 512, 64, 1), (inputs.MODE_GQA, 128, 128, 2)])
+def test_strongly_redundant_latents(oracle, mode, d_pool, d_sel, S):
+    """Neighbouring tokens nearly equal (AR(1) with rho = 0.9999: the regime of a few per cent relative deviation that the
+    paper reports for model activations): scores inside a group are close, so near-ties are frequent, and values are large."""
+    wl = inputs.Workload("redundant", B=1, L=900, H=4, S=S, d_pool=d_pool, d_sel=d_sel, g=16, w=100, dtype="bf16", mode=mode, seed=15, rho=0.9999,
+                         theta=500000.0 if mode == inputs.MODE_GQA else 10000.0)
+    _full_parity(oracle, wl)
+
+
 def test_mla_topic_shift_inputs(oracle):
     wl = inputs.Workload("mla_topics", B=2, L=640, H=2, S=1, d_pool=512, d_sel=64, g=16, w=64, dtype="bf16", seed=9, segments=8)
     _full_parity(oracle, wl)
