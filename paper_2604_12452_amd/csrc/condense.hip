@@ -510,6 +510,10 @@ hipError_t launch_condense(const CondenseArgs &a, hipStream_t st)
     // 1. summary query (Algorithm 1, first step)
     hipError_t err = launch_summary_query(d, a.Q, d.L, a.qbar, st);
     if (err != hipSuccess || d.m == 0) return err;
+    // MLA widths, several sets, groups of whole 16-row tiles: scores and pooling on the matrix cores.  (Measured at 128K, g = 16,
+    // this kernel / the register kernel below, summary query included: 52 / 40 us with one set, 52 / 51 with two, 55 / 72 with
+    // four, 60 / 111 with eight, 72 / 190 with sixteen.)
+    if (condense_mla_mfma_supported(d) && d.S >= 3) return launch_condense_mla_mfma(a, st);
     // 2. groups
     const bool mla = d.mode == LCA_MODE_MLA;
     // the register kernels implement the method's own strategies (weighted pooling, max selection); the ablation's others run generic

@@ -71,6 +71,8 @@ int persistent_grid();
 // Launchers return hipSuccess or the launch error. They assume validated arguments.
 hipError_t launch_condense(const CondenseArgs &a, hipStream_t st);
 hipError_t launch_summary_query(const Dims &d, const void *Q, int L, float *qbar, hipStream_t st);
+bool condense_mla_mfma_supported(const Dims &d);
+hipError_t launch_condense_mla_mfma(const CondenseArgs &a, hipStream_t st);
 hipError_t launch_attn_simple(const AttnArgs &a, hipStream_t st);
 bool attn_mla_supported(const Dims &d);
 size_t attn_mla_up_workspace_bytes(const Dims &d);

@@ -594,3 +594,29 @@ def test_decode_step_with_multiplicity_bias_and_scale(oracle, mode, d_pool, d_se
     print(f"  decode err {err:.2e} (the same step without the bias differs by {hp.vec_rel_err(nobias, ref):.2e})", flush=True)
     assert err <= hp.TOL[dtype]
     assert hp.vec_rel_err(nobias, ref) > 10 * hp.TOL[dtype], "the bias must matter on this input, or the case proves nothing"
+
+
+# ---- condensation with several sets at the MLA widths: the matrix-core kernel ------------------------------------------------
+@pytest.mark.parametrize("B,L,H,S,g,w,n_q,scale,dtype", [
+    (1, 700, 16, 16, 16, 100, 0, 1.0, "bf16"),        # one set per head, the benchmark's variant
+    (2, 1500, 16, 16, 16, 37, 0, 1.0, "f16"),         # more groups than wavefronts in a small grid, two sequences
+    (1, 900, 8, 4, 32, 64, 0, 1.0, "bf16"),           # two tiles per group (online softmax across them), two heads per set
+    (2, 1000, 12, 3, 48, 20, 5, 0.37, "bf16"),        # three tiles per group, three sets, n_q != g, scale != 1
+    (1, 1300, 16, 8, 64, 10, 64, 1.0, "f16"),         # four tiles per group
+    (3, 200, 6, 6, 16, 8, 3, -0.5, "bf16"),           # a negative scale turns the order of the scores around
+    (1, 300, 5, 5, 16, 12, 0, 0.0, "f16"),            # zero scale: uniform weights, the first row of each group
+    (1, 4500, 32, 16, 16, 64, 0, 3.0, "bf16"),        # sharp weights, two heads per set, several tiles per wavefront
+])
+def test_condense_matrix_core_kernel(oracle, B, L, H, S, g, w, n_q, scale, dtype):
+    """lca_condense where it runs on the matrix cores (MLA widths, at least three sets, groups of whole 16-row tiles): weights,
+    anchors, copied keys and pooled vectors against the oracle; the summary query and the weights enter the products as hi + lo
+    pairs of 16-bit numbers, so the weights must still agree to 1e-4 and the anchors wherever the margin allows."""
+    wl = inputs.Workload("condense_mc", B=B, L=L, H=H, S=S, d_pool=512, d_sel=64, g=g, w=w, n_q=n_q, dtype=dtype, seed=600 + L, scale=scale)
+    print(f"[case] {wl}", flush=True)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense(alpha=True)
+    hp.check_condense(oracle, wl, run, inputs.to_f64(Q[:, wl.L - wl.nq:], wl.dtype), inputs.to_f64(POOL, wl.dtype), inputs.to_f64(SEL, wl.dtype))
+    # without the weights' debug output the kernel takes the same path otherwise: identical representatives
+    again = hp.GpuRun(wl, Q, POOL, SEL).condense(alpha=False)
+    for x, y in ((run.pool_rep, again.pool_rep), (run.sel_rep, again.sel_rep), (run.anchor, again.anchor)):
+        assert bool((x.view(-1) == y.view(-1)).all())
