@@ -362,6 +362,10 @@ def main():
     ws_sq = lca.alloc_workspace(d_sq)
     ms_sq = time_kernel(lambda: lca.condense(d_sq, run.Q, run.POOL, run.SEL, run.pool_rep, run.sel_rep, run.anchor, None, ws_sq), 21, 3,
                         behind=f_attn)
+    # ... and the floor under any launch: the same kernel over ONE query row of one head (nothing to read to speak of)
+    d_min = hp.lca_desc(wl.with_(w=wl.L, n_q=1, H=wl.S))
+    ms_launch = time_kernel(lambda: lca.condense(d_min, run.Q, run.POOL, run.SEL, run.pool_rep, run.sel_rep, run.anchor, None, ws_sq), 21, 3,
+                            behind=f_attn)
     del ws_sq
     pairs = pair_count(wl.L, wl.w, wl.g)
     flops = 2.0 * (wl.d_qk + wl.d_v) * wl.B * wl.H * pairs
@@ -372,7 +376,7 @@ def main():
         "ms_condense": ms_cond, "ms_attn": ms_attn,
         "condense_algorithmic_bytes": cbytes, "condense_GBps": cbytes / (ms_cond * 1e-3) / 1e9,
         "condense_frac_of_hbm_peak": cbytes / (ms_cond * 1e-3) / 1e9 / PEAK_HBM_GBS,
-        "ms_summary_query": ms_sq, "ms_condense_kernel": ms_cond - ms_sq,
+        "ms_summary_query": ms_sq, "ms_smallest_launch": ms_launch, "ms_condense_kernel": ms_cond - ms_sq,
         "condense_kernel_frac_of_hbm_peak": cbytes / ((ms_cond - ms_sq) * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "attn_algorithmic_flops": flops, "input_generation_s": t_gen,
     }

@@ -767,18 +767,23 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         const float l_tot = st.l_run + __shfl_xor(st.l_run, 32, 64);
         const float inv = 1.f / l_tot;
         floatx16 up[UP ? DU / 32 : 1];
+        // The lane number is taken afresh for everything from here on.  Values derived from it before the loop are kept in
+        // spilled registers, and every reload from scratch memory is a round trip of its own that also waits for ALL
+        // vector-memory operations in flight: below, the next item's queries and first tiles and the output stores.
+        const int lane_here = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        const int n_here = lane_here & 31, G_here = lane_here >> 5;
         if (has_next) {
-            cur = make_blk(kp, nb, nh, nqb, wave, n);
-            // The queries first: what their addresses are computed from comes back from scratch memory (spilled registers),
-            // and such a reload waits for every vector-memory operation issued before it -- behind the copies it would wait
+            cur = make_blk(kp, nb, nh, nqb, wave, n_here);
+            // The queries first: behind the copies, anything their addresses still need from scratch memory would wait
             // for the tiles to arrive from HBM before the first query load could even be issued.
-            if (!UP) load_q(kp, cur, wave, lane, qf);
-            issue_first_copies(cur, wave, lds0, voff_pool, voff_sel);
+            if (!UP) load_q(kp, cur, wave, lane_here, qf);
+            issue_first_copies(cur, wave, lds0, lane_here * 16,
+                               (lane_here >> 3) * (DS * 2) + (((lane_here & 7) ^ ((4 * wave + (lane_here >> 4)) & 7)) << 4));
         }
         if constexpr (UP) {
             // (the projection needs the registers the next item's queries would take: those are requested after it)
             up_project<F16>(acc, inv, kp.W_up + (size_t)out_h * DU * DV, lane, up);
-            if (has_next) load_q(kp, cur, wave, lane, qf);
+            if (has_next) load_q(kp, cur, wave, lane_here, qf);
         }
 
         // ---- epilogue: normalise, transpose through LDS stage 3 (four passes of 128 value columns), store coalesced ----
@@ -786,11 +791,6 @@ __global__ __launch_bounds__(256) void attn_mla_kernel(const MlaParams kp)
         static_assert(4 * 32 * ORS <= STAGE_BYTES, "output staging must fit in one tile stage");
         char *obuf = &stages[3][0] + wave * 32 * ORS;
         const int t_wfirst = out_t0 + wave * 32;
-        // The lane number is taken afresh for everything from here on.  Values derived from it before the loop are kept in
-        // spilled registers, and every reload from scratch memory waits for ALL vector-memory operations in flight: here
-        // the next item's queries and first tiles, just requested, and below the output stores.
-        const int lane_here = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-        const int n_here = lane_here & 31, G_here = lane_here >> 5;
         // The stores go through a buffer descriptor of this wavefront's rows of this head (row r at r*H*1 KB): scalar
         // offsets instead of 64-bit address arithmetic per store, and rows past the end of the sequence fall outside
         // the descriptor's range and are dropped.
