@@ -116,7 +116,8 @@ def cpu_baseline(wl, Q, POOL, SEL, n_rows: int, gpu_anchor=None, gpu_sel_rep=Non
     }, rows, O, near_ties
 
 
-PROFILES = {"cfg4": "lca_prefill_cfg4_128k.md", "cfg5": "lca_prefill_cfg5_gqa_64k.md",
+PROFILES = {"cfg4": "lca_prefill_cfg4_128k.md", "cfg5": "lca_prefill_cfg5_gqa_64k.md", "cfg3": "lca_prefill_cfg3_32k.md",
+            "cfg2": "lca_prefill_cfg2_8k.md", "cfg4+S=16": "lca_prefill_cfg4_128k_per_head_sets.md",
             "cfg4/decode": "lca_decode_cfg4_mla_128k.md", "cfg5/decode": "lca_decode_cfg5_gqa_64k.md"}
 
 
@@ -299,6 +300,7 @@ def main():
         assert set(over) <= {"B", "L", "H", "S", "g", "w", "n_q"}, over
         wl = wl.with_(name=wl.name + "+" + ",".join(args.set), **over)
     tdt = torch.bfloat16 if args.dtype == "bf16" else torch.float16
+    prof_key = args.config + ("+" + ",".join(sorted(args.set)) if args.set else "")       # a summary exists for few of the overrides
     if args.pmc_calib:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -312,7 +314,7 @@ def main():
                           "n_gpus": 1, "higher_is_better": False, "dtype": args.dtype, "data": "synthetic",
                           "roofline": {"bound": "hbm", "kernel": dec_kernel + " (lca_decode_attn)", "achieved": dec["GBps"], "peak": PEAK_HBM_GBS,
                                        "unit": "GB/s", "frac": dec["frac_of_hbm_peak"],
-                                       "traffic": profiled_traffic(args.config + "/decode", dec_kernel) if args.dtype == "bf16" else None}, "extra": dec}))
+                                       "traffic": profiled_traffic(prof_key + "/decode", dec_kernel) if args.dtype == "bf16" else None}, "extra": dec}))
         return
     if args.sweep:
         print(json.dumps({"metric": f"LCA prefill over the method's settings ({wl.name} shapes)", "unit": "tokens/s", "n_gpus": 1,
@@ -477,7 +479,7 @@ def main():
                    "step": "lca_condense + lca_prefill_attn"},
         "roofline": {"bound": "mfma", "kernel": ("attn_mla_kernel" if mla else "attn_gqa64_kernel") + " (lca_prefill_attn)", "achieved": tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
-                     "traffic": profiled_traffic(args.config, "attn_mla_kernel" if mla else "attn_gqa64_kernel")},
+                     "traffic": profiled_traffic(prof_key, "attn_mla_kernel" if mla else "attn_gqa64_kernel") if args.dtype == "bf16" else None},
         "cpu_baseline": base,
         "extra": extra,
     }
