@@ -620,3 +620,30 @@ def test_condense_matrix_core_kernel(oracle, B, L, H, S, g, w, n_q, scale, dtype
     again = hp.GpuRun(wl, Q, POOL, SEL).condense(alpha=False)
     for x, y in ((run.pool_rep, again.pool_rep), (run.sel_rep, again.sel_rep), (run.anchor, again.anchor)):
         assert bool((x.view(-1) == y.view(-1)).all())
+
+
+def _random_condense_mc_shapes(n, seed):
+    """Seeded draws of shapes the matrix-core condensation kernel takes: 3..16 sets, groups of 1..4 tiles, lengths from fewer
+    groups than wavefronts to several groups per wavefront, several sequences, heads per set 1..3, n_q around g."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        S = int(rng.integers(3, 17))
+        hps = int(rng.choice([1, 1, 2, 3]))
+        g = int(rng.choice([16, 16, 32, 48, 64]))
+        m = int(rng.choice([1, 2, 3, 5, 17, 40, 130]))
+        w = int(rng.choice([0, 1, 16, 33, 100]))
+        L = w + m * g + int(rng.integers(0, g))
+        n_q = int(rng.choice([0, 1, g // 2, g + 3]))
+        out.append((int(rng.integers(1, 4)), L, S * hps, S, g, w, min(n_q, L), str(rng.choice(["bf16", "f16"]))))
+    return out
+
+
+@pytest.mark.parametrize("B,L,H,S,g,w,n_q,dtype", _random_condense_mc_shapes(20, 2028))
+def test_condense_matrix_core_kernel_random_shapes(oracle, B, L, H, S, g, w, n_q, dtype):
+    wl = inputs.Workload("condense_mc_rand", B=B, L=L, H=H, S=S, d_pool=512, d_sel=64, g=g, w=w, n_q=n_q, dtype=dtype, seed=700 + L + S)
+    print(f"[case] {wl}", flush=True)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    run = hp.GpuRun(wl, Q, POOL, SEL).condense(alpha=True)
+    assert run.desc.m == (L - w) // g
+    hp.check_condense(oracle, wl, run, inputs.to_f64(Q[:, wl.L - wl.nq:], wl.dtype), inputs.to_f64(POOL, wl.dtype), inputs.to_f64(SEL, wl.dtype))
