@@ -99,3 +99,42 @@ def test_noalloc_rejects_what_its_scratch_cannot_hold():
                                   vp(base + 28 * MB), vp(idx.data_ptr()), vp(0), vp(torch.cuda.current_stream().cuda_stream))
     assert rc == lca.OK, lib.lca_last_error()
     torch.cuda.synchronize()
+
+
+def test_noalloc_replays_in_a_graph():
+    """What the entry point is for: recorded once into a HIP graph (after one eager call, which looks up the scratch's address) and
+    replayed with eager work in between.  The queries change between the replays, so every replay has to rewrite the summary
+    queries in the built-in scratch; each replay is compared bit for bit with lca_condense run eagerly on the same inputs."""
+    import torch
+    from paper_2604_12452_amd import lca
+    wl = inputs.Workload("noalloc_graph", B=2, L=900, H=8, S=2, d_pool=512, d_sel=64, g=16, w=100, dtype="bf16", seed=806)
+    Q, POOL, SEL = inputs.gen_all(wl)
+    run = hp.GpuRun(wl, Q, POOL, SEL)
+    d = run.desc
+    variants = [run.Q.clone()]
+    for k in (1, 2, 3):                                  # other queries in the rows the summary query reads
+        v = run.Q.clone()
+        v[:, wl.L - wl.nq:] = torch.roll(run.Q[:, wl.L - wl.nq:], shifts=k, dims=1) * (1.0 + 0.25 * k)
+        variants.append(v)
+    got = lca.alloc_condensed(d)[:3]
+    ref = lca.alloc_condensed(d)[:3]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        lca.condense_noalloc(d, run.Q, run.POOL, run.SEL, *got, None)       # eager warm-up on the capturing stream
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        lca.condense_noalloc(d, run.Q, run.POOL, run.SEL, *got, None)
+    for replay, qv in enumerate(variants):
+        run.Q.copy_(qv)
+        for x in got:
+            x.view(torch.uint8).fill_(0xA5)
+        junk = (torch.randn(1 << 20, device="cuda") * 2).sum()            # eager work between the replays
+        lca.condense(d, run.Q, run.POOL, run.SEL, *ref, None, run.ws)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(got, ref):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), f"replay {replay} differs from the eager lca_condense"
+        assert bool(torch.isfinite(junk))
