@@ -2,7 +2,7 @@
 // delta_k, delta_v of the error bound (section 4.4, Theorem 1 of the paper), measured as in its appendix on
 // empirical per-token deviations (Tables 9-10).  HBM-bound: every condensed token's row is read once.
 //
-//   deviation_group_kernel   one wavefront per (sequence, set, group): lanes stride over the columns of each of the
+//   deviation_group_kernel   one wavefront per (sequence, set, group): lanes stride over the 16-byte pieces of each of the
 //                            g rows, wave reductions give || row - rep ||^2 and || row ||^2 for both components;
 //                            writes the group's (sum dk, sum dk/||k||, max dk, sum dv, sum dv/||v||, max dv).
 //   deviation_reduce_kernel  one workgroup per (sequence, set): adds the groups in a fixed order (deterministic).
@@ -13,10 +13,51 @@ namespace {
 
 constexpr int WAVE = 64;
 
+// 16-byte pieces of a row: EPC elements of type T, widened to float
 template <typename T> struct VElt;
-template <> struct VElt<uint16_t> { __device__ static float ld(const uint16_t *p) { return __uint_as_float((unsigned)*p << 16); } };
-template <> struct VElt<f16_t> { __device__ static float ld(const f16_t *p) { return f16_bits_to_float(p->bits); } };
-template <> struct VElt<float> { __device__ static float ld(const float *p) { return *p; } };
+template <> struct VElt<uint16_t> {
+    static constexpr int EPC = 8;
+    __device__ static void unpack(const uint4 &c, float *f)
+    {
+        const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { f[2 * i] = __uint_as_float(w[i] << 16); f[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
+    }
+};
+template <> struct VElt<f16_t> {
+    static constexpr int EPC = 8;
+    __device__ static void unpack(const uint4 &c, float *f)
+    {
+        const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { f[2 * i] = f16_bits_to_float((uint16_t)w[i]); f[2 * i + 1] = f16_bits_to_float((uint16_t)(w[i] >> 16)); }
+    }
+};
+template <> struct VElt<float> {
+    static constexpr int EPC = 4;
+    __device__ static void unpack(const uint4 &c, float *f)
+    {
+        f[0] = __uint_as_float(c.x); f[1] = __uint_as_float(c.y); f[2] = __uint_as_float(c.z); f[3] = __uint_as_float(c.w);
+    }
+};
+
+// sum over this lane's 16-byte pieces of (row - rep)^2 and row^2 (widths are multiples of EPC, rows 16-byte aligned: checked at the boundary)
+template <typename T>
+__device__ __forceinline__ void diff_norms(const T *row, const T *rep, int width, int lane, float &d2, float &n2)
+{
+    constexpr int EPC = VElt<T>::EPC;
+    for (int c = lane; c < width / EPC; c += WAVE) {
+        float v[EPC], r[EPC];
+        VElt<T>::unpack(*reinterpret_cast<const uint4 *>(row + c * EPC), v);
+        VElt<T>::unpack(*reinterpret_cast<const uint4 *>(rep + c * EPC), r);
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) {
+            const float x = v[e] - r[e];
+            d2 = fmaf(x, x, d2);
+            n2 = fmaf(v[e], v[e], n2);
+        }
+    }
+}
 
 __device__ __forceinline__ float wave_sum(float x)
 {
@@ -41,14 +82,8 @@ __global__ __launch_bounds__(256) void deviation_group_kernel(const T *__restric
     for (int r = 0; r < g; ++r) {
         const T *pr = pool_base + (size_t)(j * g + r) * P * d_pool, *sr = sel_base + (size_t)(j * g + r) * P * d_sel;
         float dp2 = 0.f, np2 = 0.f, ds2 = 0.f, ns2 = 0.f;
-        for (int x = lane; x < d_pool; x += WAVE) {
-            const float v = VElt<T>::ld(pr + x), e = v - VElt<T>::ld(prep + x);
-            dp2 = fmaf(e, e, dp2); np2 = fmaf(v, v, np2);
-        }
-        for (int x = lane; x < d_sel; x += WAVE) {
-            const float v = VElt<T>::ld(sr + x), e = v - VElt<T>::ld(srep + x);
-            ds2 = fmaf(e, e, ds2); ns2 = fmaf(v, v, ns2);
-        }
+        diff_norms(pr, prep, d_pool, lane, dp2, np2);
+        diff_norms(sr, srep, d_sel, lane, ds2, ns2);
         dp2 = wave_sum(dp2); np2 = wave_sum(np2); ds2 = wave_sum(ds2); ns2 = wave_sum(ns2);
         const float dk = sqrtf(mla ? dp2 + ds2 : ds2), nk = sqrtf(mla ? np2 + ns2 : ns2), dv = sqrtf(dp2), nv = sqrtf(np2);
         sum_dk += dk; sum_rk += nk > 0.f ? dk / nk : 0.f; max_dk = fmaxf(max_dk, dk);
