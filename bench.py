@@ -117,7 +117,7 @@ def cpu_baseline(wl, Q, POOL, SEL, n_rows: int, gpu_anchor=None, gpu_sel_rep=Non
 
 
 PROFILES = {"cfg4": "lca_prefill_cfg4_128k.md", "cfg5": "lca_prefill_cfg5_gqa_64k.md", "cfg3": "lca_prefill_cfg3_32k.md",
-            "cfg2": "lca_prefill_cfg2_8k.md", "cfg4+S=16": "lca_prefill_cfg4_128k_per_head_sets.md",
+            "cfg2": "lca_prefill_cfg2_8k.md", "cfg4+S=16": "lca_prefill_cfg4_128k_per_head_sets.md", "cfg4+g=32": "lca_prefill_cfg4_128k_g32.md",
             "cfg4/decode": "lca_decode_cfg4_mla_128k.md", "cfg5/decode": "lca_decode_cfg5_gqa_64k.md"}
 
 
