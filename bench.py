@@ -75,6 +75,29 @@ def rotating(make_call, n=N_ROT):
     return fn
 
 
+def measured_ceilings(torch, lca, behind):
+    """What this chip sustains at the two operations the roofline fractions are read against, from the library's two
+    probes: one pass over 151 MB (the bytes one 128K condensation reads) out of HBM, inputs rotated so that no call
+    finds them in the memory-side cache, and back-to-back bf16 matrix-core products on every SIMD (the clock the chip
+    settles at under that load is part of the figure).  The published peaks stay the denominators of `roofline`."""
+    n_words = 151 * (1 << 20) // 4
+    bufs = [torch.randint(-2 ** 31, 2 ** 31 - 1, (n_words,), dtype=torch.int32, device="cuda") for _ in range(N_ROT + 1)]
+    sums = torch.empty(lca.PROBE_WORDS, dtype=torch.int32, device="cuda")
+    ms_read = time_kernel(rotating(lambda i: (lambda: lca.probe_hbm_read(bufs[i], sums)), n=N_ROT + 1), 24, 4, behind=behind)
+    del bufs
+    out = torch.empty(lca.PROBE_MFMA_FLOATS, dtype=torch.float32, device="cuda")
+    iters = 50000
+    waves = lca.probe_mfma_bf16(iters, out)
+    # pattern 1: operands with every mantissa bit in use, as a kernel's real data (the clock under load depends on it); pattern 0:
+    # small integers (the probe's checkable form), which toggle few bits and run faster
+    ms_mfma = time_kernel(lambda: lca.probe_mfma_bf16(iters, out, pattern=1), 5, 1)
+    ms_mfma_int = time_kernel(lambda: lca.probe_mfma_bf16(iters, out, pattern=0), 5, 1)
+    fl = waves * iters * 4 * 32768.0
+    return {"hbm_read_TBps": n_words * 4 / (ms_read * 1e-3) / 1e12, "hbm_read_bytes": n_words * 4, "ms_hbm_read": ms_read,
+            "mfma_bf16_TFLOPs": fl / (ms_mfma * 1e-3) / 1e12, "ms_mfma": ms_mfma,
+            "mfma_bf16_small_integer_operands_TFLOPs": fl / (ms_mfma_int * 1e-3) / 1e12, "mfma_wavefronts": waves}
+
+
 def cpu_baseline(wl, Q, POOL, SEL, n_rows: int, gpu_anchor=None, gpu_sel_rep=None):
     """The fp64 oracle as it stands, timed on the host cores, on a bounded sample of the workload:
     the full condensation plus n_rows evenly spaced query rows (all heads); extrapolated to a full
@@ -406,6 +429,10 @@ def main():
         ms_gemm = time_kernel(lambda: torch.matmul(ga, gb), 10, 2)
         extra["context_library_gemm_bf16_8192_TFLOPs"] = 2.0 * 8192 ** 3 / (ms_gemm * 1e-3) / 1e12
         del ga, gb
+        extra["measured_ceilings"] = measured_ceilings(torch, lca, f_attn)
+        extra["measured_ceilings"]["attn_frac_of_measured_mfma"] = flops / (ms_attn * 1e-3) / 1e12 / extra["measured_ceilings"]["mfma_bf16_TFLOPs"]
+        extra["measured_ceilings"]["condense_call_frac_of_measured_read"] = (
+            cbytes / (ms_cond * 1e-3) / 1e12 / extra["measured_ceilings"]["hbm_read_TBps"])
         # in-run dense MLA baseline (same kernel engine, plain causal mask)
         O2 = torch.empty_like(O)
         n_dense = 2 if wl.L > 65536 else 5

@@ -268,6 +268,35 @@ lca_status lca_decode_attn_q8(const lca_desc *desc, const lca_cache_layout *layo
                               const uint8_t *sel_q8, const float *scales, const void *pool_tail, const void *sel_tail,
                               void *O, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Measurement aids, not steps of the method: what the device sustains at the two operations the roofline fractions
+ * of the kernels above are read against (the measured-ceiling lines asked for beside the published peaks).  Time
+ * them from outside, with events on the stream they are given.
+ *
+ * lca_probe_hbm_read streams `bytes` bytes (a positive multiple of 16, buf 16-byte aligned, device memory) once, with
+ * the launch shape that read fastest on gfx950, and leaves in wg_sums (device, LCA_PROBE_WORDS words) per-workgroup
+ * sums of the 32-bit words read: their total modulo 2^32 is the sum of all words of the buffer; unused entries are 0.
+ *
+ * lca_probe_mfma_bf16 runs, on every SIMD of the device, iters (1 .. 65536) rounds of four independent
+ * 32x32x16 bf16 matrix-core products with fp32 accumulation: chain c (0..3) accumulates D_c += A_c B_c, A_c 32 x 16,
+ * B_c 16 x 32, constant over the rounds.
+ *   pattern 0: A_c[i][k] = (5 i + 3 c) mod 7 - 2, B_c[k][j] = (3 j + 5 c + 1) mod 7 - 2: every output element is the
+ *              integer 16 iters A_c[i][0] B_c[0][j], exact in fp32.
+ *   pattern 1: operands with all mantissa bits in use and mixed signs, as a real kernel's (the clock the device
+ *              settles at under matrix-core load depends on how many operand bits toggle): element (x, k) of operand
+ *              o (0 = A with x = i, 1 = B with x = j) of chain c has the bf16 bit pattern
+ *              sign(h >> 31) | exponent 126 + ((h >> 8) & 1) | mantissa h & 127, where h = mix(((o 4 + c) 32 + x) 16 + k + 1),
+ *              mix(x): x *= 2654435761; x ^= x >> 15; x *= 2246822519; x ^= x >> 13 (32-bit unsigned arithmetic).
+ * *wavefronts (host) receives the number of wavefronts that ran; flops = wavefronts * iters * 4 * 32768.
+ * out (device, LCA_PROBE_MFMA_FLOATS floats, the first wavefronts * 256 written): out[(64 v + l) * 4 + c] = the sum of
+ * the 16 elements of D_c that lane l of wavefront v holds -- rows of column l mod 32, lanes l and l + 32 together the
+ * whole column -- so out[(64 v + l) * 4 + c] + out[(64 v + l + 32) * 4 + c] = sum_i D_c[i][l] for l < 32.
+ */
+#define LCA_PROBE_WORDS 256
+#define LCA_PROBE_MFMA_FLOATS (256 * 256 * 4)
+lca_status lca_probe_hbm_read(const void *buf, size_t bytes, uint32_t *wg_sums, void *stream);
+lca_status lca_probe_mfma_bf16(int32_t iters, int32_t pattern, float *out, int32_t *wavefronts, void *stream);
+
 /* Message for the calling thread's last non-OK status; never NULL. */
 const char *lca_last_error(void);
 

@@ -135,6 +135,25 @@ lca_status static_scratch(void **out)
 
 extern "C" {
 
+lca_status lca_probe_hbm_read(const void *buf, size_t bytes, uint32_t *wg_sums, void *stream)
+{
+    LCA_TRY(check_ptr(buf, "buf"));
+    if (wg_sums == nullptr) return fail(LCA_ERR_INVALID_ARG, "wg_sums is NULL");
+    if (bytes == 0 || bytes % 16 != 0) return fail(LCA_ERR_INVALID_ARG, "bytes (%zu) must be a positive multiple of 16", bytes);
+    return hip_status(lca::launch_probe_hbm_read(buf, bytes, wg_sums, static_cast<hipStream_t>(stream)), "lca_probe_hbm_read");
+}
+
+lca_status lca_probe_mfma_bf16(int32_t iters, int32_t pattern, float *out, int32_t *wavefronts, void *stream)
+{
+    if (out == nullptr || wavefronts == nullptr) return fail(LCA_ERR_INVALID_ARG, "output pointer is NULL");
+    if (iters < 1 || iters > 65536) return fail(LCA_ERR_INVALID_ARG, "iters (%d) must be in [1, 65536]", iters);
+    if (pattern != 0 && pattern != 1) return fail(LCA_ERR_INVALID_ARG, "pattern (%d) must be 0 or 1", pattern);
+    int waves = 0;
+    const hipError_t e = lca::launch_probe_mfma_bf16(iters, pattern, out, &waves, static_cast<hipStream_t>(stream));
+    *wavefronts = waves;
+    return hip_status(e, "lca_probe_mfma_bf16");
+}
+
 const char *lca_last_error(void) { return g_err; }
 
 lca_status lca_workspace_size(const lca_desc *desc, size_t *bytes)

@@ -71,6 +71,10 @@ int persistent_grid();
 // Launchers return hipSuccess or the launch error. They assume validated arguments.
 hipError_t launch_condense(const CondenseArgs &a, hipStream_t st);
 hipError_t launch_summary_query(const Dims &d, const void *Q, int L, float *qbar, hipStream_t st);
+// measurement aids (probes.hip)
+hipError_t launch_probe_hbm_read(const void *buf, size_t bytes, uint32_t *wg_sums, hipStream_t st);
+hipError_t launch_probe_mfma_bf16(int iters, int pattern, float *out, int *wavefronts, hipStream_t st);
+
 bool condense_mla_mfma_supported(const Dims &d);
 hipError_t launch_condense_mla_mfma(const CondenseArgs &a, hipStream_t st);
 hipError_t launch_attn_simple(const AttnArgs &a, hipStream_t st);

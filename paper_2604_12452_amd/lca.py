@@ -21,7 +21,9 @@ REDUCE_DEFAULT, REDUCE_WEIGHTED, REDUCE_MEAN, REDUCE_MAXSEL, REDUCE_MAXPOOL = ra
 
 EXPORTS = ("lca_workspace_size", "lca_cache_bytes", "lca_condensed_rows", "lca_condense", "lca_condense_noalloc", "lca_prefill_attn", "dense_mla_attn",
            "lca_decode_attn", "lca_decode_attn_cached", "lca_cache_update", "lca_deviation_stats", "lca_quantize_cache",
-           "lca_decode_attn_q8", "lca_prefill_attn_up", "lca_last_error")
+           "lca_decode_attn_q8", "lca_prefill_attn_up", "lca_probe_hbm_read", "lca_probe_mfma_bf16", "lca_last_error")
+PROBE_WORDS = 256                     # LCA_PROBE_WORDS
+PROBE_MFMA_FLOATS = 256 * 256 * 4     # LCA_PROBE_MFMA_FLOATS
 
 
 class LcaError(RuntimeError):
@@ -349,3 +351,20 @@ def alloc_condensed(desc: Desc, device="cuda", alpha: bool = False):
     anchor = torch.empty((desc.B, desc.S, m), dtype=torch.int32, device=device)
     a = torch.empty((desc.B, desc.S, m * desc.g), dtype=torch.float32, device=device) if alpha else None
     return pool_rep, sel_rep, anchor, a
+
+
+def probe_hbm_read(buf, wg_sums, stream=None):
+    """Stream `buf` out of HBM once (measurement aid); `wg_sums` (PROBE_WORDS int32 / uint32) receives per-workgroup word sums."""
+    if _nbytes(wg_sums) < PROBE_WORDS * 4 or wg_sums.element_size() != 4:
+        raise ValueError(f"wg_sums must hold {PROBE_WORDS} 32-bit words")
+    _check(load().lca_probe_hbm_read(_ptr(buf), ctypes.c_size_t(_nbytes(buf)), _ptr(wg_sums), _stream(stream)))
+
+
+def probe_mfma_bf16(iters: int, out, pattern: int = 0, stream=None) -> int:
+    """Back-to-back bf16 matrix-core products on every SIMD (measurement aid; pattern 0: small integers with a closed form,
+    1: hashed full-mantissa operands); returns the number of wavefronts that ran."""
+    if _nbytes(out) < PROBE_MFMA_FLOATS * 4 or str(out.dtype) != "torch.float32":
+        raise ValueError(f"out must hold {PROBE_MFMA_FLOATS} float32")
+    waves = ctypes.c_int32(0)
+    _check(load().lca_probe_mfma_bf16(ctypes.c_int32(iters), ctypes.c_int32(pattern), _ptr(out), ctypes.byref(waves), _stream(stream)))
+    return int(waves.value)

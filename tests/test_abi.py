@@ -27,7 +27,7 @@ def _declared():
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared()
-    assert set(names) == set(lca.EXPORTS) and len(names) == 15
+    assert set(names) == set(lca.EXPORTS) and len(names) == 17
     for n in names:
         assert hasattr(lib, n)
 
@@ -143,6 +143,25 @@ def test_null_misaligned_and_small_workspace_are_rejected_before_launch(lib):
     und = lca.Desc(B=1, L=100, H=3, S=1, d_pool=64, d_sel=64, g=4, w=4).c()    # no decode kernel for this shape
     assert lib.lca_decode_attn(ctypes.byref(und), vp(A), vp(A), vp(A), vp(A), vp(A), vp(A), vp(A), sz(1 << 20), vp(0)) == lca.ERR_UNSUPPORTED
     assert lib.lca_workspace_size(None, None) == lca.ERR_INVALID_ARG
+
+
+def test_probes_reject_bad_arguments_before_launch(lib):
+    import ctypes
+    words = (ctypes.c_uint32 * 4)()
+    waves = ctypes.c_int32(-1)
+    fake = ctypes.c_void_p(4096)                                       # never dereferenced: every call below is rejected on the host
+    assert lib.lca_probe_hbm_read(None, ctypes.c_size_t(1024), fake, None) == lca.ERR_INVALID_ARG
+    assert lib.lca_probe_hbm_read(fake, ctypes.c_size_t(1024), None, None) == lca.ERR_INVALID_ARG
+    assert lib.lca_probe_hbm_read(fake, ctypes.c_size_t(0), fake, None) == lca.ERR_INVALID_ARG
+    assert lib.lca_probe_hbm_read(fake, ctypes.c_size_t(1000), fake, None) == lca.ERR_INVALID_ARG
+    assert b"multiple of 16" in lib.lca_last_error()
+    assert lib.lca_probe_hbm_read(ctypes.c_void_p(4100), ctypes.c_size_t(1024), fake, None) == lca.ERR_INVALID_ARG   # misaligned
+    assert lib.lca_probe_mfma_bf16(ctypes.c_int32(0), ctypes.c_int32(0), fake, ctypes.byref(waves), None) == lca.ERR_INVALID_ARG
+    assert lib.lca_probe_mfma_bf16(ctypes.c_int32(65537), ctypes.c_int32(0), fake, ctypes.byref(waves), None) == lca.ERR_INVALID_ARG
+    assert lib.lca_probe_mfma_bf16(ctypes.c_int32(10), ctypes.c_int32(0), None, ctypes.byref(waves), None) == lca.ERR_INVALID_ARG
+    assert lib.lca_probe_mfma_bf16(ctypes.c_int32(10), ctypes.c_int32(1), fake, None, None) == lca.ERR_INVALID_ARG
+    assert lib.lca_probe_mfma_bf16(ctypes.c_int32(10), ctypes.c_int32(2), fake, ctypes.byref(waves), None) == lca.ERR_INVALID_ARG
+    assert waves.value == -1 and list(words) == [0, 0, 0, 0]
 
 
 def test_header_is_plain_c(tmp_path):
