@@ -74,6 +74,8 @@ def test_cfg1_tiny_fp32_all_rows(oracle, S):
     (1, 1, 0, 1, 1, 1),           # a single token
     (7, 2, 1, 3, 3, 2),           # fewer rows than a tile, two sequences: segments of a few rows behind one another
     (40, 4, 4, 4, 2, 3),          # three sequences back to back: nothing may leak across a sequence's end
+    (200, 16, 48, 128, 1, 1),     # 128 heads over one set: more work items per query block than workgroup slots of an XCD
+    (140, 8, 20, 48, 16, 2),      # 48 heads in 16 sets of three
 ])
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 def test_mla_mfma_small_all_rows(oracle, L, g, w, H, S, B, dtype):
