@@ -288,6 +288,56 @@ def sweep_bench(wl, args, lca, hp, torch, inputs, tdt):
     return rows
 
 
+def length_bench(wl0, lengths, args, lca, hp, torch, inputs, tdt):
+    """The hot path over the sequence length at the workload's other shapes -- the paper's efficiency analysis (section 5.3: the
+    kernel's latency against the dense baseline as the context grows, up to a million tokens).  Per length: fresh seeded inputs of
+    the same recipe, condensation and attention timed, the dense baseline timed where a launch stays under a second (L <= 128K;
+    beyond that the ratio of visible pairs, which is what the speed-up tends to at equal efficiency), the emitted cache's bytes,
+    and 32 evenly spaced rows x all heads compared with the oracle."""
+    out = []
+    for L in lengths:
+        wl = wl0.with_(L=L, name=f"{wl0.name.split('+')[0]}+L={L}")
+        Q, POOL, SEL = inputs.gen_all(wl)
+        run = hp.GpuRun(wl, Q, POOL, SEL)
+        d = run.desc
+        run.pool_rep, run.sel_rep, run.anchor, _ = lca.alloc_condensed(d)
+        O = torch.empty((d.B, d.L, d.H, d.d_pool), dtype=tdt, device="cuda")
+
+        def f_cond():
+            lca.condense(d, run.Q, run.POOL, run.SEL, run.pool_rep, run.sel_rep, run.anchor, None, run.ws)
+
+        def f_attn():
+            lca.prefill_attn(d, run.Q, run.POOL, run.SEL, run.pool_rep, run.sel_rep, O, None, run.ws)
+
+        f_cond()
+        pairs, pairs_dense = pair_count(wl.L, wl.w, wl.g), wl.L * (wl.L + 1) // 2
+        flops = 2.0 * (wl.d_qk + wl.d_v) * wl.B * wl.H * pairs
+        n_attn = max(2, min(args.steps, int(400e-3 / (flops / 1.2e15))))          # about 0.4 s of attention per length
+        ma = time_kernel(f_attn, n_attn, 1)
+        mc = time_kernel(f_cond, 10, 2, behind=f_attn)
+        row = {"L": L, "m": d.m, "ms_condense": mc, "ms_attn": ma, "tokens_per_s": wl.B * wl.L / ((mc + ma) * 1e-3),
+               "attn_TFLOPs": flops / (ma * 1e-3) / 1e12, "attn_frac_of_mfma_peak": flops / (ma * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+               "dense_over_lca_visible_pairs": pairs_dense / pairs}
+        db, cb = lca.cache_bytes(d)
+        row["kv_cache_bytes_dense"], row["kv_cache_bytes_lca"], row["kv_cache_saved_frac"] = db, cb, 1.0 - cb / db
+        _, rows, O_ref, near_ties = cpu_baseline(wl, Q, POOL, SEL, 32, run.anchor.cpu().numpy(), hp.from_dev(run.sel_rep, wl.dtype))
+        O_gpu = hp.from_dev(O[:, rows.tolist()], wl.dtype)
+        num = np.abs(O_gpu - O_ref).max(axis=-1)
+        row["parity_max_rel_err_sampled_rows"] = float((num / np.maximum(np.abs(O_ref).max(axis=-1), 1e-6)).max())
+        row["parity_anchor_near_ties"] = near_ties
+        if L <= 131072:
+            md = time_kernel(lambda: lca.dense_attn(d, run.Q, run.POOL, run.SEL, O, None, run.ws), 2 if L > 32768 else 5, 1)
+            row["ms_dense_mla_attn"], row["speedup_vs_dense_mla"] = md, md / (mc + ma)
+        else:
+            row["ms_dense_mla_attn"], row["speedup_vs_dense_mla"] = None, None
+        print(f"[lengths] L={L}: attention {ma:.3f} ms, condensation {mc * 1e3:.1f} us, parity {row['parity_max_rel_err_sampled_rows']:.2e}",
+              file=sys.stderr, flush=True)
+        out.append(row)
+        del run, O, Q, POOL, SEL, O_gpu, O_ref
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -304,6 +354,8 @@ def main():
                          "--set H=28 --set S=4 --set L=131072 for the head layout of the GQA model the paper reports on")
     ap.add_argument("--sweep", action="store_true",
                     help="time the prefill over group sizes, windows, numbers of summary queries and pooling strategies instead")
+    ap.add_argument("--lengths", default=None, metavar="L1,L2,...",
+                    help="time the hot path at these sequence lengths (the workload's other shapes kept) instead of the default run")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size kernel the HBM counters are scaled by")
     args = ap.parse_args()
@@ -342,6 +394,14 @@ def main():
     if args.sweep:
         print(json.dumps({"metric": f"LCA prefill over the method's settings ({wl.name} shapes)", "unit": "tokens/s", "n_gpus": 1,
                           "steps": args.steps, "dtype": args.dtype, "data": "synthetic", "sweep": sweep_bench(wl, args, lca, hp, torch, inputs, tdt)}))
+        return
+    if args.lengths:
+        res = length_bench(wl, [int(x) for x in args.lengths.split(",")], args, lca, hp, torch, inputs, tdt)
+        tol = 1e-2 if args.dtype == "bf16" else 2e-3
+        print(json.dumps({"metric": f"LCA prefill over the sequence length ({wl.name} shapes)", "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+                          "dtype": args.dtype, "data": "synthetic", "lengths": res}))
+        if not all(r["parity_max_rel_err_sampled_rows"] <= tol for r in res):
+            sys.exit("bench.py: sampled rows differ from the oracle by more than the tolerance")
         return
     t_gen = time.perf_counter()
     Q, POOL, SEL = inputs.gen_all(wl)
