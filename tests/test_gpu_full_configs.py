@@ -129,3 +129,11 @@ def test_cfg5_gqa_64k_prefill_and_decode(oracle):
         assert not (differ & (rc["margin"][0] > hp.ANCHOR_MARGIN)).any()
         assert hp.vec_rel_err(hp.from_dev(pool_rep[b], "bf16"), rc["pool_rep"][0]) <= hp.TOL["bf16"]
     assert bool(O.isfinite().all())
+
+
+def test_mla_prefill_at_the_longest_supported_sequence(oracle):
+    """2^21 tokens, the longest sequence the matrix-core kernels take: their 32-bit byte offsets into the token rows reach 2^31
+    there.  One head keeps the queries and outputs at 4.5 GB; the cache side -- 131 008 representatives behind a 1 024-token
+    window, 2.4 GB of raw rows -- is at its full size, and the sampled rows include the first and the last of the sequence."""
+    wl = inputs.Workload("mla_2m", B=1, L=1 << 21, H=1, S=1, d_pool=512, d_sel=64, g=16, w=1024, dtype="bf16", seed=2021)
+    _sampled_parity(oracle, wl, 24)
