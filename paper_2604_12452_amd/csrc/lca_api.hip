@@ -1,5 +1,6 @@
 // C ABI of liblca: argument validation, workspace carving and kernel dispatch.  No allocation, no
-// synchronisation, no state beyond the thread-local error string.
+// synchronisation, no state beyond the thread-local error string, the device array of lca_condense_noalloc
+// and its per-device address.
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -96,13 +97,18 @@ lca_status hip_status(hipError_t e, const char *what)
     return fail(LCA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// The launch functions report hipGetLastError() after their kernels, and that call returns the calling thread's last
+// error whoever caused it: one left behind by an earlier runtime call of the caller's own would be taken for a failed
+// launch.  So the thread's error state is read, and thereby cleared, right before a launch function runs.
+#define LCA_LAUNCH(call, what) ((void)hipGetLastError(), hip_status((call), (what)))
+
 // The two matrix-core kernels take their widths in a 16-bit type with a positive scale (their fixed-reference softmax
 // orders logits by the raw products); every other descriptor, a zero or negative scale included, runs the general kernel.
 lca_status run_attn(const lca::AttnArgs &a, hipStream_t st, const char *what)
 {
-    if (lca::attn_mla_supported(a.d)) return hip_status(lca::launch_attn_mla(a, st), what);
-    if (lca::attn_gqa64_supported(a.d)) return hip_status(lca::launch_attn_gqa64(a, st), what);
-    return hip_status(lca::launch_attn_simple(a, st), what);
+    if (lca::attn_mla_supported(a.d)) return LCA_LAUNCH(lca::launch_attn_mla(a, st), what);
+    if (lca::attn_gqa64_supported(a.d)) return LCA_LAUNCH(lca::launch_attn_gqa64(a, st), what);
+    return LCA_LAUNCH(lca::launch_attn_simple(a, st), what);
 }
 
 // ---- lca_condense_noalloc: the summary query lives in a device array of the library's own ----
@@ -140,7 +146,7 @@ lca_status lca_probe_hbm_read(const void *buf, size_t bytes, uint32_t *wg_sums, 
     LCA_TRY(check_ptr(buf, "buf"));
     if (wg_sums == nullptr) return fail(LCA_ERR_INVALID_ARG, "wg_sums is NULL");
     if (bytes == 0 || bytes % 16 != 0) return fail(LCA_ERR_INVALID_ARG, "bytes (%zu) must be a positive multiple of 16", bytes);
-    return hip_status(lca::launch_probe_hbm_read(buf, bytes, wg_sums, static_cast<hipStream_t>(stream)), "lca_probe_hbm_read");
+    return LCA_LAUNCH(lca::launch_probe_hbm_read(buf, bytes, wg_sums, static_cast<hipStream_t>(stream)), "lca_probe_hbm_read");
 }
 
 lca_status lca_probe_mfma_bf16(int32_t iters, int32_t pattern, float *out, int32_t *wavefronts, void *stream)
@@ -149,6 +155,7 @@ lca_status lca_probe_mfma_bf16(int32_t iters, int32_t pattern, float *out, int32
     if (iters < 1 || iters > 65536) return fail(LCA_ERR_INVALID_ARG, "iters (%d) must be in [1, 65536]", iters);
     if (pattern != 0 && pattern != 1) return fail(LCA_ERR_INVALID_ARG, "pattern (%d) must be 0 or 1", pattern);
     int waves = 0;
+    (void)hipGetLastError();       // (see LCA_LAUNCH)
     const hipError_t e = lca::launch_probe_mfma_bf16(iters, pattern, out, &waves, static_cast<hipStream_t>(stream));
     *wavefronts = waves;
     return hip_status(e, "lca_probe_mfma_bf16");
@@ -202,7 +209,7 @@ lca_status lca_condense(const lca_desc *desc, const void *Q, const void *POOL, c
     lca::CondenseArgs a;
     a.d = d; a.Q = Q; a.POOL = POOL; a.SEL = SEL; a.pool_rep = pool_rep; a.sel_rep = sel_rep;
     a.anchor = anchor_idx; a.alpha_dbg = alpha_dbg; a.qbar = static_cast<float *>(workspace);
-    return hip_status(lca::launch_condense(a, static_cast<hipStream_t>(stream)), "lca_condense");
+    return LCA_LAUNCH(lca::launch_condense(a, static_cast<hipStream_t>(stream)), "lca_condense");
 }
 
 lca_status lca_condense_noalloc(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL, void *pool_rep, void *sel_rep,
@@ -226,7 +233,7 @@ lca_status lca_condense_noalloc(const lca_desc *desc, const void *Q, const void 
     a.d = d; a.Q = Q; a.POOL = POOL; a.SEL = SEL; a.pool_rep = pool_rep; a.sel_rep = sel_rep;
     a.anchor = anchor_idx; a.alpha_dbg = alpha_dbg; a.qbar = static_cast<float *>(qbar);
     // (nothing in the scratch has to start at zero: the first kernel writes every summary query before the second reads it)
-    return hip_status(lca::launch_condense(a, static_cast<hipStream_t>(stream)), "lca_condense_noalloc");
+    return LCA_LAUNCH(lca::launch_condense(a, static_cast<hipStream_t>(stream)), "lca_condense_noalloc");
 }
 
 lca_status lca_prefill_attn(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL, const void *pool_rep,
@@ -266,7 +273,7 @@ lca_status lca_prefill_attn_up(const lca_desc *desc, const void *Q, const void *
     a.d = d; a.Q = Q; a.POOL = POOL; a.SEL = SEL; a.pool_rep = pool_rep; a.sel_rep = sel_rep; a.O = O_up; a.lse = lse; a.dense = 0;
     a.W_up = W_up;
     a.up_scratch = workspace;
-    return hip_status(lca::launch_attn_mla(a, static_cast<hipStream_t>(stream)), "lca_prefill_attn_up");
+    return LCA_LAUNCH(lca::launch_attn_mla(a, static_cast<hipStream_t>(stream)), "lca_prefill_attn_up");
 }
 
 lca_status dense_mla_attn(const lca_desc *desc, const void *Q, const void *POOL, const void *SEL, void *O, float *lse,
@@ -318,7 +325,7 @@ static lca_status decode_common(const lca_desc *desc, const lca_cache_layout *la
     a.m_cap = layout ? layout->m_cap : d.m;
     a.k_cap = layout ? layout->k_cap : d.k;
     a.k_start = layout ? layout->k_start : 0;
-    return hip_status(lca::launch_decode(a, static_cast<hipStream_t>(stream)), what);
+    return LCA_LAUNCH(lca::launch_decode(a, static_cast<hipStream_t>(stream)), what);
 }
 
 lca_status lca_decode_attn(const lca_desc *desc, const void *q, const void *pool_rep, const void *sel_rep, const void *pool_tail,
@@ -357,7 +364,7 @@ lca_status lca_cache_update(const lca_desc *desc, const lca_cache_layout *layout
     a.qbar = static_cast<float *>(workspace);
     a.d = d; a.q_recent = q_recent; a.pool_tail = pool_tail; a.sel_tail = sel_tail; a.pool_rep = pool_rep; a.sel_rep = sel_rep;
     a.anchor = anchor_idx; a.m_cap = layout->m_cap; a.k_cap = layout->k_cap; a.k_start = layout->k_start;
-    return hip_status(lca::launch_cache_update(a, static_cast<hipStream_t>(stream)), "lca_cache_update");
+    return LCA_LAUNCH(lca::launch_cache_update(a, static_cast<hipStream_t>(stream)), "lca_cache_update");
 }
 
 lca_status lca_quantize_cache(const lca_desc *desc, const lca_cache_layout *layout, int32_t first_row, const void *pool_rep, const void *sel_rep,
@@ -378,7 +385,7 @@ lca_status lca_quantize_cache(const lca_desc *desc, const lca_cache_layout *layo
     a.d = d; a.pool_rep = pool_rep; a.sel_rep = sel_rep; a.pool_q8 = pool_q8; a.sel_q8 = sel_q8; a.scales = scales;
     a.m_cap = layout ? layout->m_cap : d.m;
     a.first_row = first_row;
-    return hip_status(lca::launch_quantize_cache(a, static_cast<hipStream_t>(stream)), "lca_quantize_cache");
+    return LCA_LAUNCH(lca::launch_quantize_cache(a, static_cast<hipStream_t>(stream)), "lca_quantize_cache");
 }
 
 lca_status lca_decode_attn_q8(const lca_desc *desc, const lca_cache_layout *layout, const void *q, const uint8_t *pool_q8, const uint8_t *sel_q8,
@@ -409,7 +416,7 @@ lca_status lca_decode_attn_q8(const lca_desc *desc, const lca_cache_layout *layo
     a.k_start = layout ? layout->k_start : 0;
     // (with m = 0 there are no representatives: the kernel for the 16-bit cache reads the tail alone)
     if (d.m == 0) { a.pool_q8 = nullptr; a.sel_q8 = nullptr; a.scales = nullptr; }
-    return hip_status(lca::launch_decode(a, static_cast<hipStream_t>(stream)), "lca_decode_attn_q8");
+    return LCA_LAUNCH(lca::launch_decode(a, static_cast<hipStream_t>(stream)), "lca_decode_attn_q8");
 }
 
 lca_status lca_deviation_stats(const lca_desc *desc, const void *POOL, const void *SEL, const void *pool_rep, const void *sel_rep, float *stats,
@@ -426,7 +433,7 @@ lca_status lca_deviation_stats(const lca_desc *desc, const void *POOL, const voi
     lca::DeviationArgs a;
     a.d = d; a.POOL = POOL; a.SEL = SEL; a.pool_rep = pool_rep; a.sel_rep = sel_rep; a.stats = stats;
     a.partial = static_cast<float *>(workspace);
-    return hip_status(lca::launch_deviation_stats(a, static_cast<hipStream_t>(stream)), "lca_deviation_stats");
+    return LCA_LAUNCH(lca::launch_deviation_stats(a, static_cast<hipStream_t>(stream)), "lca_deviation_stats");
 }
 
 }  // extern "C"

@@ -104,6 +104,14 @@ def load() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_12452_amd.build`; "
                                     "there is no fallback path")
+        # PyTorch brings a HIP runtime of its own, with the system runtime's soname.  Opened after torch, this library is served
+        # by torch's copy; opened before it, the library maps the system's copy and torch still maps its own afterwards: two
+        # runtimes in one process, and the one that initialises second finds no device (every launch then fails with
+        # "no ROCm-capable device is detected").  The tensors this binding takes are torch's, so torch goes first.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = ctypes.CDLL(LIB_PATH)
         for name in EXPORTS:
             getattr(lib, name).restype = ctypes.c_int

@@ -137,3 +137,16 @@ def test_mla_prefill_at_the_longest_supported_sequence(oracle):
     window, 2.4 GB of raw rows -- is at its full size, and the sampled rows include the first and the last of the sequence."""
     wl = inputs.Workload("mla_2m", B=1, L=1 << 21, H=1, S=1, d_pool=512, d_sel=64, g=16, w=1024, dtype="bf16", seed=2021)
     _sampled_parity(oracle, wl, 24)
+
+
+def test_gqa_prefill_at_the_longest_supported_sequence(oracle):
+    """The GQA widths with 8 KV heads at the longest sequence the matrix-core kernel takes there: a token's row of 8 keys is
+    2 KB, and (L + 4 tiles) rows of them must stay below 2^32 bytes.  One query head per KV head; the cache side is at its full
+    size (130 976 representatives per KV head behind the window)."""
+    L = (1 << 21) - 512
+    wl = inputs.Workload("gqa_2m", B=1, L=L, H=8, S=8, d_pool=128, d_sel=128, g=16, w=1024, dtype="bf16", mode=inputs.MODE_GQA, seed=2022,
+                         theta=5e5)
+    from paper_2604_12452_amd import lca
+    from paper_2604_12452_amd import device
+    assert lca.condensed_rows(device.lca_desc(wl)) == ((L - 1024) // 16, L - ((L - 1024) // 16) * 16)
+    _sampled_parity(oracle, wl, 24)

@@ -90,3 +90,44 @@ def test_probe_buffers_are_checked_by_the_binding():
         lca.probe_mfma_bf16(10, torch.zeros(1024, dtype=torch.float32, device="cuda"))
     with pytest.raises(ValueError):
         lca.probe_hbm_read(torch.zeros(64, dtype=torch.int32), torch.zeros(lca.PROBE_WORDS, dtype=torch.int32, device="cuda"))
+
+
+
+def test_library_opened_before_torch_is_imported_still_finds_the_device():
+    """The binding opened first in a fresh process, torch only afterwards: both must end up on one HIP runtime (two runtimes
+    in one process leave the second without a device, and every launch of the library then fails)."""
+    import os
+    import subprocess
+    import sys
+    code = (
+        "import sys\n"
+        "from paper_2604_12452_amd import lca\n"
+        "lca.load()\n"
+        "import torch\n"
+        "buf = torch.arange(4096, dtype=torch.int32, device='cuda')\n"
+        "sums = torch.zeros(lca.PROBE_WORDS, dtype=torch.int32, device='cuda')\n"
+        "lca.probe_hbm_read(buf, sums)\n"
+        "torch.cuda.synchronize()\n"
+        "assert int(sums.sum()) == 4095 * 4096 // 2\n"
+        "print('ok')\n")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
+
+
+def test_an_error_left_by_the_caller_is_not_taken_for_a_failed_launch():
+    """hipGetLastError() after a launch returns the thread's last error whoever caused it: the library reads (clears) the
+    state before it launches, so an earlier failed runtime call of the caller's does not fail the library's call."""
+    import ctypes
+    import torch
+    buf = torch.arange(4096, dtype=torch.int32, device="cuda")
+    sums = torch.zeros(lca.PROBE_WORDS, dtype=torch.int32, device="cuda")
+    lca.load()
+    hip = ctypes.CDLL("libamdhip64.so.7")            # by soname: the runtime already in the process
+    assert hip.hipSetDevice(12345) != 0              # rejected on the host (no such ordinal); the current device stays, the error is recorded
+    assert hip.hipPeekAtLastError() != 0             # ... and is still there (peeking does not clear it)
+    lca.probe_hbm_read(buf, sums)
+    torch.cuda.synchronize()
+    assert int(sums.sum()) == 4095 * 4096 // 2
+    assert hip.hipPeekAtLastError() == 0
+
