@@ -11,9 +11,9 @@ from tests import helpers as hp
 pytestmark = pytest.mark.gpu
 
 
-def _sampled_parity(oracle, wl, n_rows, dense_rows=0):
+def _sampled_parity(oracle, wl, n_rows, dense_rows=0, arrays=None):
     print(f"[case] {wl}", flush=True)
-    Q, POOL, SEL = inputs.gen_all(wl)
+    Q, POOL, SEL = inputs.gen_all(wl) if arrays is None else arrays
     POOLf, SELf = inputs.to_f64(POOL, wl.dtype), inputs.to_f64(SEL, wl.dtype)
     run = hp.GpuRun(wl, Q, POOL, SEL).condense(alpha=False)
     ref, differ = hp.check_condense(oracle, wl, run, inputs.to_f64(Q[:, wl.L - wl.nq:], wl.dtype), POOLf, SELf)
@@ -142,11 +142,17 @@ def test_mla_prefill_at_the_longest_supported_sequence(oracle):
 def test_gqa_prefill_at_the_longest_supported_sequence(oracle):
     """The GQA widths with 8 KV heads at the longest sequence the matrix-core kernel takes there: a token's row of 8 keys is
     2 KB, and (L + 4 tiles) rows of them must stay below 2^32 bytes.  One query head per KV head; the cache side is at its full
-    size (130 976 representatives per KV head behind the window)."""
+    size (130 976 representatives per KV head behind the window); condensation is compared in full, attention on sampled rows."""
     L = (1 << 21) - 512
     wl = inputs.Workload("gqa_2m", B=1, L=L, H=8, S=8, d_pool=128, d_sel=128, g=16, w=1024, dtype="bf16", mode=inputs.MODE_GQA, seed=2022,
                          theta=5e5)
     from paper_2604_12452_amd import lca
     from paper_2604_12452_amd import device
     assert lca.condensed_rows(device.lca_desc(wl)) == ((L - 1024) // 16, L - ((L - 1024) // 16) * 16)
-    _sampled_parity(oracle, wl, 24)
+    # 13 GB of inputs: a seeded block of 60 001 tokens repeated along the sequence (a period that divides no power of two, so
+    # an offset that wrapped around would land on other data) -- drawing 2 M tokens x 8 heads afresh takes minutes
+    P = 60001
+    blk = inputs.gen_all(wl.with_(L=P))
+    reps = -(-L // P)
+    arrays = tuple(np.ascontiguousarray(np.tile(a, (1, reps) + (1,) * (a.ndim - 2))[:, :L]) for a in blk)
+    _sampled_parity(oracle, wl, 24, arrays=arrays)
