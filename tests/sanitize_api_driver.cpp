@@ -107,6 +107,19 @@ int main()
     odd_widths.d_pool = 64; odd_widths.d_sel = 64;
     EXPECT(lca_decode_attn(&odd_widths, A, A, A, A, A, A, A, size_t(1) << 20, nullptr) == LCA_ERR_UNSUPPORTED);
     EXPECT(lca_prefill_attn_up(&odd_widths, A, A, A, A, A, A, A, nullptr, A, size_t(1) << 20, nullptr) == LCA_ERR_UNSUPPORTED);
+    // the measurement aids
+    int32_t waves = -7;
+    EXPECT(lca_probe_hbm_read(nullptr, 1024, static_cast<uint32_t *>(A), nullptr) == LCA_ERR_INVALID_ARG);
+    EXPECT(lca_probe_hbm_read(A, 1024, nullptr, nullptr) == LCA_ERR_INVALID_ARG);
+    EXPECT(lca_probe_hbm_read(A, 0, static_cast<uint32_t *>(A), nullptr) == LCA_ERR_INVALID_ARG);
+    EXPECT(lca_probe_hbm_read(A, 1000, static_cast<uint32_t *>(A), nullptr) == LCA_ERR_INVALID_ARG);
+    EXPECT(lca_probe_hbm_read(odd, 1024, static_cast<uint32_t *>(A), nullptr) == LCA_ERR_INVALID_ARG);
+    EXPECT(lca_probe_mfma_bf16(0, 0, static_cast<float *>(A), &waves, nullptr) == LCA_ERR_INVALID_ARG);
+    EXPECT(lca_probe_mfma_bf16(65537, 1, static_cast<float *>(A), &waves, nullptr) == LCA_ERR_INVALID_ARG);
+    EXPECT(lca_probe_mfma_bf16(16, 2, static_cast<float *>(A), &waves, nullptr) == LCA_ERR_INVALID_ARG);
+    EXPECT(lca_probe_mfma_bf16(16, 0, nullptr, &waves, nullptr) == LCA_ERR_INVALID_ARG);
+    EXPECT(lca_probe_mfma_bf16(16, 0, static_cast<float *>(A), nullptr, nullptr) == LCA_ERR_INVALID_ARG);
+    EXPECT(waves == -7);
     std::printf("checks %d failed %d\n", n_checks, n_bad);
     return n_bad == 0 ? 0 : 1;
 }
