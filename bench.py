@@ -507,7 +507,7 @@ def main():
             # the same report on latents as redundant as the method assumes (section 4.1; the paper measures 2-5 % relative
             # deviations on model activations, appendix Tables 9-10): AR(1) with rho = 0.9999, everything else unchanged
             wr = wl.with_(rho=0.9999)
-            kv = [inputs.gen_kv(wr, b) for b in range(wr.B)]
+            kv = inputs.gen_kv_all(wr)
             keep = (run.POOL, run.SEL)
             run.POOL, run.SEL = hp.to_dev(np.stack([p for p, _ in kv]), wl.dtype), hp.to_dev(np.stack([s for _, s in kv]), wl.dtype)
             f_cond()

@@ -160,6 +160,13 @@ def gen_kv(wl: Workload, b: int):
     return to_storage(v, wl.dtype), to_storage(k, wl.dtype)
 
 
+def gen_kv_all(wl: Workload):
+    """gen_kv of every sequence, [(POOL_b, SEL_b)]: the sequences have random streams of their own, so they are drawn side by side
+    (the data does not depend on the order)."""
+    with ThreadPoolExecutor(max_workers=min(16, len(os.sched_getaffinity(0)), wl.B)) as ex:
+        return list(ex.map(lambda b: gen_kv(wl, b), range(wl.B)))
+
+
 def gen_q_rows(wl: Workload, b: int, t0: int, t1: int) -> np.ndarray:
     """Queries of tokens [t0, t1) of sequence b, storage form, [t1-t0, H, d_qk].
 
@@ -186,7 +193,7 @@ def gen_all(wl: Workload):
         parts = list(ex.map(lambda j: gen_q_rows(wl, *j), jobs))
     per_b = len(jobs) // wl.B
     Q = np.stack([np.concatenate(parts[b * per_b:(b + 1) * per_b], axis=0) for b in range(wl.B)])
-    kv = [gen_kv(wl, b) for b in range(wl.B)]
+    kv = gen_kv_all(wl)
     return Q, np.stack([p for p, _ in kv]), np.stack([s for _, s in kv])
 
 

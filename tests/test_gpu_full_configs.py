@@ -93,7 +93,7 @@ def test_cfg5_gqa_64k_prefill_and_decode(oracle):
     B = 32
     wd = wl.with_(B=B, L=wl.L + 1, seed=2005)
     print(f"[case] {wd}", flush=True)
-    kv = [inputs.gen_kv(wd, b) for b in range(B)]
+    kv = inputs.gen_kv_all(wd)
     V = np.stack([p for p, _ in kv]); K = np.stack([s for _, s in kv])
     q_last = np.stack([inputs.gen_q_rows(wd, b, wd.L - 1, wd.L)[0] for b in range(B)])           # [B, H, d]
     q_tail = np.stack([inputs.gen_q_rows(wd, b, wd.L - wd.nq, wd.L) for b in range(B)])         # [B, n_q, H, d]
